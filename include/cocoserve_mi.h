@@ -1,0 +1,194 @@
+/*
+ * cocoserve_mi.h - C ABI of the module-replica hot path for AMD Instinct MI355X (gfx950).
+ *
+ * The library implements the data-parallel core of CoCoServe's module scaling on ONE GPU:
+ *   - a *module* is a LLaMA-style decoder layer or a single projection (the paper's module
+ *     definition: Section 1, footnote on modules; Section 2.1 lists the projections);
+ *   - *replication* clones the module's weights and runs the unmodified module on contiguous
+ *     slices of the batch (15 requests -> 7 and 8), collecting the outputs in batch order
+ *     (Section 3.1 "Replication");
+ *   - *migration* copies a module to a new place and drops the old copy (Section 3.1
+ *     "Migration" and "Implementation").
+ * Replicas live in separate weight arenas of the same GPU's HBM and run on separate HIP
+ * streams; there is no second device and no collective.
+ *
+ * Conventions (all entry points)
+ *   - Every pointer argument says "host" or "device".  All device memory (weight arenas,
+ *     workspaces, activations, KV caches) and all streams are owned by the CALLER; the library
+ *     owns only the handle, its events and host-side metadata.
+ *   - Streams are passed as `void*` holding a `hipStream_t`.
+ *   - Calls enqueue work and return; ordering is by stream and event.  `ccs_module_sync`
+ *     waits for everything the module has enqueued.
+ *   - Every call returns a `ccs_status`; nothing throws across the ABI.  `ccs_last_error()`
+ *     returns a thread-local description of the last non-OK return on this thread.
+ *   - There is no CPU fallback: without a usable HIP device calls fail with CCS_EHIP.
+ *
+ * Data layouts
+ *   - Caller-side weights are row-major [out_features, in_features]; a forward computes
+ *     y = x W^T, no bias (Section 2.1: projections are linear maps).
+ *   - Activations x / y are row-major [rows, features] in the module's dtype.
+ *   - KV caches are [n_seqs, n_kv_heads, cache_cap, head_dim] in the module's dtype; keys are
+ *     stored after the rotary embedding.
+ *   - `ccs_module_create` re-packs the weights into the arena in the library's own streaming
+ *     order; a clone is one contiguous copy of `ccs_module_arena_bytes` bytes.
+ */
+#ifndef COCOSERVE_MI_H
+#define COCOSERVE_MI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ccs_module ccs_module; /* opaque, library-owned */
+
+typedef enum ccs_status {
+    CCS_OK = 0,
+    CCS_EINVAL = -1,       /* bad argument (null pointer, bad shape, lens out of range, ...) */
+    CCS_ESTATE = -2,       /* call not legal in the module's state (replica not instantiated) */
+    CCS_ENOMEM = -3,       /* a caller-provided buffer is too small / host allocation failed */
+    CCS_EUNSUPPORTED = -4, /* shape outside what the kernels support */
+    CCS_EHIP = -5          /* a HIP runtime call failed; message holds the HIP error string */
+} ccs_status;
+
+typedef enum ccs_kind { CCS_DECODER_LAYER = 0, CCS_LINEAR = 1 } ccs_kind;
+typedef enum ccs_dtype { CCS_F32 = 0, CCS_BF16 = 1 } ccs_dtype;
+typedef enum ccs_mode {
+    CCS_PREFILL = 0, /* whole prompts, causal, right padding masked (Section 2.1 "prefill") */
+    CCS_DECODE = 1,  /* one new token per sequence against the KV cache (Section 2.1 "decode") */
+    CCS_ROWS = 2     /* CCS_LINEAR modules: independent token rows */
+} ccs_mode;
+
+enum { CCS_MAX_REPLICAS = 16 };
+
+/* Shape of a module.  Decoder layer: hidden, heads, head_dim, intermediate (SwiGLU width),
+ * rms_eps, rope_base; requires n_q_heads % n_kv_heads == 0 and head_dim even.  The bf16 path
+ * additionally needs hidden, n_q_heads*head_dim and intermediate to be multiples of 32,
+ * n_kv_heads*head_dim a multiple of 16 and head_dim == 128 (else CCS_EUNSUPPORTED); the f32 path takes
+ * any shape with head_dim <= 256.  Linear: in_features, out_features (bf16: in % 32 == 0,
+ * out % 16 == 0). */
+typedef struct ccs_module_desc {
+    int32_t kind;  /* ccs_kind */
+    int32_t dtype; /* ccs_dtype: storage type of weights, activations and caches */
+    int32_t hidden, n_q_heads, n_kv_heads, head_dim, intermediate;
+    int32_t in_features, out_features;
+    float rms_eps, rope_base;
+} ccs_module_desc;
+
+/* Device pointers to the caller's weights in the module's dtype, row-major [out, in].
+ * Decoder layer: wq [n_q*d, H], wk/wv [n_kv*d, H], wo [H, n_q*d], wgate/wup [I, H],
+ * wdown [H, I], g1/g2 [H] (RMSNorm gains).  Linear: w [out, in]; the others are ignored.
+ * Read only during ccs_module_create. */
+typedef struct ccs_weights {
+    const void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown, *g1, *g2;
+    const void *w;
+} ccs_weights;
+
+/* One batch (or one contiguous slice of it).
+ *   PREFILL: x, y are [n_seqs, seq_pad, hidden]; lens[b] in [1, seq_pad] is the prompt length,
+ *            rows t >= lens[b] are padding: never read as keys, their y rows are unspecified
+ *            (finite).  If k_cache/v_cache are non-null the rotated keys and the values of
+ *            positions < lens[b] are stored there (cache_cap >= lens[b]).
+ *   DECODE:  x, y are [n_seqs, hidden]; lens[b] >= 0 is the number of cached positions; the
+ *            new token is position lens[b]: its key/value are stored at slot lens[b] and the
+ *            query attends over slots 0..lens[b] (cache_cap >= lens[b] + 1).  The caches are
+ *            required.  lens itself is not advanced by the library.
+ *   ROWS:    x is [n_seqs, in_features], y is [n_seqs, out_features]; seq_pad, lens and the
+ *            caches are ignored.
+ * lens_host and lens_dev hold the same n_seqs values (host copy for validation and launch
+ * planning, device copy for the kernels).  n_seqs == 0 is a legal no-op. */
+typedef struct ccs_batch {
+    int32_t mode; /* ccs_mode */
+    int32_t n_seqs, seq_pad;
+    const void *x;            /* device */
+    void *y;                  /* device */
+    const int32_t *lens_host; /* host   */
+    const int32_t *lens_dev;  /* device */
+    void *k_cache, *v_cache;  /* device */
+    int32_t cache_cap;
+} ccs_batch;
+
+/* Bytes of one replica's packed weights (what a clone copies); 0 if the desc is invalid.
+ * Table 1 of the paper counts the same bytes for a layer (projections only) - the arena adds
+ * the two norm-gain vectors and alignment padding.  Host-only, no GPU needed. */
+size_t ccs_module_arena_bytes(const ccs_module_desc *desc);
+
+/* Bytes of scratch one replica needs to run batches of at most max_seqs sequences with
+ * max_seq_pad rows each (1 for DECODE and ROWS) and caches of at most max_cache_cap slots.
+ * Host-only.  0 if the desc is invalid. */
+size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
+                                  int32_t max_seq_pad, int32_t max_cache_cap);
+
+/* Create a module with ONE instance (replica 0, "the original"): packs `weights` (device) into
+ * `arena0` (device, >= ccs_module_arena_bytes, 256-byte aligned) on `stream`, and remembers
+ * `workspace0` (device, workspace_bytes long, 256-byte aligned) and `stream` as replica 0's.
+ * The caller's weight buffers may be released after the stream has been synchronised.
+ * Errors: CCS_EINVAL (null/misaligned pointers, bad desc), CCS_EUNSUPPORTED, CCS_EHIP. */
+int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *weights, void *arena0,
+                      void *workspace0, size_t workspace_bytes, void *stream, ccs_module **out);
+
+/* Set the number of instances to k (1 <= k <= CCS_MAX_REPLICAS).  For every replica j that
+ * does not exist yet, arenas[j], workspaces[j] (device) and streams[j] are taken over and the
+ * weights of replica 0 are cloned into arenas[j] by a streaming HBM->HBM copy enqueued on
+ * streams[j] (after replica 0's pending pack/clone); replica j's forwards are ordered after
+ * its clone.  Entries of existing replicas (j < current k, including 0) are ignored and may
+ * be null.  Shrinking (k below the current count) waits for the dropped replicas' work and
+ * forgets them; their buffers go back to the caller.  Section 3.1 "Replication".
+ * Errors: CCS_EINVAL, CCS_EHIP. */
+int ccs_module_replicate(ccs_module *m, int32_t k, void *const *arenas, void *const *workspaces,
+                         size_t workspace_bytes, void *const *streams);
+
+/* Number of instances the module currently has (>= 1), or CCS_EINVAL. */
+int ccs_module_replicas(const ccs_module *m);
+
+/* Run the module on ONE replica over one contiguous slice, on that replica's stream.
+ * `slice` (host struct; its pointers as documented above) already points at the slice's first
+ * row / sequence.  Errors: CCS_EINVAL (bad replica index, bad batch), CCS_ESTATE, CCS_ENOMEM
+ * (workspace too small for this batch), CCS_EHIP. */
+int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice);
+
+/* The replicated forward of Section 3.1: cut the batch into k = ccs_module_replicas(m)
+ * contiguous slices [floor(j n / k), floor((j+1) n / k)) - over sequences for a decoder layer,
+ * over token rows for a projection - order `caller_stream` -> every replica stream (fork
+ * event), run slice j on replica j, and order every replica stream -> `caller_stream` (join
+ * events).  Outputs land in `full->y` at their batch positions, so the gather is free.
+ * Output rows are bit-identical for every k at a fixed batch. */
+int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream);
+
+/* Clone replica `replica`'s packed weights into `dst_arena` (device, arena_bytes) on `stream`
+ * (ordered after that replica's pending work); the source stays in use. */
+int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *stream);
+
+/* Migrate: clone as ccs_module_copy, then make `dst_arena` the replica's arena; later
+ * forwards on the replica are ordered after the copy.  The old arena belongs to the caller
+ * again once `stream` has been synchronised (Section 3.1 "Implementation": replicate to the
+ * destination, remove the local copy). */
+int ccs_module_migrate(ccs_module *m, int32_t replica, void *dst_arena, void *stream);
+
+/* Copy / migrate a KV cache that travels with its layer (Section 3.1 "Implementation":
+ * optional migration of the KV cache): a streaming copy of `bytes` bytes device->device on
+ * `stream`.  src and dst must not overlap; both 16-byte aligned. */
+int ccs_cache_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/* Device address of replica `replica`'s arena (for tests and for freeing after migrate). */
+int ccs_module_arena(const ccs_module *m, int32_t replica, void **arena_out);
+
+/* Block the host until every stream of the module has drained. */
+int ccs_module_sync(ccs_module *m);
+
+/* Wait for the module's work, release events and host metadata.  Device buffers stay with
+ * the caller. */
+int ccs_module_destroy(ccs_module *m);
+
+/* Thread-local, never null; valid until the next library call on this thread. */
+const char *ccs_last_error(void);
+
+/* Library version string. */
+const char *ccs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COCOSERVE_MI_H */

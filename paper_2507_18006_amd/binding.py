@@ -1,0 +1,278 @@
+"""ctypes binding of libcocoserve_mi.so: same names as the C ABI, marshalling only.
+
+PyTorch is used for what the library leaves to the caller: device allocations (weight arenas,
+workspaces, activations, KV caches) and HIP streams.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libcocoserve_mi.so"
+
+CCS_OK, CCS_EINVAL, CCS_ESTATE, CCS_ENOMEM, CCS_EUNSUPPORTED, CCS_EHIP = 0, -1, -2, -3, -4, -5
+CCS_DECODER_LAYER, CCS_LINEAR = 0, 1
+CCS_F32, CCS_BF16 = 0, 1
+CCS_PREFILL, CCS_DECODE, CCS_ROWS = 0, 1, 2
+CCS_MAX_REPLICAS = 16
+_STATUS = {0: "CCS_OK", -1: "CCS_EINVAL", -2: "CCS_ESTATE", -3: "CCS_ENOMEM",
+           -4: "CCS_EUNSUPPORTED", -5: "CCS_EHIP"}
+
+EXPORTS = (
+    "ccs_module_arena_bytes", "ccs_module_workspace_bytes", "ccs_module_create",
+    "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
+    "ccs_module_forward_split", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
+    "ccs_module_arena", "ccs_module_sync", "ccs_module_destroy", "ccs_last_error", "ccs_version",
+)
+
+
+class CcsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class ccs_module_desc(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("hidden", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("intermediate", ctypes.c_int32),
+                ("in_features", ctypes.c_int32), ("out_features", ctypes.c_int32),
+                ("rms_eps", ctypes.c_float), ("rope_base", ctypes.c_float)]
+
+
+class ccs_weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "g1", "g2", "w")]
+
+
+class ccs_batch(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("n_seqs", ctypes.c_int32), ("seq_pad", ctypes.c_int32),
+                ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
+                ("lens_host", ctypes.c_void_p), ("lens_dev", ctypes.c_void_p),
+                ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+                ("cache_cap", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, _LIB_NAME)
+
+
+def lib():
+    """Load the HIP library; there is no fallback when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(hipcc --offload-arch=gfx950); there is no CPU fallback")
+    L = ctypes.CDLL(path)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    L.ccs_module_arena_bytes.restype = sz
+    L.ccs_module_arena_bytes.argtypes = [ctypes.POINTER(ccs_module_desc)]
+    L.ccs_module_workspace_bytes.restype = sz
+    L.ccs_module_workspace_bytes.argtypes = [ctypes.POINTER(ccs_module_desc), i32, i32, i32]
+    L.ccs_module_create.argtypes = [ctypes.POINTER(ccs_module_desc), ctypes.POINTER(ccs_weights), vp, vp, sz, vp,
+                                    ctypes.POINTER(vp)]
+    L.ccs_module_replicate.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), sz, ctypes.POINTER(vp)]
+    L.ccs_module_replicas.argtypes = [vp]
+    L.ccs_module_forward.argtypes = [vp, i32, ctypes.POINTER(ccs_batch)]
+    L.ccs_module_forward_split.argtypes = [vp, ctypes.POINTER(ccs_batch), vp]
+    L.ccs_module_copy.argtypes = [vp, i32, vp, vp]
+    L.ccs_module_migrate.argtypes = [vp, i32, vp, vp]
+    L.ccs_cache_copy.argtypes = [vp, vp, sz, vp]
+    L.ccs_module_arena.argtypes = [vp, i32, ctypes.POINTER(vp)]
+    L.ccs_module_sync.argtypes = [vp]
+    L.ccs_module_destroy.argtypes = [vp]
+    L.ccs_last_error.restype = ctypes.c_char_p
+    L.ccs_version.restype = ctypes.c_char_p
+    for name in ("ccs_module_create", "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
+                 "ccs_module_forward_split", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
+                 "ccs_module_arena", "ccs_module_sync", "ccs_module_destroy"):
+        getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc < 0:
+        raise CcsError(rc, lib().ccs_last_error().decode())
+    return rc
+
+
+@dataclass
+class ModuleDesc:
+    kind: int = CCS_DECODER_LAYER
+    dtype: int = CCS_BF16
+    hidden: int = 0
+    n_q_heads: int = 0
+    n_kv_heads: int = 0
+    head_dim: int = 0
+    intermediate: int = 0
+    in_features: int = 0
+    out_features: int = 0
+    rms_eps: float = 1e-5
+    rope_base: float = 10000.0
+
+    def c(self) -> ccs_module_desc:
+        return ccs_module_desc(self.kind, self.dtype, self.hidden, self.n_q_heads, self.n_kv_heads,
+                               self.head_dim, self.intermediate, self.in_features, self.out_features,
+                               self.rms_eps, self.rope_base)
+
+
+def module_arena_bytes(desc: ModuleDesc) -> int:
+    d = desc.c()
+    return int(lib().ccs_module_arena_bytes(ctypes.byref(d)))
+
+
+def module_workspace_bytes(desc: ModuleDesc, max_seqs: int, max_seq_pad: int = 1, max_cache_cap: int = 0) -> int:
+    d = desc.c()
+    return int(lib().ccs_module_workspace_bytes(ctypes.byref(d), max_seqs, max_seq_pad, max_cache_cap))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _vp_array(items):
+    arr = (ctypes.c_void_p * len(items))()
+    for i, v in enumerate(items):
+        arr[i] = v
+    return arr
+
+
+class Module:
+    """One module (decoder layer or projection) with k >= 1 instances on one GPU.
+
+    Holds the torch allocations the C ABI expects the caller to own (arenas, workspaces,
+    streams) and forwards every operation to the library."""
+
+    def __init__(self, desc: ModuleDesc, weights: dict, max_seqs: int, max_seq_pad: int = 1,
+                 max_cache_cap: int = 0, device: str = "cuda:0"):
+        import torch
+        self._torch = torch
+        self.desc = desc
+        self.device = torch.device(device)
+        self.L = lib()
+        self.arena_bytes = module_arena_bytes(desc)
+        self.ws_bytes = module_workspace_bytes(desc, max_seqs, max_seq_pad, max_cache_cap)
+        if self.arena_bytes == 0 or self.ws_bytes == 0:
+            raise CcsError(CCS_EINVAL, self.L.ccs_last_error().decode())
+        self.torch_dtype = torch.bfloat16 if desc.dtype == CCS_BF16 else torch.float32
+        self.arenas = [self._alloc(self.arena_bytes)]
+        self.workspaces = [self._alloc(self.ws_bytes)]
+        self.streams = [torch.cuda.Stream(device=self.device)]
+        cw = ccs_weights()
+        keep = []
+        for name, t in weights.items():
+            if t.dtype != self.torch_dtype or not t.is_cuda or not t.is_contiguous():
+                raise ValueError(f"weight {name}: need a contiguous {self.torch_dtype} CUDA tensor")
+            keep.append(t)
+            setattr(cw, name, t.data_ptr())
+        d = desc.c()
+        h = ctypes.c_void_p()
+        # the weights may still be in flight on the current stream
+        self.streams[0].wait_stream(torch.cuda.current_stream(self.device))
+        _check(self.L.ccs_module_create(ctypes.byref(d), ctypes.byref(cw), self.arenas[0].data_ptr(),
+                                        self.workspaces[0].data_ptr(), self.ws_bytes,
+                                        self.streams[0].cuda_stream, ctypes.byref(h)))
+        self.handle = h
+        self.streams[0].synchronize()   # caller's weight tensors may now be dropped
+
+    def _alloc(self, nbytes: int):
+        return self._torch.empty(max(nbytes, 256), dtype=self._torch.uint8, device=self.device)
+
+    # -- module_replicate(k) ------------------------------------------------------------------
+    def replicate(self, k: int):
+        torch = self._torch
+        cur = self.replicas()
+        if k > CCS_MAX_REPLICAS or k < 1:
+            _check(self.L.ccs_module_replicate(self.handle, k, None, None, 0, None))
+        while len(self.arenas) < k:
+            self.arenas.append(self._alloc(self.arena_bytes))
+            self.workspaces.append(self._alloc(self.ws_bytes))
+            self.streams.append(torch.cuda.Stream(device=self.device))
+        a = _vp_array([t.data_ptr() for t in self.arenas[:k]])
+        w = _vp_array([t.data_ptr() for t in self.workspaces[:k]])
+        s = _vp_array([st.cuda_stream for st in self.streams[:k]])
+        _check(self.L.ccs_module_replicate(self.handle, k, a, w, self.ws_bytes, s))
+        if k < cur:
+            del self.arenas[k:], self.workspaces[k:], self.streams[k:]
+
+    def replicas(self) -> int:
+        return _check(self.L.ccs_module_replicas(self.handle))
+
+    # -- batches --------------------------------------------------------------------------------
+    def batch(self, mode: int, x, y, lens_host=None, lens_dev=None, k_cache=None, v_cache=None,
+              seq_pad: int = 1):
+        """Marshal tensors into a ccs_batch.  x: prefill [B,S,H] / decode [B,H] / rows [T,in]."""
+        n_seqs = x.shape[0]
+        cap = 0 if k_cache is None else k_cache.shape[2]
+        b = ccs_batch(mode, n_seqs, seq_pad, _ptr(x), _ptr(y),
+                      None if lens_host is None else lens_host.data_ptr(), _ptr(lens_dev),
+                      _ptr(k_cache), _ptr(v_cache), cap)
+        b._keep = (x, y, lens_host, lens_dev, k_cache, v_cache)
+        return b
+
+    def forward(self, replica: int, batch: ccs_batch):
+        _check(self.L.ccs_module_forward(self.handle, replica, ctypes.byref(batch)))
+
+    def forward_split(self, batch: ccs_batch, stream=None):
+        s = self._torch.cuda.current_stream(self.device) if stream is None else stream
+        _check(self.L.ccs_module_forward_split(self.handle, ctypes.byref(batch), s.cuda_stream))
+
+    # -- module_copy / module_migrate -----------------------------------------------------------
+    def copy(self, replica: int, stream=None):
+        """Clone a replica's weights into a fresh arena (returned)."""
+        s = self._torch.cuda.current_stream(self.device) if stream is None else stream
+        dst = self._alloc(self.arena_bytes)
+        _check(self.L.ccs_module_copy(self.handle, replica, dst.data_ptr(), s.cuda_stream))
+        return dst
+
+    def copy_into(self, replica: int, dst, stream=None):
+        s = self._torch.cuda.current_stream(self.device) if stream is None else stream
+        _check(self.L.ccs_module_copy(self.handle, replica, dst.data_ptr(), s.cuda_stream))
+
+    def migrate(self, replica: int, stream=None):
+        """Move a replica's weights to a fresh arena; the old arena is released after the copy."""
+        s = self._torch.cuda.current_stream(self.device) if stream is None else stream
+        dst = self._alloc(self.arena_bytes)
+        _check(self.L.ccs_module_migrate(self.handle, replica, dst.data_ptr(), s.cuda_stream))
+        s.synchronize()
+        old = self.arenas[replica]
+        self.arenas[replica] = dst
+        return old
+
+    def arena_ptr(self, replica: int) -> int:
+        p = ctypes.c_void_p()
+        _check(self.L.ccs_module_arena(self.handle, replica, ctypes.byref(p)))
+        return int(p.value)
+
+    def sync(self):
+        _check(self.L.ccs_module_sync(self.handle))
+
+    def destroy(self):
+        if getattr(self, "handle", None):
+            _check(self.L.ccs_module_destroy(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def cache_copy(dst, src, stream=None):
+    """Streaming device-to-device copy of a KV cache (same byte size, no overlap)."""
+    import torch
+    s = torch.cuda.current_stream(dst.device) if stream is None else stream
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    _check(lib().ccs_cache_copy(dst.data_ptr(), src.data_ptr(), nbytes, s.cuda_stream))

@@ -1,0 +1,81 @@
+// Shared device/host helpers of the gfx950 kernels: storage types, the fragment-packed matrix
+// layout, wavefront reductions.  Everything here is for 64-wide wavefronts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ccs {
+
+typedef uint16_t bf16_t;  // bf16 bit pattern
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// 16-byte streaming accesses (data touched once: weights, cached K/V, clone traffic)
+__device__ __forceinline__ uint4 ld_stream(const uint4 *p)
+{
+    u32x4_t v = __builtin_nontemporal_load((const u32x4_t *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_stream(uint4 *p, const uint4 &v)
+{
+    u32x4_t t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, (u32x4_t *)p);
+}
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ bf16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi)
+{
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// ---- fragment-packed layout --------------------------------------------------------------
+// A bf16 matrix [R, K] (R padded to 16, K a multiple of 32) that feeds the matrix cores is
+// stored as 1 KiB fragments of 16 rows x 32 columns, fragment (rb, kb) at ((rb * K/32) + kb);
+// inside a fragment lane l = (r % 16) + 16 * ((k % 32) / 8) owns 8 consecutive k (16 bytes).
+// This is exactly the operand register layout of v_mfma_f32_16x16x32_bf16 (both operands), so
+// a wavefront fetches one operand with one fully coalesced 1 KiB load and LDS copies of packed
+// data are bank-conflict free.
+__host__ __device__ __forceinline__ size_t packed_index(int r, int k, int kfrags)
+{
+    return ((((size_t)(r >> 4) * kfrags + (k >> 5)) * 64) + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+template <typename T> struct io;
+template <> struct io<float> {
+    static __device__ __forceinline__ float ld(const float *p) { return *p; }
+    static __device__ __forceinline__ void st(float *p, float v) { *p = v; }
+};
+template <> struct io<bf16_t> {
+    static __device__ __forceinline__ float ld(const bf16_t *p) { return bf2f(*p); }
+    static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f2bf(v); }
+};
+
+}  // namespace ccs

@@ -1,0 +1,241 @@
+// HBM-bound kernels of the decoder-layer path: replica clone (streaming copy), weight packing,
+// RMSNorm, rotary embedding + KV-cache append, SwiGLU (f32 path).
+#include "ccs_common.h"
+#include "ccs_kernels.h"
+
+namespace ccs {
+
+// ---------------------------------------------------------------------------------------------
+// Replica clone: the replica-instantiation step of module replication / migration (paper,
+// Section 3.1 "Implementation": the module is duplicated with its weights).  Pure HBM traffic:
+// `bytes` read + `bytes` written.  Each lane moves 16 bytes per access, four accesses in
+// flight per lane before the first store; the grid is a fixed multiple of the CU count and
+// strides over the buffer so that consecutive wavefronts touch consecutive 1 KiB lines.
+// ---------------------------------------------------------------------------------------------
+constexpr int kCloneThreads = 256;
+constexpr int kCloneUnroll = 4;
+
+__global__ __launch_bounds__(kCloneThreads) void clone_kernel(uint4 *__restrict__ dst,
+                                                              const uint4 *__restrict__ src,
+                                                              size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * kCloneThreads;
+    size_t i = (size_t)blockIdx.x * kCloneThreads + threadIdx.x;
+    for (; i + (kCloneUnroll - 1) * stride < n16; i += kCloneUnroll * stride) {
+        uint4 v[kCloneUnroll];
+#pragma unroll
+        for (int u = 0; u < kCloneUnroll; ++u) v[u] = ld_stream(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < kCloneUnroll; ++u) st_stream(dst + i + u * stride, v[u]);
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ void clone_tail_kernel(uint8_t *dst, const uint8_t *src, size_t from, size_t bytes)
+{
+    size_t i = from + threadIdx.x;
+    if (i < bytes) dst[i] = src[i];
+}
+
+hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return hipSuccess;
+    size_t n16 = bytes / 16;
+    if (n16) {
+        size_t want = (n16 + (size_t)kCloneThreads * kCloneUnroll - 1) / ((size_t)kCloneThreads * kCloneUnroll);
+        int blocks = (int)(want < 4096 ? want : 4096);  // 16 workgroups per CU on 256 CUs
+        hipLaunchKernelGGL(clone_kernel, dim3(blocks), dim3(kCloneThreads), 0, st, (uint4 *)dst,
+                           (const uint4 *)src, n16);
+    }
+    if (bytes % 16)
+        hipLaunchKernelGGL(clone_tail_kernel, dim3(1), dim3(16), 0, st, (uint8_t *)dst,
+                           (const uint8_t *)src, n16 * 16, bytes);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight packing (module_create): row-major [N, K] bf16 -> fragment-packed.  One thread per
+// 16-byte chunk (8 consecutive k of one row).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4 *__restrict__ src,
+                                                        uint4 *__restrict__ dst, int N, int K,
+                                                        int blk_stride, int blk_offset)
+{
+    const int kchunks = K >> 3;
+    const size_t total = (size_t)N * kchunks;
+    const int kfrags = K >> 5;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        int n = (int)(i / kchunks), kc = (int)(i % kchunks);
+        int nb = (n >> 4) * blk_stride + blk_offset;
+        size_t o = (((size_t)nb * kfrags + (kc >> 2)) * 64) + (n & 15) + 16 * (kc & 3);
+        dst[o] = src[i];
+    }
+}
+
+hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int blk_stride,
+                            int blk_offset, hipStream_t st)
+{
+    size_t total = (size_t)N * (K / 8);
+    if (!total) return hipSuccess;
+    int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
+    hipLaunchKernelGGL(pack_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src,
+                       (uint4 *)dst_packed, N, K, blk_stride, blk_offset);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm: one wavefront per row, wave-wide butterfly reduction of the squares; the second
+// pass re-reads the row (it is in L1/L2).  A row's arithmetic does not depend on how many
+// rows the launch has.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint4 *__restrict__ x,
+                                                           const uint4 *__restrict__ g,
+                                                           uint4 *__restrict__ out, int rows, int H,
+                                                           float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int chunks = H >> 3;
+    const uint4 *xr = x + (size_t)row * chunks;
+    float ss = 0.f;
+    for (int c = lane; c < chunks; c += 64) {
+        uint4 v = xr[c];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = bf_lo(w[j]), b = bf_hi(w[j]);
+            ss = fmaf(a, a, ss);
+            ss = fmaf(b, b, ss);
+        }
+    }
+    ss = wave_sum(ss);
+    const float r = 1.0f / sqrtf(ss / (float)H + eps);
+    const int kfrags = H >> 5;
+    for (int c = lane; c < chunks; c += 64) {
+        uint4 v = xr[c], gv = g[c];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            o[j] = pack2bf(bf_lo(w[j]) * r * bf_lo(gw[j]), bf_hi(w[j]) * r * bf_hi(gw[j]));
+        size_t dst = (((size_t)(row >> 4) * kfrags + (c >> 2)) * 64) + (row & 15) + 16 * (c & 3);
+        out[dst] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_f32_kernel(const float *__restrict__ x,
+                                                          const float *__restrict__ g,
+                                                          float *__restrict__ out, int rows, int H,
+                                                          float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float *xr = x + (size_t)row * H;
+    float ss = 0.f;
+    for (int c = lane; c < H; c += 64) ss = fmaf(xr[c], xr[c], ss);
+    ss = wave_sum(ss);
+    const float r = 1.0f / sqrtf(ss / (float)H + eps);
+    for (int c = lane; c < H; c += 64) out[(size_t)row * H + c] = xr[c] * r * g[c];
+}
+
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H,
+                          float eps, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    dim3 grid((rows + 3) / 4), block(256);
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(rmsnorm_bf16_kernel, grid, block, 0, st, (const uint4 *)x, (const uint4 *)g,
+                           (uint4 *)out, rows, H, eps);
+    else
+        hipLaunchKernelGGL(rmsnorm_f32_kernel, grid, block, 0, st, (const float *)x, (const float *)g,
+                           (float *)out, rows, H, eps);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rotary embedding + KV-cache append.  One workgroup per row, thread i owns the pair
+// (i, i + d/2) of every head; the angle pos * base^(-2i/d) and its sine/cosine are evaluated
+// in fp64 once per thread and applied in fp32.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, int nkv, int d,
+                                                  float base, int decode, int seq_pad,
+                                                  const int32_t *__restrict__ lens,
+                                                  T *__restrict__ k_cache, T *__restrict__ v_cache,
+                                                  int cap)
+{
+    const int row = blockIdx.x;
+    const int half = d >> 1;
+    const int width = (nq + 2 * nkv) * d;
+    T *r = qkv + (size_t)row * width;
+    int seq, pos, len;
+    if (decode) { seq = row; pos = lens[row]; len = pos + 1; }
+    else { seq = row / seq_pad; pos = row % seq_pad; len = lens[seq]; }
+    const bool store = (k_cache != nullptr) && (pos < len) && (pos < cap);
+    for (int i = threadIdx.x; i < half; i += 64) {
+        double theta = pow((double)base, -2.0 * (double)i / (double)d);
+        double sd, cd;
+        sincos((double)pos * theta, &sd, &cd);
+        const float c = (float)cd, s = (float)sd;
+        for (int h = 0; h < nq + nkv; ++h) {
+            T *z = r + (size_t)h * d;
+            float a = io<T>::ld(z + i), b = io<T>::ld(z + i + half);
+            float ra = a * c - b * s, rb = b * c + a * s;
+            io<T>::st(z + i, ra);
+            io<T>::st(z + i + half, rb);
+            if (store && h >= nq) {
+                T *kc = k_cache + (((size_t)seq * nkv + (h - nq)) * cap + pos) * d;
+                io<T>::st(kc + i, ra);
+                io<T>::st(kc + i + half, rb);
+            }
+        }
+        if (store) {
+            for (int h = 0; h < nkv; ++h) {
+                const T *v = r + (size_t)(nq + nkv + h) * d;
+                T *vc = v_cache + (((size_t)seq * nkv + h) * cap + pos) * d;
+                vc[i] = v[i];
+                vc[i + half] = v[i + half];
+            }
+        }
+    }
+}
+
+hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, float base,
+                       int decode, int seq_pad, const int32_t *lens_dev, void *k_cache,
+                       void *v_cache, int cap, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(rows), dim3(64), 0, st, (bf16_t *)qkv, nq, nkv, d,
+                           base, decode, seq_pad, lens_dev, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
+    else
+        hipLaunchKernelGGL(rope_kernel<float>, dim3(rows), dim3(64), 0, st, (float *)qkv, nq, nkv, d,
+                           base, decode, seq_pad, lens_dev, (float *)k_cache, (float *)v_cache, cap);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void swiglu_f32_kernel(const float *__restrict__ gu,
+                                                         float *__restrict__ u, size_t total, int I)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    size_t t = i / I;
+    int j = (int)(i % I);
+    float g = gu[t * 2 * I + j], up = gu[t * 2 * I + I + j];
+    u[i] = g / (1.0f + expf(-g)) * up;
+}
+
+hipError_t launch_swiglu_f32(const float *gu, float *u, int rows, int I, hipStream_t st)
+{
+    size_t total = (size_t)rows * I;
+    if (!total) return hipSuccess;
+    hipLaunchKernelGGL(swiglu_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, gu, u,
+                       total, I);
+    return hipGetLastError();
+}
+
+}  // namespace ccs

@@ -1,0 +1,72 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher only enqueues on `st` and
+// returns the launch status; shapes are validated by the caller (ccs_module.cpp).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ccs {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+// ---- streaming / elementwise (ccs_elementwise.hip) -----------------------------------------
+// dst[0:bytes) = src[0:bytes), both 16-byte aligned, device memory, no overlap.
+hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st);
+// Row-major bf16 [N, K] -> fragment-packed rows; 16-row block nb of the source lands at packed
+// block nb * blk_stride + blk_offset of a packed matrix with K/32 fragments per block row.
+hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int blk_stride,
+                            int blk_offset, hipStream_t st);
+// out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g.  x row-major [rows, H].
+// bf16: out is fragment-packed [rows16, H]; f32: out row-major.
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H,
+                          float eps, hipStream_t st);
+// Rotary embedding (split-half pairs) in place on the q and k parts of qkv [rows, (nq+2nkv)*d]
+// row-major.  prefill (decode == 0): position = row % seq_pad; when caches are non-null the
+// rotated k and v of rows with position < lens[row / seq_pad] are stored at slot = position.
+// decode: position = lens[row]; rotated k and v stored at slot lens[row] of sequence `row`.
+hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, float base,
+                       int decode, int seq_pad, const int32_t *lens_dev, void *k_cache,
+                       void *v_cache, int cap, hipStream_t st);
+// f32 path: u[t,j] = silu(gu[t,j]) * gu[t, I + j], gu row-major [rows, 2I].
+hipError_t launch_swiglu_f32(const float *gu, float *u, int rows, int I, hipStream_t st);
+
+// ---- GEMMs (ccs_gemm.hip) ------------------------------------------------------------------
+// f32: y[m,n] = sum_k x[m,k] W[n,k] (+ res[m,n]); everything row-major.
+hipError_t launch_gemm_f32(const float *x, const float *W, const float *res, float *y, int M,
+                           int N, int K, hipStream_t st);
+
+enum GemmEpilogue {
+    EPI_STORE_RM = 0,   // y row-major bf16 [M, N], optional residual (row-major bf16 [M, N])
+    EPI_SWIGLU_PACKED = 1  // N = 2I with gate/up interleaved in 16-row blocks; u fragment-packed [M16, I]
+};
+// Number of K segments the weight-streaming GEMM uses for a [N, K] weight; depends on the
+// weight shape only, never on the number of rows, so that a row's bits do not depend on the
+// batch it is computed in.
+int skinny_segments(int N, int K);
+size_t skinny_partial_bytes(int M, int N, int K);
+// Largest row count the weight-streaming variant accepts in one launch.
+constexpr int kSkinnyMaxRows = 64;
+// bf16 weight-streaming GEMM for M <= kSkinnyMaxRows rows: partial sums per K segment into
+// `partials` (fp32 [S, M, N]) followed by a fixed-order reduction with the epilogue.
+hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, int epi,
+                              const void *res, void *out, int M, int N, int K, hipStream_t st);
+// bf16 LDS-tiled MFMA GEMM for any M; Xp must be readable up to M rounded up to 256 rows.
+hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void *res, void *out,
+                             int M, int N, int K, hipStream_t st);
+
+// ---- attention (ccs_attention.hip) ---------------------------------------------------------
+// Generic (slow, any head_dim <= 256) softmax attention: one wavefront per query row.
+// Query rows come from qkv row-major [rows, (nq+2nkv)*d].  prefill: keys/values are the k/v
+// parts of qkv of the same sequence, key j visible to row position t iff j <= t; rows with
+// position >= lens[b] are skipped.  decode: keys/values are cache slots 0..lens[b].
+// Output: f32 row-major [rows, nq*d]; bf16 fragment-packed [rows16, nq*d].
+hipError_t launch_attn_generic(int dtype, const void *qkv, void *out, int rows, int nq, int nkv,
+                               int d, int decode, int seq_pad, const int32_t *lens_dev,
+                               const void *k_cache, const void *v_cache, int cap, hipStream_t st);
+// bf16, head_dim 128 decode attention with split-KV partials (fp32) and an ordered combine.
+size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap);
+hipError_t launch_attn_decode(const void *qkv, void *out_packed, float *partials, int n_seqs,
+                              int nq, int nkv, const int32_t *lens_dev, const void *k_cache,
+                              const void *v_cache, int cap, hipStream_t st);
+
+}  // namespace ccs

@@ -1,0 +1,567 @@
+// Host runtime and C ABI (include/cocoserve_mi.h): module handle, weight-arena and workspace
+// plans, replica streams/events, the batch-slice planner and the fork/join of the replicated
+// forward (paper, Section 3.1 "Replication" / "Migration" / "Implementation").
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "../../include/cocoserve_mi.h"
+#include "ccs_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define CCS_HIP(expr)                                                                       \
+    do {                                                                                    \
+        hipError_t e__ = (expr);                                                            \
+        if (e__ != hipSuccess) return fail(CCS_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Dims {
+    int H, nq, nkv, d, I, QD, KD, W3;  // W3 = QD + 2 KD
+    int in_f, out_f;
+    size_t esz;
+};
+
+struct ArenaPlan {
+    size_t qkv, o, gu, dn, g1, g2, w, total;
+};
+
+struct WsPlan {
+    size_t h, qkv, a, x1, gu, u, xp, scratch, scratch_bytes, total;
+};
+
+int check_desc(const ccs_module_desc *D, Dims *out)
+{
+    if (!D) return fail(CCS_EINVAL, "desc is null");
+    if (D->dtype != CCS_F32 && D->dtype != CCS_BF16) return fail(CCS_EINVAL, "unknown dtype %d", D->dtype);
+    Dims d{};
+    d.esz = D->dtype == CCS_BF16 ? 2 : 4;
+    if (D->kind == CCS_DECODER_LAYER) {
+        if (D->hidden <= 0 || D->n_q_heads <= 0 || D->n_kv_heads <= 0 || D->head_dim <= 0 || D->intermediate <= 0)
+            return fail(CCS_EINVAL, "decoder-layer dimensions must be positive");
+        if (D->n_q_heads % D->n_kv_heads) return fail(CCS_EINVAL, "n_q_heads %% n_kv_heads != 0");
+        if (D->head_dim & 1) return fail(CCS_EINVAL, "head_dim must be even");
+        if (!(D->rms_eps >= 0.f) || !(D->rope_base > 0.f)) return fail(CCS_EINVAL, "bad rms_eps / rope_base");
+        d.H = D->hidden; d.nq = D->n_q_heads; d.nkv = D->n_kv_heads; d.d = D->head_dim; d.I = D->intermediate;
+        d.QD = d.nq * d.d; d.KD = d.nkv * d.d; d.W3 = d.QD + 2 * d.KD;
+        if (d.d > 256) return fail(CCS_EUNSUPPORTED, "head_dim > 256");
+        if (D->dtype == CCS_BF16) {
+            if (d.H % 32 || d.QD % 32 || d.I % 32 || d.KD % 16)
+                return fail(CCS_EUNSUPPORTED, "bf16 path: hidden, n_q*d, intermediate must be multiples of 32, n_kv*d of 16");
+            if (d.d != 128) return fail(CCS_EUNSUPPORTED, "bf16 path: head_dim must be 128");
+            const int G = d.nq / d.nkv;
+            if (G != 1 && G != 2 && G != 4 && G != 8) return fail(CCS_EUNSUPPORTED, "bf16 path: n_q/n_kv must be 1, 2, 4 or 8");
+        }
+    } else if (D->kind == CCS_LINEAR) {
+        if (D->in_features <= 0 || D->out_features <= 0) return fail(CCS_EINVAL, "linear dimensions must be positive");
+        d.in_f = D->in_features; d.out_f = D->out_features;
+        if (D->dtype == CCS_BF16 && (d.in_f % 32 || d.out_f % 16))
+            return fail(CCS_EUNSUPPORTED, "bf16 path: in_features %% 32 and out_features %% 16 must be 0");
+    } else {
+        return fail(CCS_EINVAL, "unknown kind %d", D->kind);
+    }
+    if (out) *out = d;
+    return CCS_OK;
+}
+
+ArenaPlan arena_plan(const ccs_module_desc *D, const Dims &d)
+{
+    ArenaPlan p{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    if (D->kind == CCS_LINEAR) {
+        p.w = take((size_t)d.out_f * d.in_f * d.esz);
+    } else {
+        p.qkv = take((size_t)d.W3 * d.H * d.esz);
+        p.o = take((size_t)d.H * d.QD * d.esz);
+        p.gu = take((size_t)2 * d.I * d.H * d.esz);
+        p.dn = take((size_t)d.H * d.I * d.esz);
+        p.g1 = take((size_t)d.H * d.esz);
+        p.g2 = take((size_t)d.H * d.esz);
+    }
+    p.total = off;
+    return p;
+}
+
+inline size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
+
+// Scratch one forward over `rows` rows (n_seqs sequences, caches of `cap` slots) needs.
+// `skinny`: the weight-streaming GEMM variant is in use (rows <= kSkinnyMaxRows).
+WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs, int cap, bool skinny,
+               bool decode)
+{
+    WsPlan p{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t r16 = align_up(rows, 16);
+    if (D->kind == CCS_LINEAR) {
+        if (D->dtype == CCS_BF16) {
+            p.xp = take(r16 * d.in_f * 2);
+            p.scratch_bytes = skinny ? ccs::skinny_partial_bytes((int)rows, d.out_f, d.in_f) : 0;
+            p.scratch = take(p.scratch_bytes);
+        }
+    } else if (D->dtype == CCS_BF16) {
+        p.h = take(r16 * d.H * 2);
+        p.qkv = take(rows * d.W3 * 2);
+        p.a = take(r16 * d.QD * 2);
+        p.x1 = take(rows * d.H * 2);
+        p.u = take(r16 * d.I * 2);
+        size_t s = 0;
+        if (skinny) {
+            s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.W3, d.H));
+            s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.QD));
+            s = max_sz(s, ccs::skinny_partial_bytes((int)rows, 2 * d.I, d.H));
+            s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.I));
+        }
+        if (decode) s = max_sz(s, ccs::attn_decode_partial_bytes(n_seqs, d.nq, cap));
+        p.scratch_bytes = s;
+        p.scratch = take(s);
+    } else {
+        p.h = take(rows * d.H * 4);
+        p.qkv = take(rows * d.W3 * 4);
+        p.a = take(rows * d.QD * 4);
+        p.x1 = take(rows * d.H * 4);
+        p.gu = take(rows * 2 * d.I * 4);
+        p.u = take(rows * d.I * 4);
+    }
+    p.total = off;
+    return p;
+}
+
+struct Replica {
+    void *arena = nullptr;
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    hipStream_t stream = nullptr;
+    hipEvent_t ready = nullptr;  // arena contents complete (pack / clone / migrate)
+    hipEvent_t done = nullptr;   // last forward_split slice finished
+};
+
+}  // namespace
+
+struct ccs_module {
+    ccs_module_desc desc;
+    Dims dims;
+    ArenaPlan ap;
+    int k = 0;
+    Replica rep[CCS_MAX_REPLICAS];
+    hipEvent_t fork = nullptr;
+};
+
+namespace {
+
+int make_event(hipEvent_t *ev)
+{
+    CCS_HIP(hipEventCreateWithFlags(ev, hipEventDisableTiming));
+    return CCS_OK;
+}
+
+int check_batch(const ccs_module *m, const ccs_batch *b)
+{
+    if (!b) return fail(CCS_EINVAL, "batch is null");
+    if (b->n_seqs < 0) return fail(CCS_EINVAL, "n_seqs < 0");
+    const Dims &d = m->dims;
+    if (m->desc.kind == CCS_LINEAR) {
+        if (b->mode != CCS_ROWS) return fail(CCS_EINVAL, "a linear module takes mode CCS_ROWS");
+        if (b->n_seqs > 0 && (!b->x || !b->y)) return fail(CCS_EINVAL, "x / y is null");
+        return CCS_OK;
+    }
+    if (b->mode != CCS_PREFILL && b->mode != CCS_DECODE)
+        return fail(CCS_EINVAL, "a decoder layer takes mode CCS_PREFILL or CCS_DECODE");
+    if (b->n_seqs == 0) return CCS_OK;
+    if (!b->x || !b->y) return fail(CCS_EINVAL, "x / y is null");
+    if (!b->lens_host || !b->lens_dev) return fail(CCS_EINVAL, "lens_host / lens_dev is null");
+    if ((b->k_cache == nullptr) != (b->v_cache == nullptr)) return fail(CCS_EINVAL, "k_cache and v_cache must come together");
+    if (b->mode == CCS_PREFILL) {
+        if (b->seq_pad < 1) return fail(CCS_EINVAL, "seq_pad < 1");
+        if ((long long)b->n_seqs * b->seq_pad > 0x7fffffffLL / 4) return fail(CCS_EUNSUPPORTED, "too many rows");
+        for (int i = 0; i < b->n_seqs; ++i) {
+            const int len = b->lens_host[i];
+            if (len < 1 || len > b->seq_pad) return fail(CCS_EINVAL, "lens[%d] = %d outside [1, seq_pad = %d]", i, len, b->seq_pad);
+            if (b->k_cache && len > b->cache_cap) return fail(CCS_EINVAL, "lens[%d] = %d exceeds cache_cap %d", i, len, b->cache_cap);
+        }
+        if (b->seq_pad > 8192) return fail(CCS_EUNSUPPORTED, "seq_pad > 8192");
+    } else {
+        if (!b->k_cache) return fail(CCS_EINVAL, "decode needs k_cache / v_cache");
+        if (b->cache_cap < 1) return fail(CCS_EINVAL, "cache_cap < 1");
+        for (int i = 0; i < b->n_seqs; ++i) {
+            const int len = b->lens_host[i];
+            if (len < 0 || len + 1 > b->cache_cap) return fail(CCS_EINVAL, "lens[%d] = %d needs cache_cap > %d (have %d)", i, len, len, b->cache_cap);
+        }
+        if (m->desc.dtype == CCS_F32 && b->cache_cap > 8192) return fail(CCS_EUNSUPPORTED, "f32 decode: cache_cap > 8192");
+    }
+    (void)d;
+    return CCS_OK;
+}
+
+// One replica, one slice.  variant_rows: row count that selects the GEMM variant (the full
+// batch's for a replicated forward, so that every replica count produces the same bits).
+int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows)
+{
+    using namespace ccs;
+    Replica &R = m->rep[r];
+    const Dims &d = m->dims;
+    const ccs_module_desc &D = m->desc;
+    hipStream_t st = R.stream;
+    if (b->n_seqs == 0) return CCS_OK;
+    const bool bf = D.dtype == CCS_BF16;
+    const bool skinny = bf && variant_rows <= kSkinnyMaxRows;
+    char *ws = (char *)R.ws;
+    const char *A = (const char *)R.arena;
+
+    if (D.kind == CCS_LINEAR) {
+        const int M = b->n_seqs;
+        if (!bf) {
+            CCS_HIP(launch_gemm_f32((const float *)b->x, (const float *)(A + m->ap.w), nullptr, (float *)b->y, M, d.out_f, d.in_f, st));
+            return CCS_OK;
+        }
+        WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false);
+        if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
+        CCS_HIP(launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, st));
+        if (skinny)
+            CCS_HIP(launch_gemm_skinny(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+        else
+            CCS_HIP(launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+        return CCS_OK;
+    }
+
+    const bool decode = b->mode == CCS_DECODE;
+    const int seq_pad = decode ? 1 : b->seq_pad;
+    const int T = b->n_seqs * seq_pad;
+    WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode);
+    if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
+    const int dt = bf ? DT_BF16 : DT_F32;
+
+    CCS_HIP(launch_rmsnorm(dt, b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+    if (bf) {
+        auto gemm = [&](size_t woff, size_t xoff, int epi, const void *res, void *out, int N, int K) -> hipError_t {
+            return skinny ? launch_gemm_skinny(A + woff, ws + xoff, (float *)(ws + p.scratch), epi, res, out, T, N, K, st)
+                          : launch_gemm_tiled(A + woff, ws + xoff, epi, res, out, T, N, K, st);
+        };
+        CCS_HIP(gemm(m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H));
+        CCS_HIP(launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        if (decode)
+            CCS_HIP(launch_attn_decode(ws + p.qkv, ws + p.a, (float *)(ws + p.scratch), b->n_seqs, d.nq, d.nkv, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        else
+            CCS_HIP(launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, 0, seq_pad, b->lens_dev, nullptr, nullptr, 0, st));
+        CCS_HIP(gemm(m->ap.o, p.a, EPI_STORE_RM, b->x, ws + p.x1, d.H, d.QD));
+        CCS_HIP(launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+        CCS_HIP(gemm(m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H));
+        CCS_HIP(gemm(m->ap.dn, p.u, EPI_STORE_RM, ws + p.x1, b->y, d.H, d.I));
+    } else {
+        const float *Af = (const float *)A;
+        auto W = [&](size_t off) { return (const float *)(A + off); };
+        (void)Af;
+        CCS_HIP(launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
+        CCS_HIP(launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        CCS_HIP(launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        CCS_HIP(launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)b->x, (float *)(ws + p.x1), T, d.H, d.QD, st));
+        CCS_HIP(launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+        CCS_HIP(launch_gemm_f32((const float *)(ws + p.h), W(m->ap.gu), nullptr, (float *)(ws + p.gu), T, 2 * d.I, d.H, st));
+        CCS_HIP(launch_swiglu_f32((const float *)(ws + p.gu), (float *)(ws + p.u), T, d.I, st));
+        CCS_HIP(launch_gemm_f32((const float *)(ws + p.u), W(m->ap.dn), (const float *)(ws + p.x1), (float *)b->y, T, d.H, d.I, st));
+    }
+    return CCS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ccs_last_error(void) { return g_err; }
+const char *ccs_version(void) { return "cocoserve_mi 0.1 (gfx950)"; }
+
+size_t ccs_module_arena_bytes(const ccs_module_desc *desc)
+{
+    Dims d;
+    if (check_desc(desc, &d) != CCS_OK) return 0;
+    return arena_plan(desc, d).total;
+}
+
+size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs, int32_t max_seq_pad,
+                                  int32_t max_cache_cap)
+{
+    Dims d;
+    if (check_desc(desc, &d) != CCS_OK) return 0;
+    if (max_seqs < 0 || max_seq_pad < 1 || max_cache_cap < 0) {
+        fail(CCS_EINVAL, "negative sizes");
+        return 0;
+    }
+    const size_t rows = (size_t)max_seqs * max_seq_pad;
+    const bool skinny = rows <= (size_t)ccs::kSkinnyMaxRows;
+    // a smaller batch may take the weight-streaming variant: cover both plans
+    size_t need = ws_plan(desc, d, rows, max_seqs, max_cache_cap, skinny, max_cache_cap > 0).total;
+    if (!skinny) {
+        size_t small = ws_plan(desc, d, ccs::kSkinnyMaxRows, max_seqs < ccs::kSkinnyMaxRows ? max_seqs : ccs::kSkinnyMaxRows,
+                               max_cache_cap, true, max_cache_cap > 0).total;
+        need = max_sz(need, small);
+    }
+    return need ? need : 256;
+}
+
+int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *arena0, void *workspace0,
+                      size_t workspace_bytes, void *stream, ccs_module **out)
+{
+    using namespace ccs;
+    if (!out) return fail(CCS_EINVAL, "out is null");
+    *out = nullptr;
+    Dims d;
+    int rc = check_desc(desc, &d);
+    if (rc != CCS_OK) return rc;
+    if (!w || !arena0 || !workspace0) return fail(CCS_EINVAL, "weights / arena0 / workspace0 is null");
+    if (((uintptr_t)arena0 & 255) || ((uintptr_t)workspace0 & 255)) return fail(CCS_EINVAL, "arena0 / workspace0 must be 256-byte aligned");
+    if (desc->kind == CCS_LINEAR) {
+        if (!w->w) return fail(CCS_EINVAL, "weights.w is null");
+    } else if (!w->wq || !w->wk || !w->wv || !w->wo || !w->wgate || !w->wup || !w->wdown || !w->g1 || !w->g2) {
+        return fail(CCS_EINVAL, "a decoder-layer weight pointer is null");
+    }
+    int ndev = 0;
+    CCS_HIP(hipGetDeviceCount(&ndev));
+    if (ndev < 1) return fail(CCS_EHIP, "no HIP device");
+
+    ccs_module *m = new (std::nothrow) ccs_module();
+    if (!m) return fail(CCS_ENOMEM, "host allocation failed");
+    m->desc = *desc;
+    m->dims = d;
+    m->ap = arena_plan(desc, d);
+    hipStream_t st = (hipStream_t)stream;
+    char *A = (char *)arena0;
+    const bool bf = desc->dtype == CCS_BF16;
+    hipError_t e = hipSuccess;
+    auto rm_copy = [&](size_t off, const void *src, size_t bytes) { if (e == hipSuccess) e = launch_clone(A + off, src, bytes, st); };
+    auto pack = [&](size_t off, const void *src, int N, int K, int stride, int blk_off) {
+        if (e == hipSuccess) e = launch_pack_bf16(src, A + off, N, K, stride, blk_off, st);
+    };
+    if (desc->kind == CCS_LINEAR) {
+        if (bf) pack(m->ap.w, w->w, d.out_f, d.in_f, 1, 0);
+        else rm_copy(m->ap.w, w->w, (size_t)d.out_f * d.in_f * 4);
+    } else if (bf) {
+        pack(m->ap.qkv, w->wq, d.QD, d.H, 1, 0);
+        pack(m->ap.qkv, w->wk, d.KD, d.H, 1, d.QD / 16);
+        pack(m->ap.qkv, w->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16);
+        pack(m->ap.o, w->wo, d.H, d.QD, 1, 0);
+        pack(m->ap.gu, w->wgate, d.I, d.H, 2, 0);  // gate blocks even, up blocks odd
+        pack(m->ap.gu, w->wup, d.I, d.H, 2, 1);
+        pack(m->ap.dn, w->wdown, d.H, d.I, 1, 0);
+        rm_copy(m->ap.g1, w->g1, (size_t)d.H * 2);
+        rm_copy(m->ap.g2, w->g2, (size_t)d.H * 2);
+    } else {
+        const size_t rowb = (size_t)d.H * 4;
+        rm_copy(m->ap.qkv, w->wq, d.QD * rowb);
+        rm_copy(m->ap.qkv + d.QD * rowb, w->wk, d.KD * rowb);
+        rm_copy(m->ap.qkv + (d.QD + d.KD) * rowb, w->wv, d.KD * rowb);
+        rm_copy(m->ap.o, w->wo, (size_t)d.H * d.QD * 4);
+        rm_copy(m->ap.gu, w->wgate, d.I * rowb);
+        rm_copy(m->ap.gu + d.I * rowb, w->wup, d.I * rowb);
+        rm_copy(m->ap.dn, w->wdown, (size_t)d.H * d.I * 4);
+        rm_copy(m->ap.g1, w->g1, rowb);
+        rm_copy(m->ap.g2, w->g2, rowb);
+    }
+    if (e != hipSuccess) {
+        delete m;
+        return fail(CCS_EHIP, "packing weights: %s", hipGetErrorString(e));
+    }
+    Replica &R = m->rep[0];
+    R.arena = arena0; R.ws = workspace0; R.ws_bytes = workspace_bytes; R.stream = st;
+    if (make_event(&R.ready) != CCS_OK || make_event(&R.done) != CCS_OK || make_event(&m->fork) != CCS_OK) {
+        delete m;
+        return CCS_EHIP;
+    }
+    e = hipEventRecord(R.ready, st);
+    if (e != hipSuccess) { delete m; return fail(CCS_EHIP, "hipEventRecord: %s", hipGetErrorString(e)); }
+    m->k = 1;
+    *out = m;
+    return CCS_OK;
+}
+
+int ccs_module_replicate(ccs_module *m, int32_t k, void *const *arenas, void *const *workspaces,
+                         size_t workspace_bytes, void *const *streams)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    if (k < 1 || k > CCS_MAX_REPLICAS) return fail(CCS_EINVAL, "k = %d outside [1, %d]", k, (int)CCS_MAX_REPLICAS);
+    if (k < m->k) {
+        for (int j = k; j < m->k; ++j) {
+            Replica &R = m->rep[j];
+            CCS_HIP(hipStreamSynchronize(R.stream));
+            if (R.ready) (void)hipEventDestroy(R.ready);
+            if (R.done) (void)hipEventDestroy(R.done);
+            R = Replica();
+        }
+        m->k = k;
+        return CCS_OK;
+    }
+    if (k == m->k) return CCS_OK;
+    if (!arenas || !workspaces || !streams) return fail(CCS_EINVAL, "arenas / workspaces / streams is null");
+    for (int j = m->k; j < k; ++j) {
+        if (!arenas[j] || !workspaces[j]) return fail(CCS_EINVAL, "arena / workspace of replica %d is null", j);
+        if (((uintptr_t)arenas[j] & 255) || ((uintptr_t)workspaces[j] & 255)) return fail(CCS_EINVAL, "buffers of replica %d must be 256-byte aligned", j);
+        for (int i = 0; i < j; ++i) {
+            void *other = i < m->k ? m->rep[i].arena : arenas[i];
+            if (other == arenas[j]) return fail(CCS_EINVAL, "replica %d would share replica %d's arena", j, i);
+        }
+    }
+    for (int j = m->k; j < k; ++j) {
+        Replica R;
+        R.arena = arenas[j]; R.ws = workspaces[j]; R.ws_bytes = workspace_bytes; R.stream = (hipStream_t)streams[j];
+        int rc = make_event(&R.ready);
+        if (rc != CCS_OK) return rc;
+        rc = make_event(&R.done);
+        if (rc != CCS_OK) return rc;
+        CCS_HIP(hipStreamWaitEvent(R.stream, m->rep[0].ready, 0));
+        CCS_HIP(ccs::launch_clone(R.arena, m->rep[0].arena, m->ap.total, R.stream));
+        CCS_HIP(hipEventRecord(R.ready, R.stream));
+        m->rep[j] = R;
+        m->k = j + 1;
+    }
+    return CCS_OK;
+}
+
+int ccs_module_replicas(const ccs_module *m)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    return m->k;
+}
+
+int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    if (replica < 0 || replica >= CCS_MAX_REPLICAS) return fail(CCS_EINVAL, "replica index %d out of range", replica);
+    if (replica >= m->k) return fail(CCS_ESTATE, "replica %d is not instantiated (module has %d)", replica, m->k);
+    int rc = check_batch(m, slice);
+    if (rc != CCS_OK) return rc;
+    const long long rows = (long long)slice->n_seqs * (slice->mode == CCS_PREFILL ? slice->seq_pad : 1);
+    return forward_one(m, replica, slice, rows);
+}
+
+int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    int rc = check_batch(m, full);
+    if (rc != CCS_OK) return rc;
+    hipStream_t cs = (hipStream_t)caller_stream;
+    const int k = m->k;
+    const long long n = full->n_seqs;
+    if (n == 0) return CCS_OK;
+    const bool prefill = full->mode == CCS_PREFILL;
+    const long long rows_per_seq = prefill ? full->seq_pad : 1;
+    const long long full_rows = n * rows_per_seq;
+    const Dims &d = m->dims;
+    const size_t esz = d.esz;
+    const size_t x_row = (m->desc.kind == CCS_LINEAR ? (size_t)d.in_f : (size_t)d.H) * esz;
+    const size_t y_row = (m->desc.kind == CCS_LINEAR ? (size_t)d.out_f : (size_t)d.H) * esz;
+    const size_t cache_seq = (size_t)d.nkv * (size_t)full->cache_cap * d.d * esz;
+
+    CCS_HIP(hipEventRecord(m->fork, cs));
+    for (int j = 0; j < k; ++j) {
+        const long long lo = j * n / k, hi = (j + 1) * n / k;  // slice j = [floor(jn/k), floor((j+1)n/k))
+        if (hi == lo) continue;
+        Replica &R = m->rep[j];
+        ccs_batch s = *full;
+        s.n_seqs = (int32_t)(hi - lo);
+        s.x = (const char *)full->x + (size_t)lo * rows_per_seq * x_row;
+        s.y = (char *)full->y + (size_t)lo * rows_per_seq * y_row;
+        if (full->lens_host) s.lens_host = full->lens_host + lo;
+        if (full->lens_dev) s.lens_dev = full->lens_dev + lo;
+        if (full->k_cache) {
+            s.k_cache = (char *)full->k_cache + (size_t)lo * cache_seq;
+            s.v_cache = (char *)full->v_cache + (size_t)lo * cache_seq;
+        }
+        if (R.stream != cs) CCS_HIP(hipStreamWaitEvent(R.stream, m->fork, 0));
+        rc = forward_one(m, j, &s, full_rows);
+        if (rc != CCS_OK) return rc;
+        if (R.stream != cs) {
+            CCS_HIP(hipEventRecord(R.done, R.stream));
+            CCS_HIP(hipStreamWaitEvent(cs, R.done, 0));
+        }
+    }
+    return CCS_OK;
+}
+
+int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *stream)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    if (replica < 0 || replica >= CCS_MAX_REPLICAS) return fail(CCS_EINVAL, "replica index %d out of range", replica);
+    if (replica >= m->k) return fail(CCS_ESTATE, "replica %d is not instantiated", replica);
+    if (!dst_arena || ((uintptr_t)dst_arena & 255)) return fail(CCS_EINVAL, "dst_arena is null or not 256-byte aligned");
+    Replica &R = m->rep[replica];
+    if (dst_arena == R.arena) return fail(CCS_EINVAL, "dst_arena is the replica's own arena");
+    hipStream_t st = (hipStream_t)stream;
+    if (st != R.stream) {
+        // order after everything the replica has enqueued so far (its pack/clone included)
+        CCS_HIP(hipEventRecord(R.done, R.stream));
+        CCS_HIP(hipStreamWaitEvent(st, R.done, 0));
+    }
+    CCS_HIP(ccs::launch_clone(dst_arena, R.arena, m->ap.total, st));
+    return CCS_OK;
+}
+
+int ccs_module_migrate(ccs_module *m, int32_t replica, void *dst_arena, void *stream)
+{
+    int rc = ccs_module_copy(m, replica, dst_arena, stream);
+    if (rc != CCS_OK) return rc;
+    Replica &R = m->rep[replica];
+    hipStream_t st = (hipStream_t)stream;
+    CCS_HIP(hipEventRecord(R.ready, st));
+    if (st != R.stream) CCS_HIP(hipStreamWaitEvent(R.stream, R.ready, 0));
+    R.arena = dst_arena;
+    return CCS_OK;
+}
+
+int ccs_cache_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (bytes == 0) return CCS_OK;
+    if (!dst || !src) return fail(CCS_EINVAL, "dst / src is null");
+    if (((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return fail(CCS_EINVAL, "dst / src must be 16-byte aligned");
+    const char *s = (const char *)src;
+    char *t = (char *)dst;
+    if ((s < t + bytes) && (t < s + bytes)) return fail(CCS_EINVAL, "src and dst overlap");
+    CCS_HIP(ccs::launch_clone(dst, src, bytes, (hipStream_t)stream));
+    return CCS_OK;
+}
+
+int ccs_module_arena(const ccs_module *m, int32_t replica, void **arena_out)
+{
+    if (!m || !arena_out) return fail(CCS_EINVAL, "null argument");
+    if (replica < 0 || replica >= m->k) return fail(CCS_ESTATE, "replica %d is not instantiated", replica);
+    *arena_out = m->rep[replica].arena;
+    return CCS_OK;
+}
+
+int ccs_module_sync(ccs_module *m)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    for (int j = 0; j < m->k; ++j) CCS_HIP(hipStreamSynchronize(m->rep[j].stream));
+    return CCS_OK;
+}
+
+int ccs_module_destroy(ccs_module *m)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    for (int j = 0; j < m->k; ++j) {
+        Replica &R = m->rep[j];
+        (void)hipStreamSynchronize(R.stream);
+        if (R.ready) (void)hipEventDestroy(R.ready);
+        if (R.done) (void)hipEventDestroy(R.done);
+    }
+    if (m->fork) (void)hipEventDestroy(m->fork);
+    delete m;
+    return CCS_OK;
+}
+
+}  // extern "C"

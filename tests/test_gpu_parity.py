@@ -1,0 +1,265 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded
+inputs, and k-replica runs against k = 1 bit for bit.
+
+Bars: max|y - ref| / max|ref| over valid rows <= 2e-2 (bf16), <= 1e-4 (fp32); replica splits
+bit-identical to the unsplit run."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from paper_2507_18006_amd import binding as B
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "f32": 1e-4}
+C = workloads.CONFIGS
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def run_case(cfg, ks, seed=0, seqs=None):
+    """Oracle once, GPU at every k: parity for each, bit-exactness across k."""
+    say(f"[case] {cfg.name} kind={cfg.kind} mode={cfg.mode} n_seqs={cfg.n_seqs} seq_pad={cfg.seq_pad} ks={ks} seed={seed}")
+    w = workloads.make_weights(cfg, seed)
+    inp = workloads.make_inputs(cfg, seed)
+    ref = U.oracle_forward(cfg, seed, w, inp, seqs=seqs)
+    mask = None
+    if cfg.mode == "prefill":
+        lens = inp.lens if seqs is None else inp.lens[seqs]
+        mask = U.valid_mask(cfg, lens)
+    ys = {}
+    for k in ks:
+        say(f"  [gpu] forward_split k={k}")
+        y = U.gpu_forward(cfg, k, seed, w, inp)
+        ys[k] = y
+        part = y if seqs is None else y[seqs]
+        err = U.rel_err(part, ref, mask)
+        say(f"  [gpu] k={k} rel_err={err:.3e}")
+        assert err <= TOL[cfg.dtype], f"{cfg.name} k={k}: rel err {err}"
+        assert np.isfinite(y).all()
+    full_mask = U.valid_mask(cfg, inp.lens) if cfg.mode == "prefill" else None
+    base = ys[ks[0]]
+    for k in ks[1:]:
+        a, b = (base, ys[k]) if full_mask is None else (base[full_mask], ys[k][full_mask])
+        assert np.array_equal(a, b), f"{cfg.name}: k={k} is not bit-identical to k={ks[0]}"
+    return ys
+
+
+# ---------------------------------------------------------------- BASELINE configs[0]: tiny fp32
+def test_c1_tiny_fp32_prefill():
+    run_case(C["C1"], [1, 2])
+
+
+def test_f32_ragged_prefill_and_decode_gqa():
+    cfg = workloads.scaled(C["C1"], n_q_heads=4, n_kv_heads=2, n_seqs=5, seq_pad=24, len_lo=3, len_hi=24)
+    run_case(cfg, [1, 2, 3], seed=3)
+    dec = workloads.scaled(cfg, mode="decode", n_seqs=7, seq_pad=1, len_lo=0, len_hi=40)
+    run_case(dec, [1, 2, 4], seed=4)
+
+
+# ---------------------------------------------------------------- scaled bf16 cases (several tiles + ragged tails)
+def test_bf16_decode_scaled_mha():
+    cfg = workloads.scaled(C["C2"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
+                           n_seqs=15, len_lo=200, len_hi=700)
+    run_case(cfg, [1, 2, 4], seed=1)          # 15 -> 7 + 8 and 3/4/4/4
+
+
+def test_bf16_decode_scaled_gqa():
+    for g, nkv in ((8, 2), (4, 2), (2, 4)):
+        cfg = workloads.scaled(C["C4"], hidden=1024, n_q_heads=g * nkv, n_kv_heads=nkv, intermediate=1792,
+                               n_seqs=9, len_lo=0, len_hi=530)
+        run_case(cfg, [1, 2], seed=2 + g)
+
+
+def test_bf16_prefill_scaled_ragged():
+    cfg = workloads.scaled(C["C3"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
+                           n_seqs=5, seq_pad=80, len_lo=17, len_hi=80)
+    run_case(cfg, [1, 2], seed=5)             # 400 rows: two 256-row tiles with a ragged tail
+    gqa = workloads.scaled(cfg, n_kv_heads=2, n_seqs=3, seq_pad=48, len_lo=1, len_hi=48)
+    run_case(gqa, [1, 3], seed=6)
+
+
+def test_bf16_linear_rows_across_variants():
+    base = workloads.scaled(C["C5"], in_features=2752, out_features=1024)
+    for n in (1, 15, 64, 65, 130, 300):       # weight-streaming up to 64 rows, tiled above
+        run_case(workloads.scaled(base, n_seqs=n), [1, 2, 4], seed=n)
+
+
+# ---------------------------------------------------------------- full-size configs
+def test_c2_llama7b_decode_full():
+    run_case(C["C2"], [1, 2, 4])
+
+
+def test_c4_llama70b_gqa_decode_full_and_clone():
+    run_case(C["C4"], [1, 2])
+
+
+def test_c3_llama13b_prefill_full_sampled_sequences():
+    cfg = C["C3"]
+    inp = workloads.make_inputs(cfg, 0)
+    short = int(np.argmin(inp.lens))          # the oracle finishes the shortest sequence in seconds
+    run_case(cfg, [1, 2], seqs=slice(short, short + 1))
+
+
+def test_c5_down_proj_bursty_full():
+    cfg = C["C5"]
+    counts = workloads.bursty_token_counts(0)
+    w = workloads.make_weights(cfg, 0)
+    m = U.make_module(cfg, w, max_seqs=max(counts))
+    try:
+        m.replicate(4)
+        # every replica count on a sample of batch sizes from the seeded stream (small, medium, burst)
+        picks = sorted(set(counts))[:: max(1, len(set(counts)) // 6)][:6] + [max(counts)]
+        for n in picks:
+            c = workloads.scaled(cfg, n_seqs=n)
+            inp = workloads.make_inputs(c, seed=n)
+            rows = np.unique(np.linspace(0, n - 1, min(n, 24)).astype(int))
+            import oracle
+            ref = oracle.linear(inp.x[rows], w["w"])
+            outs = []
+            for k in (1, 2, 4):
+                say(f"[case] C5 n={n} k={k}")
+                m.replicate(k)
+                db = U.DeviceBatch(m, c, inp)
+                m.forward_split(db.batch)
+                y = db.out()
+                assert U.rel_err(y[rows], ref) <= TOL["bf16"]
+                outs.append(y)
+            assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    finally:
+        m.destroy()
+
+
+# ---------------------------------------------------------------- cache append, prefill -> decode
+def test_decode_appends_rotated_key_and_value_to_cache():
+    cfg = workloads.scaled(C["C2"], hidden=512, n_q_heads=4, n_kv_heads=4, intermediate=1024,
+                           n_seqs=5, len_lo=0, len_hi=300)
+    w = workloads.make_weights(cfg, 7)
+    inp = workloads.make_inputs(cfg, 7)
+    ref, kc, vc = U.oracle_forward(cfg, 7, w, inp, return_caches=True)
+    y, gk, gv = U.gpu_forward(cfg, 2, 7, w, inp, return_caches=True)
+    assert U.rel_err(y, ref) <= TOL["bf16"]
+    for b, L in enumerate(inp.lens):
+        assert np.array_equal(gk[b, :, :L], inp.k_cache[b, :, :L])      # history untouched
+        assert U.rel_err(gk[b, :, L], kc[b, :, L]) <= TOL["bf16"]
+        assert U.rel_err(gv[b, :, L], vc[b, :, L]) <= TOL["bf16"]
+        assert not gk[b, :, L + 1:].any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prefill_fills_cache_then_decode_continues(dtype):
+    import oracle
+    if dtype == "f32":
+        cfg = workloads.scaled(C["C1"], n_seqs=3, seq_pad=12, len_lo=4, len_hi=12)
+    else:
+        cfg = workloads.scaled(C["C3"], hidden=512, n_q_heads=4, n_kv_heads=2, intermediate=1024,
+                               n_seqs=3, seq_pad=40, len_lo=9, len_hi=40)
+    w = workloads.make_weights(cfg, 8)
+    inp = workloads.make_inputs(cfg, 8)
+    cap = cfg.seq_pad + 8
+    d = U.oracle_desc(cfg)
+    kc = np.zeros((cfg.n_seqs, cfg.n_kv_heads, cap, cfg.head_dim), np.float32)
+    vc = np.zeros_like(kc)
+    oracle.decoder_layer_prefill(d, w, inp.x, inp.lens, kc, vc)
+    dcfg = workloads.scaled(cfg, mode="decode", seq_pad=1)
+    xd = workloads.make_inputs(workloads.scaled(dcfg, len_lo=0, len_hi=0), 9).x
+    ref = oracle.decoder_layer_decode(d, w, xd, inp.lens, kc, vc)
+
+    m = U.make_module(cfg, w, max_cap=cap)
+    try:
+        m.replicate(2)
+        pb = U.DeviceBatch(m, cfg, inp, with_cache=cap)
+        m.forward_split(pb.batch)
+        db = U.DeviceBatch(m, dcfg, workloads.Inputs(x=xd, lens=inp.lens, k_cache=None, v_cache=None))
+        db.k, db.v = pb.k, pb.v
+        db.batch = m.batch(B.CCS_DECODE, db.x, db.y, db.lens_host, db.lens_dev, db.k, db.v)
+        m.forward_split(db.batch)
+        y = db.out()
+        assert U.rel_err(y, ref) <= TOL[dtype]
+        assert U.rel_err(pb.k.float().cpu().numpy(), kc) <= TOL[dtype]
+    finally:
+        m.destroy()
+
+
+# ---------------------------------------------------------------- clone / copy / migrate
+def test_replica_clone_copy_and_migrate_are_byte_exact():
+    cfg = workloads.scaled(C["C2"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752, n_seqs=4,
+                           len_lo=10, len_hi=50)
+    w = workloads.make_weights(cfg, 11)
+    inp = workloads.make_inputs(cfg, 11)
+    m = U.make_module(cfg, w)
+    try:
+        m.replicate(3)
+        m.sync()
+        for j in (1, 2):
+            assert torch.equal(m.arenas[0][:m.arena_bytes], m.arenas[j][:m.arena_bytes])
+        db = U.DeviceBatch(m, cfg, inp)
+        m.forward_split(db.batch)
+        y0 = db.out()
+        spare = m.copy(1)
+        torch.cuda.synchronize()
+        assert torch.equal(spare[:m.arena_bytes], m.arenas[0][:m.arena_bytes])
+        old = m.migrate(0)
+        assert m.arena_ptr(0) == m.arenas[0].data_ptr() != old.data_ptr()
+        old.zero_()                              # the old copy is gone: results must not change
+        db2 = U.DeviceBatch(m, cfg, inp)
+        m.forward_split(db2.batch)
+        assert np.array_equal(db2.out(), y0)
+        # KV cache travels with its layer
+        dst = torch.empty_like(db.k)
+        B.cache_copy(dst, db.k)
+        torch.cuda.synchronize()
+        assert torch.equal(dst, db.k)
+        m.replicate(1)
+        assert m.replicas() == 1
+    finally:
+        m.destroy()
+
+
+# ---------------------------------------------------------------- edge cases and error paths
+def test_empty_batches_more_replicas_than_sequences_and_errors():
+    cfg = workloads.scaled(C["C2"], hidden=512, n_q_heads=4, n_kv_heads=4, intermediate=1024, n_seqs=3,
+                           len_lo=0, len_hi=20)
+    w = workloads.make_weights(cfg, 12)
+    inp = workloads.make_inputs(cfg, 12)
+    ref = U.oracle_forward(cfg, 12, w, inp)
+    m = U.make_module(cfg, w)
+    try:
+        m.replicate(8)                           # k > n: some slices are empty
+        db = U.DeviceBatch(m, cfg, inp)
+        m.forward_split(db.batch)
+        assert U.rel_err(db.out(), ref) <= TOL["bf16"]
+        empty = m.batch(B.CCS_DECODE, db.x[:0], db.y[:0], db.lens_host[:0], db.lens_dev[:0], db.k[:0], db.v[:0])
+        m.forward_split(empty)                   # n = 0 is a no-op
+        m.forward(0, empty)
+        with pytest.raises(B.CcsError) as e:
+            m.forward(9, db.batch)
+        assert e.value.status == B.CCS_ESTATE
+        with pytest.raises(B.CcsError) as e:
+            m.forward(-1, db.batch)
+        assert e.value.status == B.CCS_EINVAL
+        bad = db.lens_host.clone(); bad[0] = db.k.shape[2]
+        with pytest.raises(B.CcsError) as e:
+            m.forward(0, m.batch(B.CCS_DECODE, db.x, db.y, bad, db.lens_dev, db.k, db.v))
+        assert e.value.status == B.CCS_EINVAL
+        with pytest.raises(B.CcsError) as e:
+            m.forward(0, m.batch(B.CCS_ROWS, db.x, db.y))
+        assert e.value.status == B.CCS_EINVAL
+        big = workloads.scaled(cfg, n_seqs=64)
+        binp = workloads.make_inputs(big, 1)
+        bdb = U.DeviceBatch(m, big, binp)
+        with pytest.raises(B.CcsError) as e:
+            m.forward(0, bdb.batch)              # workspace was sized for 3 sequences
+        assert e.value.status == B.CCS_ENOMEM
+        with pytest.raises(B.CcsError):
+            m.replicate(17)
+        m.sync()
+    finally:
+        m.destroy()

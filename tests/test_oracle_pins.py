@@ -11,7 +11,7 @@ import torch.nn.functional as F
 
 import oracle
 import workloads
-from conftest import read_golden
+from tests.conftest import read_golden
 
 RNG = np.random.default_rng(1234)
 

@@ -175,6 +175,35 @@ int ccs_cache_copy(void *dst, const void *src, size_t bytes, void *stream);
 /* Device address of replica `replica`'s arena (for tests and for freeing after migrate). */
 int ccs_module_arena(const ccs_module *m, int32_t replica, void **arena_out);
 
+/* Kernels of one replica forward, for per-kernel device timing.  The weight-streaming GEMM
+ * variant is two launches (main + REDUCE); the LDS-tiled variant only reports the main stage.
+ * A projection module reports PACK_X and GEMM_DOWN(+_REDUCE). */
+typedef enum ccs_stage {
+    CCS_ST_RMSNORM1 = 0,
+    CCS_ST_GEMM_QKV = 1, CCS_ST_GEMM_QKV_REDUCE = 2,
+    CCS_ST_ROPE = 3,
+    CCS_ST_ATTN = 4, CCS_ST_ATTN_COMBINE = 5,
+    CCS_ST_GEMM_O = 6, CCS_ST_GEMM_O_REDUCE = 7,
+    CCS_ST_RMSNORM2 = 8,
+    CCS_ST_GEMM_GU = 9, CCS_ST_GEMM_GU_REDUCE = 10,
+    CCS_ST_GEMM_DOWN = 11, CCS_ST_GEMM_DOWN_REDUCE = 12,
+    CCS_ST_PACK_X = 13,
+    CCS_ST_CLONE = 14,
+    CCS_N_STAGES = 15
+} ccs_stage;
+
+/* Per-kernel timing (the paper's Monitor gathers latencies with event timers, Section 5
+ * "Metrics Monitor").  While bit s of stage_mask is set, every launch of stage s is bracketed
+ * by a pair of HIP events on the stream it is enqueued on; 0 switches timing off (default).
+ * Recording stops silently after 65536 unread pairs per replica. */
+int ccs_module_profile(ccs_module *m, uint32_t stage_mask);
+
+/* Wait for the recorded pairs of `replica`, and return per stage the summed kernel time in
+ * milliseconds (ms_sum, host, CCS_N_STAGES doubles) and the number of launches (count, host,
+ * CCS_N_STAGES int64) accumulated since the last reset; reset != 0 clears them afterwards. */
+int ccs_module_profile_read(ccs_module *m, int32_t replica, double *ms_sum, int64_t *count,
+                            int32_t reset);
+
 /* Block the host until every stream of the module has drained. */
 int ccs_module_sync(ccs_module *m);
 

@@ -16,6 +16,10 @@ CCS_DECODER_LAYER, CCS_LINEAR = 0, 1
 CCS_F32, CCS_BF16 = 0, 1
 CCS_PREFILL, CCS_DECODE, CCS_ROWS = 0, 1, 2
 CCS_MAX_REPLICAS = 16
+STAGES = ("rmsnorm1", "gemm_qkv", "gemm_qkv_reduce", "rope", "attn", "attn_combine", "gemm_o",
+          "gemm_o_reduce", "rmsnorm2", "gemm_gu", "gemm_gu_reduce", "gemm_down", "gemm_down_reduce",
+          "pack_x", "clone")
+CCS_N_STAGES = len(STAGES)
 _STATUS = {0: "CCS_OK", -1: "CCS_EINVAL", -2: "CCS_ESTATE", -3: "CCS_ENOMEM",
            -4: "CCS_EUNSUPPORTED", -5: "CCS_EHIP"}
 
@@ -23,7 +27,7 @@ EXPORTS = (
     "ccs_module_arena_bytes", "ccs_module_workspace_bytes", "ccs_module_create",
     "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
     "ccs_module_forward_split", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
-    "ccs_module_arena", "ccs_module_sync", "ccs_module_destroy", "ccs_last_error", "ccs_version",
+    "ccs_module_arena", "ccs_module_profile", "ccs_module_profile_read", "ccs_module_sync", "ccs_module_destroy", "ccs_last_error", "ccs_version",
 )
 
 
@@ -87,13 +91,16 @@ def lib():
     L.ccs_module_migrate.argtypes = [vp, i32, vp, vp]
     L.ccs_cache_copy.argtypes = [vp, vp, sz, vp]
     L.ccs_module_arena.argtypes = [vp, i32, ctypes.POINTER(vp)]
+    L.ccs_module_profile.argtypes = [vp, ctypes.c_uint32]
+    L.ccs_module_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(ctypes.c_int64), i32]
     L.ccs_module_sync.argtypes = [vp]
     L.ccs_module_destroy.argtypes = [vp]
     L.ccs_last_error.restype = ctypes.c_char_p
     L.ccs_version.restype = ctypes.c_char_p
     for name in ("ccs_module_create", "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
                  "ccs_module_forward_split", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
-                 "ccs_module_arena", "ccs_module_sync", "ccs_module_destroy"):
+                 "ccs_module_arena", "ccs_module_profile", "ccs_module_profile_read", "ccs_module_sync", "ccs_module_destroy"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -252,6 +259,24 @@ class Module:
         p = ctypes.c_void_p()
         _check(self.L.ccs_module_arena(self.handle, replica, ctypes.byref(p)))
         return int(p.value)
+
+    # -- per-kernel timing ------------------------------------------------------------------------
+    def profile(self, stages=None):
+        """Time the named stages (None: all; empty: off) with HIP events on the replica streams."""
+        if stages is None:
+            mask = (1 << CCS_N_STAGES) - 1
+        else:
+            mask = 0
+            for s in stages:
+                mask |= 1 << STAGES.index(s)
+        _check(self.L.ccs_module_profile(self.handle, mask))
+
+    def profile_read(self, replica: int = 0, reset: bool = True) -> dict:
+        """{stage: (total_ms, launches)} for the stages that ran."""
+        ms = (ctypes.c_double * CCS_N_STAGES)()
+        cnt = (ctypes.c_int64 * CCS_N_STAGES)()
+        _check(self.L.ccs_module_profile_read(self.handle, replica, ms, cnt, 1 if reset else 0))
+        return {STAGES[i]: (float(ms[i]), int(cnt[i])) for i in range(CCS_N_STAGES) if cnt[i]}
 
     def sync(self):
         _check(self.L.ccs_module_sync(self.handle))

@@ -282,9 +282,9 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restri
     out[packed_index(b, h * 128 + c, (nq * 128) >> 5)] = f2bf(a / L);
 }
 
-hipError_t launch_attn_decode(const void *qkv, void *out_packed, float *partials, int n_seqs,
-                              int nq, int nkv, const int32_t *lens_dev, const void *k_cache,
-                              const void *v_cache, int cap, hipStream_t st)
+hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs, int nq, int nkv,
+                                   const int32_t *lens_dev, const void *k_cache,
+                                   const void *v_cache, int cap, hipStream_t st)
 {
     if (n_seqs <= 0) return hipSuccess;
     const int nchunks = dec_chunks(cap), G = nq / nkv;
@@ -301,8 +301,14 @@ hipError_t launch_attn_decode(const void *qkv, void *out_packed, float *partials
         default: return hipErrorInvalidValue;
     }
 #undef CCS_DEC
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, int n_seqs, int nq,
+                                      const int32_t *lens_dev, int cap, hipStream_t st)
+{
+    if (n_seqs <= 0) return hipSuccess;
+    const int nchunks = dec_chunks(cap);
     hipLaunchKernelGGL(attn_combine_kernel, dim3(n_seqs * nq), dim3(128), 0, st, partials, (bf16_t *)out_packed,
                        nq, lens_dev, nchunks);
     return hipGetLastError();

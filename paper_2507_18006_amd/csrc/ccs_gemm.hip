@@ -217,8 +217,8 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restr
     }
 }
 
-hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, int epi,
-                              const void *res, void *out, int M, int N, int K, hipStream_t st)
+hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
+                                   int K, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows) return hipErrorInvalidValue;
@@ -237,8 +237,14 @@ hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, i
         default: CCS_SK(4); break;
     }
 #undef CCS_SK
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,
+                                     int M, int N, int K, hipStream_t st)
+{
+    if (M <= 0) return hipSuccess;
+    const int S = skinny_segments(N, K);
     const int ncols = (epi == EPI_SWIGLU_PACKED) ? N / 2 : N;
     const int total = M * (ncols / 4);
     hipLaunchKernelGGL(skinny_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, partials, S, M, N,

@@ -46,10 +46,12 @@ int skinny_segments(int N, int K);
 size_t skinny_partial_bytes(int M, int N, int K);
 // Largest row count the weight-streaming variant accepts in one launch.
 constexpr int kSkinnyMaxRows = 64;
-// bf16 weight-streaming GEMM for M <= kSkinnyMaxRows rows: partial sums per K segment into
-// `partials` (fp32 [S, M, N]) followed by a fixed-order reduction with the epilogue.
-hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, int epi,
-                              const void *res, void *out, int M, int N, int K, hipStream_t st);
+// bf16 weight-streaming GEMM for M <= kSkinnyMaxRows rows, two launches: partial sums per K
+// segment into `partials` (fp32 [S, M, N]), then a fixed-order reduction with the epilogue.
+hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
+                                   int K, hipStream_t st);
+hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,
+                                     int M, int N, int K, hipStream_t st);
 // bf16 LDS-tiled MFMA GEMM for any M; Xp must be readable up to M rounded up to 256 rows.
 hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void *res, void *out,
                              int M, int N, int K, hipStream_t st);
@@ -65,8 +67,10 @@ hipError_t launch_attn_generic(int dtype, const void *qkv, void *out, int rows, 
                                const void *k_cache, const void *v_cache, int cap, hipStream_t st);
 // bf16, head_dim 128 decode attention with split-KV partials (fp32) and an ordered combine.
 size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap);
-hipError_t launch_attn_decode(const void *qkv, void *out_packed, float *partials, int n_seqs,
-                              int nq, int nkv, const int32_t *lens_dev, const void *k_cache,
-                              const void *v_cache, int cap, hipStream_t st);
+hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs, int nq, int nkv,
+                                   const int32_t *lens_dev, const void *k_cache,
+                                   const void *v_cache, int cap, hipStream_t st);
+hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, int n_seqs, int nq,
+                                      const int32_t *lens_dev, int cap, hipStream_t st);
 
 }  // namespace ccs

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "../../include/cocoserve_mi.h"
 #include "ccs_kernels.h"
@@ -144,7 +145,21 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
     return p;
 }
 
+// Per-kernel device timing with HIP events on the replica's own stream (the paper's Monitor
+// collects latencies with event timers, Section 5 "Metrics Monitor").
+struct ProfPair {
+    hipEvent_t a, b;
+    int stage;
+};
+struct Prof {
+    std::vector<ProfPair> pending;
+    std::vector<ProfPair> pool;
+    double ms[CCS_N_STAGES] = {0};
+    int64_t count[CCS_N_STAGES] = {0};
+};
+
 struct Replica {
+    Prof *prof = nullptr;
     void *arena = nullptr;
     void *ws = nullptr;
     size_t ws_bytes = 0;
@@ -162,6 +177,7 @@ struct ccs_module {
     int k = 0;
     Replica rep[CCS_MAX_REPLICAS];
     hipEvent_t fork = nullptr;
+    uint32_t prof_mask = 0;
 };
 
 namespace {
@@ -171,6 +187,48 @@ int make_event(hipEvent_t *ev)
     CCS_HIP(hipEventCreateWithFlags(ev, hipEventDisableTiming));
     return CCS_OK;
 }
+
+constexpr size_t kProfMaxPending = 1u << 16;
+
+ProfPair *prof_begin(ccs_module *m, Replica &R, int stage, hipStream_t st)
+{
+    if (!(m->prof_mask & (1u << stage))) return nullptr;
+    if (!R.prof) R.prof = new (std::nothrow) Prof();
+    if (!R.prof || R.prof->pending.size() >= kProfMaxPending) return nullptr;
+    ProfPair p{nullptr, nullptr, stage};
+    if (!R.prof->pool.empty()) {
+        p = R.prof->pool.back();
+        p.stage = stage;
+        R.prof->pool.pop_back();
+    } else if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) {
+        return nullptr;
+    }
+    if (hipEventRecord(p.a, st) != hipSuccess) return nullptr;
+    R.prof->pending.push_back(p);
+    return &R.prof->pending.back();
+}
+
+void prof_end(ProfPair *p, hipStream_t st)
+{
+    if (p) (void)hipEventRecord(p->b, st);
+}
+
+void prof_free(Replica &R)
+{
+    if (!R.prof) return;
+    for (auto &p : R.prof->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+    for (auto &p : R.prof->pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+    delete R.prof;
+    R.prof = nullptr;
+}
+
+#define CCS_STAGE(sid, expr)                              \
+    do {                                                  \
+        ProfPair *pp__ = prof_begin(m, R, (sid), st);     \
+        hipError_t se__ = (expr);                         \
+        prof_end(pp__, st);                               \
+        if (se__ != hipSuccess) return fail(CCS_EHIP, "%s: %s", #expr, hipGetErrorString(se__)); \
+    } while (0)
 
 int check_batch(const ccs_module *m, const ccs_batch *b)
 {
@@ -228,16 +286,18 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     if (D.kind == CCS_LINEAR) {
         const int M = b->n_seqs;
         if (!bf) {
-            CCS_HIP(launch_gemm_f32((const float *)b->x, (const float *)(A + m->ap.w), nullptr, (float *)b->y, M, d.out_f, d.in_f, st));
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)b->x, (const float *)(A + m->ap.w), nullptr, (float *)b->y, M, d.out_f, d.in_f, st));
             return CCS_OK;
         }
         WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false);
         if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
-        CCS_HIP(launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, st));
-        if (skinny)
-            CCS_HIP(launch_gemm_skinny(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
-        else
-            CCS_HIP(launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+        CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, st));
+        if (skinny) {
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, st));
+            CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_gemm_skinny_reduce((const float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+        } else {
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+        }
         return CCS_OK;
     }
 
@@ -248,34 +308,42 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
 
-    CCS_HIP(launch_rmsnorm(dt, b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+    CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm(dt, b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
     if (bf) {
-        auto gemm = [&](size_t woff, size_t xoff, int epi, const void *res, void *out, int N, int K) -> hipError_t {
-            return skinny ? launch_gemm_skinny(A + woff, ws + xoff, (float *)(ws + p.scratch), epi, res, out, T, N, K, st)
-                          : launch_gemm_tiled(A + woff, ws + xoff, epi, res, out, T, N, K, st);
-        };
-        CCS_HIP(gemm(m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H));
-        CCS_HIP(launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        if (decode)
-            CCS_HIP(launch_attn_decode(ws + p.qkv, ws + p.a, (float *)(ws + p.scratch), b->n_seqs, d.nq, d.nkv, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        else
-            CCS_HIP(launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, 0, seq_pad, b->lens_dev, nullptr, nullptr, 0, st));
-        CCS_HIP(gemm(m->ap.o, p.a, EPI_STORE_RM, b->x, ws + p.x1, d.H, d.QD));
-        CCS_HIP(launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
-        CCS_HIP(gemm(m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H));
-        CCS_HIP(gemm(m->ap.dn, p.u, EPI_STORE_RM, ws + p.x1, b->y, d.H, d.I));
+        float *scratch = (float *)(ws + p.scratch);
+        // one projection: weight-streaming (two launches) or LDS-tiled (one launch)
+#define CCS_GEMM(sid, woff, xoff, epi, res, out, N, K)                                                        \
+    do {                                                                                                      \
+        if (skinny) {                                                                                         \
+            CCS_STAGE(sid, launch_gemm_skinny_main(A + (woff), ws + (xoff), scratch, T, (N), (K), st));        \
+            CCS_STAGE((sid) + 1, launch_gemm_skinny_reduce(scratch, (epi), (res), (out), T, (N), (K), st));    \
+        } else {                                                                                              \
+            CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), st));  \
+        }                                                                                                     \
+    } while (0)
+        CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
+        CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        if (decode) {
+            CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+            CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, b->lens_dev, b->cache_cap, st));
+        } else {
+            CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, 0, seq_pad, b->lens_dev, nullptr, nullptr, 0, st));
+        }
+        CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, b->x, ws + p.x1, d.H, d.QD);
+        CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+        CCS_GEMM(CCS_ST_GEMM_GU, m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H);
+        CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, ws + p.x1, b->y, d.H, d.I);
+#undef CCS_GEMM
     } else {
-        const float *Af = (const float *)A;
         auto W = [&](size_t off) { return (const float *)(A + off); };
-        (void)Af;
-        CCS_HIP(launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
-        CCS_HIP(launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        CCS_HIP(launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        CCS_HIP(launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)b->x, (float *)(ws + p.x1), T, d.H, d.QD, st));
-        CCS_HIP(launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
-        CCS_HIP(launch_gemm_f32((const float *)(ws + p.h), W(m->ap.gu), nullptr, (float *)(ws + p.gu), T, 2 * d.I, d.H, st));
-        CCS_HIP(launch_swiglu_f32((const float *)(ws + p.gu), (float *)(ws + p.u), T, d.I, st));
-        CCS_HIP(launch_gemm_f32((const float *)(ws + p.u), W(m->ap.dn), (const float *)(ws + p.x1), (float *)b->y, T, d.H, d.I, st));
+        CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
+        CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)b->x, (float *)(ws + p.x1), T, d.H, d.QD, st));
+        CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+        CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.gu), nullptr, (float *)(ws + p.gu), T, 2 * d.I, d.H, st));
+        CCS_STAGE(CCS_ST_GEMM_GU_REDUCE, launch_swiglu_f32((const float *)(ws + p.gu), (float *)(ws + p.u), T, d.I, st));
+        CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)(ws + p.u), W(m->ap.dn), (const float *)(ws + p.x1), (float *)b->y, T, d.H, d.I, st));
     }
     return CCS_OK;
 }
@@ -401,6 +469,7 @@ int ccs_module_replicate(ccs_module *m, int32_t k, void *const *arenas, void *co
             CCS_HIP(hipStreamSynchronize(R.stream));
             if (R.ready) (void)hipEventDestroy(R.ready);
             if (R.done) (void)hipEventDestroy(R.done);
+            prof_free(R);
             R = Replica();
         }
         m->k = k;
@@ -424,7 +493,10 @@ int ccs_module_replicate(ccs_module *m, int32_t k, void *const *arenas, void *co
         rc = make_event(&R.done);
         if (rc != CCS_OK) return rc;
         CCS_HIP(hipStreamWaitEvent(R.stream, m->rep[0].ready, 0));
-        CCS_HIP(ccs::launch_clone(R.arena, m->rep[0].arena, m->ap.total, R.stream));
+        {
+            hipStream_t st = R.stream;
+            CCS_STAGE(CCS_ST_CLONE, ccs::launch_clone(R.arena, m->rep[0].arena, m->ap.total, st));
+        }
         CCS_HIP(hipEventRecord(R.ready, R.stream));
         m->rep[j] = R;
         m->k = j + 1;
@@ -507,7 +579,7 @@ int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *strea
         CCS_HIP(hipEventRecord(R.done, R.stream));
         CCS_HIP(hipStreamWaitEvent(st, R.done, 0));
     }
-    CCS_HIP(ccs::launch_clone(dst_arena, R.arena, m->ap.total, st));
+    CCS_STAGE(CCS_ST_CLONE, ccs::launch_clone(dst_arena, R.arena, m->ap.total, st));
     return CCS_OK;
 }
 
@@ -543,6 +615,37 @@ int ccs_module_arena(const ccs_module *m, int32_t replica, void **arena_out)
     return CCS_OK;
 }
 
+int ccs_module_profile(ccs_module *m, uint32_t stage_mask)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    if (stage_mask >> CCS_N_STAGES) return fail(CCS_EINVAL, "stage_mask has bits beyond CCS_N_STAGES");
+    m->prof_mask = stage_mask;
+    return CCS_OK;
+}
+
+int ccs_module_profile_read(ccs_module *m, int32_t replica, double *ms_sum, int64_t *count, int32_t reset)
+{
+    if (!m || !ms_sum || !count) return fail(CCS_EINVAL, "null argument");
+    if (replica < 0 || replica >= m->k) return fail(CCS_ESTATE, "replica %d is not instantiated", replica);
+    Replica &R = m->rep[replica];
+    for (int i = 0; i < CCS_N_STAGES; ++i) { ms_sum[i] = 0.0; count[i] = 0; }
+    if (!R.prof) return CCS_OK;
+    Prof &P = *R.prof;
+    for (auto &p : P.pending) {
+        CCS_HIP(hipEventSynchronize(p.b));
+        float ms = 0.f;
+        CCS_HIP(hipEventElapsedTime(&ms, p.a, p.b));
+        P.ms[p.stage] += ms;
+        P.count[p.stage] += 1;
+        P.pool.push_back(p);
+    }
+    P.pending.clear();
+    for (int i = 0; i < CCS_N_STAGES; ++i) { ms_sum[i] = P.ms[i]; count[i] = P.count[i]; }
+    if (reset)
+        for (int i = 0; i < CCS_N_STAGES; ++i) { P.ms[i] = 0.0; P.count[i] = 0; }
+    return CCS_OK;
+}
+
 int ccs_module_sync(ccs_module *m)
 {
     if (!m) return fail(CCS_EINVAL, "module is null");
@@ -558,6 +661,7 @@ int ccs_module_destroy(ccs_module *m)
         (void)hipStreamSynchronize(R.stream);
         if (R.ready) (void)hipEventDestroy(R.ready);
         if (R.done) (void)hipEventDestroy(R.done);
+        prof_free(R);
     }
     if (m->fork) (void)hipEventDestroy(m->fork);
     delete m;

@@ -25,8 +25,8 @@ METRIC = "decoder-layer tokens/s (7B shape, k=1/2/4 replicas); module replicate 
 
 # HBM bytes per launch of the decode-attention kernel on configs[1], from two `rocprofv3 --pmc`
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by the same counters on the clone kernel of known size;
-# see profiles/attn_decode_C2_pmc.md.  None until measured.
-MEASURED_TRAFFIC_BYTES = {"attn_decode@C2": None}
+# see profiles/decoder_layer_decode_C2_k1_pmc_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"attn_decode@C2": 540769864}
 
 
 def main():

@@ -1,12 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the module-replica hot path on ONE MI355X.
 
-A step = one replicated forward (split -> k replica forwards on their streams -> join) of the
-Llama-2-7B-shaped decoder layer in a decode step: batch 32, 1024 cached positions per sequence
-(BASELINE configs[1]), bf16, seeded synthetic tensors resident in HBM before timing starts.
-`value` is tokens/s at k = 1; k = 2 and k = 4 (same total batch) and the replica-clone rate are
-reported beside it.  The `roofline` object prices the dominant kernel (decode attention) against
-HBM; `cpu_baseline` is the CPU oracle timed on this machine's host cores.
+Default workload (the one BASELINE's metric is quoted on): a step = one replicated forward
+(split -> k replica forwards on their streams -> join) of the Llama-2-7B-shaped decoder layer in
+a decode step: batch 32, 1024 cached positions per sequence (BASELINE configs[1]), bf16, seeded
+synthetic tensors resident in HBM before timing starts.  `value` is tokens/s at k = 1; k = 2 and
+k = 4 (same total batch) and the replica-clone rate are reported beside it.  The `roofline`
+object prices the dominant kernel against its roofline (decode attention vs HBM; for the prefill
+workload the gate/up projection vs the bf16 MFMA peak); `cpu_baseline` is the CPU oracle timed
+on this machine's host cores.
+
+`--workload C3|C4|C5` runs the other BASELINE configs the same way (13B prefill, 70B GQA decode,
+bursty down-projection); they are reported in the design doc, not by the driver.
 
 Prints ONE JSON line.
 """
@@ -21,40 +26,39 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 METRIC = "decoder-layer tokens/s (7B shape, k=1/2/4 replicas); module replicate GB/s"
 
-# HBM bytes per launch of the decode-attention kernel on configs[1], from two `rocprofv3 --pmc`
-# runs (FETCH_SIZE, WRITE_SIZE) scaled by the same counters on the clone kernel of known size;
-# see profiles/decoder_layer_decode_C2_k1_pmc_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"attn_decode@C2": 540769864}
+# HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` runs (FETCH_SIZE,
+# WRITE_SIZE) scaled by the same counters on the clone kernel of known size; see
+# profiles/decoder_layer_decode_C2_k1_pmc_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"C2": 540769864}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--replicas", type=str, default="1,2,4")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (replicas are HIP streams of one MI355X, no "
-              "collectives); --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def time_events(torch, fn, reps):
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(reps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / reps * 1e-3
 
+
+def bench_layer(args, name):
     import numpy as np
     import torch
     import workloads
     from paper_2507_18006_amd import binding as B
-    if not os.path.exists(B.lib_path()):
-        import __graft_entry__
-        __graft_entry__.build()
     from tests import gpu_util as U
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
-    cfg = workloads.CONFIGS["C2"]
+    cfg = workloads.CONFIGS[name]
     K, W = args.steps, args.warmup
-    ks = [int(v) for v in args.replicas.split(",")]
+    ks = [int(v) for v in args.replicas.split(",") if int(v) in cfg.replicas or int(v) == 1]
+    decode = cfg.mode == "decode"
 
     w = workloads.make_weights(cfg, 0)
     inp = workloads.make_inputs(cfg, 0)
@@ -62,10 +66,19 @@ def main():
     db = U.DeviceBatch(m, cfg, inp)
     torch.cuda.synchronize()
 
-    n_tok = cfg.n_seqs
+    H, d, nq, nkv, I = cfg.hidden, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads, cfg.intermediate
+    lens = inp.lens.astype(np.int64)
+    n_tok = int(cfg.n_seqs if decode else lens.sum())          # tokens the step produces / processes
+    rows = cfg.n_seqs * (1 if decode else cfg.seq_pad)          # rows the kernels execute
     arena = m.arena_bytes
-    kv_bytes = int((inp.lens.astype(np.int64) + 1).sum()) * cfg.n_kv_heads * cfg.head_dim * 2 * 2
-    act_bytes = n_tok * (2 * cfg.hidden + 2 * cfg.n_kv_heads * cfg.head_dim) * 2   # x in, y out, new K/V out
+    shapes = {"gemm_qkv": ((nq + 2 * nkv) * d, H), "gemm_o": (H, nq * d), "gemm_gu": (2 * I, H), "gemm_down": (H, I)}
+    if decode:
+        kv_bytes = int((lens + 1).sum()) * nkv * d * 2 * 2
+        act_bytes = n_tok * (2 * H + 2 * nkv * d) * 2           # x in, y out, new K/V out
+        dominant = "attn"
+    else:
+        kv_bytes, act_bytes = 0, 2 * rows * H * 2
+        dominant = "gemm_gu"
 
     def timed(k, stages=()):
         m.replicate(k)
@@ -86,93 +99,184 @@ def main():
 
     per_k = {}
     # k = 1: the timed region also brackets the dominant kernel with HIP events on its stream
-    t1, prof1 = timed(1, ("attn",))
-    attn_ms, attn_n = prof1[0]["attn"]
-    attn_avg_s = attn_ms / attn_n * 1e-3
-    per_k[1] = t1
+    per_k[1], prof1 = timed(1, (dominant,))
+    dom_ms, dom_n = prof1[0][dominant]
+    dom_s = dom_ms / dom_n * 1e-3
     for k in ks:
         if k != 1:
             per_k[k], _ = timed(k)
 
     # per-kernel breakdown at k = 1 (separate pass: bracketing every launch perturbs the step)
     _, prof_all = timed(1, None)
-    breakdown_us = {s: round(ms / n * 1e3, 2) for s, (ms, n) in prof_all[0].items()}
+    breakdown = {}
+    for s, (ms, n) in prof_all[0].items():
+        us = ms / n * 1e3
+        e = {"us": round(us, 2)}
+        if s in shapes:
+            N, Kd = shapes[s]
+            e["TFLOPs"] = round(2.0 * rows * N * Kd / us / 1e6, 1)
+            e["weight_GBps"] = round(N * Kd * 2 / us / 1e3, 1)
+        if s == "attn" and decode:
+            e["GBps"] = round(kv_bytes / us / 1e3, 1)
+        breakdown[s] = e
 
     # replica clone: this layer's arena, and a 70B-layer-sized buffer (configs[3]: 1,711.3 MB)
     m.replicate(1)
     spare = torch.empty(arena, dtype=torch.uint8, device=U.DEV)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-
-    def time_clone(fn, reps=20):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        ev0.record()
-        for _ in range(reps):
-            fn()
-        ev1.record()
-        torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) / reps * 1e-3
-
-    t_clone = time_clone(lambda: m.copy_into(0, spare))
+    t_clone = time_events(torch, lambda: m.copy_into(0, spare), 20)
     big_bytes = 2 * (2 * 8192 * 8192 + 2 * 8192 * 1024 + 3 * 8192 * 28672)
     src_big = torch.empty(big_bytes, dtype=torch.uint8, device=U.DEV).random_(0, 255)
     dst_big = torch.empty_like(src_big)
-    t_clone_big = time_clone(lambda: B.cache_copy(dst_big, src_big))
+    t_clone_big = time_events(torch, lambda: B.cache_copy(dst_big, src_big), 20)
     assert torch.equal(dst_big[:: 4097], src_big[:: 4097])
     del src_big, dst_big, spare
 
     # check the timed configuration once against the oracle (sampled sequences keep it short)
     y = db.out()
-    sel = slice(0, 4)
-    ref = U.oracle_forward(cfg, 0, w, inp, seqs=sel)
-    parity = U.rel_err(y[sel], ref)
+    if decode:
+        sel = slice(0, 4)
+        parity = U.rel_err(y[sel], U.oracle_forward(cfg, 0, w, inp, seqs=sel))
+    else:
+        b0 = int(np.argmin(lens))
+        sel = slice(b0, b0 + 1)
+        parity = U.rel_err(y[sel], U.oracle_forward(cfg, 0, w, inp, seqs=sel), U.valid_mask(cfg, inp.lens[sel]))
 
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
+        if decode:
+            csel, ctok, what = slice(None), n_tok, f"full step ({cfg.n_seqs} sequences)"
+        else:
+            csel, ctok, what = sel, int(lens[sel].sum()), f"the shortest sequence ({int(lens[sel].sum())} tokens)"
         reps, t_cpu = 0, 0.0
         while reps < 8 and t_cpu < 12.0:
             t0 = time.perf_counter()
-            U.oracle_forward(cfg, 0, w, inp)
+            U.oracle_forward(cfg, 0, w, inp, seqs=csel)
             t_cpu += time.perf_counter() - t0
             reps += 1
-        cpu = {"value": round(n_tok / (t_cpu / reps), 2), "unit": "tokens/s", "cores": oracle.omp_threads(),
-               "kind": "oracle",
-               "sample": f"full configs[1] decode step (32 sequences x 1024 cached), mean of {reps} passes, fp64 arithmetic"}
-
+        cpu = {"value": round(ctok / (t_cpu / reps), 2), "unit": "tokens/s", "cores": oracle.omp_threads(),
+               "kind": "oracle", "sample": f"{what} of {cfg.name}, mean of {reps} passes, fp64 arithmetic"}
     m.destroy()
-    out = {
-        "metric": METRIC,
+
+    if decode:
+        roof = {"kernel": "attn_decode_kernel", "bound": "hbm",
+                "achieved": round(kv_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(kv_bytes / dom_s / 1e9 / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "algorithmic_bytes_per_launch": kv_bytes}
+    else:
+        N, Kd = shapes[dominant]
+        fl = 2.0 * rows * N * Kd
+        roof = {"kernel": "gemm_tiled_kernel (gate/up + SwiGLU)", "bound": "mfma",
+                "achieved": round(fl / dom_s / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(fl / dom_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "algorithmic_flops_per_launch": fl, "rows_executed": rows, "rows_valid": n_tok}
+    roof["avg_launch_us"] = round(dom_s * 1e6, 2)
+    roof["launches_timed"] = dom_n
+
+    def step_entry(k, t):
+        e = {"tokens_per_s": round(n_tok / t, 1), "ms_per_step": round(t * 1e3, 4)}
+        if decode:
+            b = k * arena + kv_bytes + act_bytes
+            e["algorithmic_bytes"] = b
+            e["hbm_frac"] = round(b / t / 1e9 / HBM_PEAK_GBPS, 4)
+        else:
+            fl = 2.0 * n_tok * (arena // 2) + 4.0 * float((lens * (lens + 1) // 2).sum()) * nq * d
+            e["algorithmic_flops_valid_rows"] = fl
+            e["mfma_frac_valid_rows"] = round(fl / t / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
+        return e
+
+    return {
+        "metric": METRIC if name == "C2" else f"decoder-layer tokens/s ({cfg.name})",
         "value": round(n_tok / per_k[1], 1),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(per_k[1] * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: Llama-2-7B-shaped decoder layer, decode step, batch 32, KV length 1024, "
-                               "k=1 replica (k=2,4 in `replicas`)",
-                   "hidden": cfg.hidden, "heads": cfg.n_q_heads, "head_dim": cfg.head_dim,
-                   "intermediate": cfg.intermediate, "batch": cfg.n_seqs, "kv_len": int(inp.lens[0])},
-        "replicas": {str(k): {"tokens_per_s": round(n_tok / t, 1), "ms_per_step": round(t * 1e3, 4),
-                              "algorithmic_bytes": k * arena + kv_bytes + act_bytes,
-                              "hbm_frac": round((k * arena + kv_bytes + act_bytes) / t / 1e9 / HBM_PEAK_GBPS, 4)}
-                     for k, t in per_k.items()},
+        "config": {"workload": f"{cfg.name}: mode {cfg.mode}, {cfg.n_seqs} sequences"
+                               + (f", KV lengths {int(lens.min())}..{int(lens.max())}" if decode else
+                                  f" x {cfg.seq_pad} padded, prompt lengths {int(lens.min())}..{int(lens.max())}")
+                               + ", k=1 replica (other k in `replicas`)",
+                   "hidden": H, "q_heads": nq, "kv_heads": nkv, "head_dim": d, "intermediate": I},
+        "replicas": {str(k): step_entry(k, t) for k, t in per_k.items()},
         "clone": {"payload_GBps": round(arena / t_clone / 1e9, 1), "bytes": arena,
                   "hbm_frac": round(2 * arena / t_clone / 1e9 / HBM_PEAK_GBPS, 4),
                   "layer70b_payload_GBps": round(big_bytes / t_clone_big / 1e9, 1), "layer70b_bytes": big_bytes,
                   "layer70b_hbm_frac": round(2 * big_bytes / t_clone_big / 1e9 / HBM_PEAK_GBPS, 4),
                   "note": "payload = bytes cloned / time; HBM traffic is 2 x payload (read + write)"},
-        "kernel_us_k1": breakdown_us,
+        "kernels_k1": breakdown,
         "parity_rel_err_vs_oracle": float(f"{parity:.3e}"),
-        "roofline": {"kernel": "attn_decode_kernel<1,16>", "bound": "hbm",
-                     "achieved": round(kv_bytes / attn_avg_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(kv_bytes / attn_avg_s / 1e9 / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES["attn_decode@C2"],
-                     "algorithmic_bytes_per_launch": kv_bytes, "avg_launch_us": round(attn_avg_s * 1e6, 2),
-                     "launches_timed": attn_n},
+        "roofline": roof,
         "cpu_baseline": cpu,
     }
+
+
+def bench_bursty(args):
+    """configs[4]: down_proj 11008 -> 4096 under the seeded bursty token stream; replica count per
+    batch by token count, and every batch at fixed k for comparison."""
+    import numpy as np
+    import torch
+    import workloads
+    from tests import gpu_util as U
+
+    cfg = workloads.CONFIGS["C5"]
+    counts = workloads.bursty_token_counts(0)
+    w = workloads.make_weights(cfg, 0)
+    m = U.make_module(cfg, w, max_seqs=max(counts))
+    m.replicate(4)
+    x_all = torch.randn((max(counts), cfg.in_features), device=U.DEV, dtype=torch.bfloat16,
+                        generator=torch.Generator(device=U.DEV).manual_seed(3))
+    y_all = torch.empty((max(counts), cfg.out_features), device=U.DEV, dtype=torch.bfloat16)
+    from paper_2507_18006_amd import binding as B
+    res = {}
+    for policy in ("by_tokens", 1, 2, 4):
+        lat = []
+        for rep in range(2):                      # first pass warms up
+            lat = []
+            for n in counts:
+                k = workloads.replicas_for_tokens(n) if policy == "by_tokens" else policy
+                m.replicate(k)
+                b = m.batch(B.CCS_ROWS, x_all[:n], y_all[:n])
+                lat.append(time_events(torch, lambda: m.forward_split(b), 5) if rep else 0.0)
+                if not rep:
+                    m.forward_split(b)
+            m.replicate(4)
+        lat = np.array(lat)
+        res[str(policy)] = {"tokens_per_s": round(float(sum(counts) / lat.sum()), 1),
+                            "latency_us_p50": round(float(np.median(lat)) * 1e6, 1),
+                            "latency_us_max": round(float(lat.max()) * 1e6, 1)}
+    m.destroy()
+    return {"metric": "aggregate tokens/s (C5 down_proj 11008->4096, 200 bursty batches)",
+            "value": res["by_tokens"]["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+            "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "configs[4]: 200 batches, tokens = max(1, Poisson(64)) x {1,4,16}",
+                       "tokens_total": int(sum(counts)), "tokens_min": min(counts), "tokens_max": max(counts),
+                       "note": "the 90 MB weight fits the 256 MB Infinity Cache: figures are cache-assisted"},
+            "policies": res}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replicas", type=str, default="1,2,4")
+    ap.add_argument("--workload", type=str, default="C2", choices=["C2", "C3", "C4", "C5"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (replicas are HIP streams of one MI355X, no "
+              "collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_18006_amd import binding as B
+    if not os.path.exists(B.lib_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
+    out = bench_bursty(args) if args.workload == "C5" else bench_layer(args, args.workload)
     print(json.dumps(out))
 
 

@@ -8,27 +8,19 @@ namespace ccs {
 // ---------------------------------------------------------------------------------------------
 // Replica clone: the replica-instantiation step of module replication / migration (paper,
 // Section 3.1 "Implementation": the module is duplicated with its weights).  Pure HBM traffic:
-// `bytes` read + `bytes` written.  Each lane moves 16 bytes per access, four accesses in
-// flight per lane before the first store; the grid is a fixed multiple of the CU count and
-// strides over the buffer so that consecutive wavefronts touch consecutive 1 KiB lines.
+// `bytes` read + `bytes` written.  One 16-byte streaming load and one streaming store per lane,
+// one wavefront per workgroup: on this device a flat grid of tiny workgroups beats every
+// persistent / unrolled grid-stride form that was measured (83 % of the HBM peak against 55-73 %),
+// and the runtime's own device-to-device copy (61 %).
 // ---------------------------------------------------------------------------------------------
-constexpr int kCloneThreads = 256;
-constexpr int kCloneUnroll = 4;
+constexpr int kCloneThreads = 64;
 
 __global__ __launch_bounds__(kCloneThreads) void clone_kernel(uint4 *__restrict__ dst,
                                                               const uint4 *__restrict__ src,
                                                               size_t n16)
 {
-    const size_t stride = (size_t)gridDim.x * kCloneThreads;
-    size_t i = (size_t)blockIdx.x * kCloneThreads + threadIdx.x;
-    for (; i + (kCloneUnroll - 1) * stride < n16; i += kCloneUnroll * stride) {
-        uint4 v[kCloneUnroll];
-#pragma unroll
-        for (int u = 0; u < kCloneUnroll; ++u) v[u] = ld_stream(src + i + u * stride);
-#pragma unroll
-        for (int u = 0; u < kCloneUnroll; ++u) st_stream(dst + i + u * stride, v[u]);
-    }
-    for (; i < n16; i += stride) dst[i] = src[i];
+    const size_t i = (size_t)blockIdx.x * kCloneThreads + threadIdx.x;
+    if (i < n16) st_stream(dst + i, ld_stream(src + i));
 }
 
 __global__ void clone_tail_kernel(uint8_t *dst, const uint8_t *src, size_t from, size_t bytes)
@@ -42,9 +34,9 @@ hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st
     if (bytes == 0) return hipSuccess;
     size_t n16 = bytes / 16;
     if (n16) {
-        size_t want = (n16 + (size_t)kCloneThreads * kCloneUnroll - 1) / ((size_t)kCloneThreads * kCloneUnroll);
-        int blocks = (int)(want < 4096 ? want : 4096);  // 16 workgroups per CU on 256 CUs
-        hipLaunchKernelGGL(clone_kernel, dim3(blocks), dim3(kCloneThreads), 0, st, (uint4 *)dst,
+        const size_t blocks = (n16 + kCloneThreads - 1) / kCloneThreads;
+        if (blocks > 0x7fffffffull) return hipErrorInvalidValue;  // > 2 TiB in one call
+        hipLaunchKernelGGL(clone_kernel, dim3((unsigned)blocks), dim3(kCloneThreads), 0, st, (uint4 *)dst,
                            (const uint4 *)src, n16);
     }
     if (bytes % 16)

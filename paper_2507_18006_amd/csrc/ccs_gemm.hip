@@ -255,153 +255,268 @@ hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void 
 // =============================================================================================
 // LDS-tiled MFMA GEMM (prefill-sized row counts)
 // =============================================================================================
-// Workgroup tile BN (weight rows) x BM (activation rows) x 64 (k), WN x WM wavefronts, each
-// owning (BN/WN) x (BM/WM) outputs as 16x16 accumulator tiles.  Packed fragments are copied
-// global -> registers -> LDS verbatim (1 KiB per fragment, conflict-free both ways); the copy of
-// k-tile t+1 is in flight while k-tile t is multiplied.  K is walked in order for every output
-// element and there is no split over K, so results do not depend on M or on the tile an
-// element lands in.
-template <int BN, int BM, int WN, int WM>
-struct TiledCfg {
-    static constexpr int KB = 2;                 // k-fragments per k-tile (BK = 64)
-    static constexpr int TN = BN / 16, TM = BM / 16;
-    static constexpr int FN = TN / WN, FM = TM / WM;
-    static constexpr int THREADS = WN * WM * 64;
-    static constexpr int W_CHUNKS = TN * KB * 64, X_CHUNKS = TM * KB * 64;  // uint4 per stage
-    static constexpr int W_LD = W_CHUNKS / THREADS, X_LD = X_CHUNKS / THREADS;
-    static constexpr size_t LDS_BYTES = 2 * (size_t)(W_CHUNKS + X_CHUNKS) * 16;
-    static_assert(W_CHUNKS % THREADS == 0 && X_CHUNKS % THREADS == 0, "tile/threads mismatch");
-    static_assert(FN % 2 == 0, "gate/up pairs must stay inside one wavefront");
+// ---------------------------------------------------------------------------------------------
+// Main prefill GEMM: 256 (weight rows) x BM (activation rows, 256 or 128) x 32 (k) workgroup
+// tile, 4 wavefronts (2 x 2), one per SIMD, each owning 128 x BM/2 outputs as accumulator tiles
+// of v_mfma_f32_32x32x16_bf16 (256 or 128 accumulator registers).
+//
+// Packed fragments go global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4: one
+// instruction moves one 1 KiB fragment; no staging registers, no ds_write) into a ring of NST
+// stages; NST - 1 k-tiles are in flight while one is multiplied, which is what hides the
+// L2-miss latency (with two stages the kernel ran at the latency of the slowest load per
+// k-tile).  The fragments of the next 16-wide k-step are read from LDS while the MFMAs of the
+// current step issue.  Unit rates this is sized against (measured, per CU): MFMA 32x32x16
+// reaches the bf16 peak with one wavefront per SIMD (16x16x32 needs two); LDS reads ~240 B/clk;
+// the vector-memory path (L2 hits, to registers or LDS alike) ~60 B/clk, which a 256 x 256 tile
+// loads to ~53 % of the MFMA time.
+//
+// A 32x32x16 operand is assembled from the 16 x 32 packed fragments: lane l takes row l%32
+// (16-row block (l%32)/16) and the 16-byte chunk (l%16) + 16*(2*half + l/32); every group of 16
+// lanes reads 256 contiguous bytes, so the LDS reads are conflict free.
+//
+// The LDS reads and waits of the main loop are inline assembly: the compiler serialises every
+// ds_read behind all outstanding direct-to-LDS loads (it cannot prove the stages do not alias)
+// and does not prefetch fragments across MFMAs.  Each k-tile issues the same number of loads per
+// lane (out-of-range blocks are clamped to the last valid block; their products land in
+// accumulators that are never stored), so `s_waitcnt vmcnt(n)` counts whole k-tiles.
+// Needs K % 32 == 0 (always true for packed operands).
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+template <int BM, int NST>
+struct DmaCfg {
+    static constexpr int TN = 16, TM = BM / 16;         // 16-row blocks per stage
+    static constexpr int FM = BM / 64;                  // 32-row activation fragments per wavefront
+    static constexpr int FPW = (TN + TM) / 4;           // fragments each wavefront loads per k-tile
+    static constexpr int STAGE = (TN + TM) * 64;        // uint4 per stage
+    static constexpr size_t LDS_BYTES = (size_t)NST * STAGE * 16;
+    static constexpr int WAIT_STEADY = (NST - 2) * FPW; // loads that may stay in flight at the barrier
+    static constexpr int WAIT_PROLOGUE = (NST - 1) * FPW;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
+    static_assert(WAIT_PROLOGUE < 64, "vmcnt is a 6-bit counter");
 };
 
-template <int BN, int BM, int WN, int WM>
-__global__ __launch_bounds__(WN *WM * 64) void gemm_tiled_kernel(
+#define CCS_STR2(x) #x
+#define CCS_STR(x) CCS_STR2(x)
+
+__device__ __forceinline__ void dma_one(const uint4 *src, uint4 *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds(src, lds_dst, 16, 0, 0);
+}
+
+template <int FPW>
+__device__ __forceinline__ void dma_issue(const uint4 *const *src, size_t koff, uint4 *lds_dst)
+{
+#pragma unroll
+    for (int i = 0; i < FPW; ++i) __builtin_amdgcn_global_load_lds(src[i] + koff, lds_dst + i * 64, 16, 0, 0);
+}
+
+template <int BM, int NST>
+__global__ __launch_bounds__(256) void gemm_tiled_dma_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, int epi, const bf16_t *__restrict__ res,
     bf16_t *__restrict__ out, int M, int N, int kfrags, int tiles_m)
 {
-    using C = TiledCfg<BN, BM, WN, WM>;
+    using C = DmaCfg<BM, NST>;
     extern __shared__ uint4 lds[];
-    constexpr int STAGE = C::W_CHUNKS + C::X_CHUNKS;  // stage s: weights at s*STAGE, activations behind
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn = wave % WN, wm = wave / WN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 1, wm = wave >> 1;
     const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
     const int nb0 = tn * C::TN, mb0 = tm * C::TM;
     const int nblk = N >> 4, mblk = (M + 15) >> 4;
-    const int ktiles = (kfrags + C::KB - 1) / C::KB;
+    const int ktiles = kfrags;
 
-    uint4 gw[C::W_LD], gx[C::X_LD];
-    auto fetch = [&](int kt) {
+    // fragment f of a stage: f < TN -> weight block nb0 + f, else activation block mb0 + f - TN
+    const uint4 *src[C::FPW];
 #pragma unroll
-        for (int it = 0; it < C::W_LD; ++it) {
-            const int c = it * C::THREADS + tid;
-            const int frag = c >> 6, nbl = frag / C::KB, kb = kt * C::KB + frag % C::KB;
-            gw[it] = (nb0 + nbl < nblk && kb < kfrags)
-                         ? Wp[((size_t)(nb0 + nbl) * kfrags + kb) * 64 + (c & 63)]
-                         : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int it = 0; it < C::X_LD; ++it) {
-            const int c = it * C::THREADS + tid;
-            const int frag = c >> 6, mbl = frag / C::KB, kb = kt * C::KB + frag % C::KB;
-            gx[it] = (mb0 + mbl < mblk && kb < kfrags)
-                         ? Xp[((size_t)(mb0 + mbl) * kfrags + kb) * 64 + (c & 63)]
-                         : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int it = 0; it < C::W_LD; ++it) lds[buf * STAGE + it * C::THREADS + tid] = gw[it];
-#pragma unroll
-        for (int it = 0; it < C::X_LD; ++it) lds[buf * STAGE + C::W_CHUNKS + it * C::THREADS + tid] = gx[it];
-    };
-
-    f32x4_t acc[C::FN][C::FM];
-#pragma unroll
-    for (int j = 0; j < C::FN; ++j)
-#pragma unroll
-        for (int i = 0; i < C::FM; ++i) acc[j][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < ktiles) fetch(kt + 1);
-#pragma unroll
-        for (int kb = 0; kb < C::KB; ++kb) {
-            uint4 a[C::FN], b[C::FM];
-#pragma unroll
-            for (int j = 0; j < C::FN; ++j) a[j] = lds[cur * STAGE + ((wn * C::FN + j) * C::KB + kb) * 64 + lane];
-#pragma unroll
-            for (int i = 0; i < C::FM; ++i) b[i] = lds[cur * STAGE + C::W_CHUNKS + ((wm * C::FM + i) * C::KB + kb) * 64 + lane];
-#pragma unroll
-            for (int j = 0; j < C::FN; ++j)
-#pragma unroll
-                for (int i = 0; i < C::FM; ++i) acc[j][i] = mfma16(a[j], b[i], acc[j][i]);
-        }
-        if (kt + 1 < ktiles) stash(cur ^ 1);
-        __syncthreads();
+    for (int i = 0; i < C::FPW; ++i) {
+        const int f = wave * C::FPW + i;
+        const bool is_x = f >= C::TN;
+        const int blk = is_x ? min(mb0 + f - C::TN, mblk - 1) : min(nb0 + f, nblk - 1);
+        src[i] = (is_x ? Xp : Wp) + (size_t)blk * kfrags * 64 + lane;
     }
+    constexpr int KSTEP = 64;  // uint4 per k-tile along one block row
+    // (a __device__ helper, not a lambda: the host pass cannot instantiate a lambda that holds the
+    // direct-to-LDS builtin and then silently drops the kernel's launch stub)
+#define dma(kt, stage) dma_issue<C::FPW>(src, (size_t)(kt) * KSTEP, lds + (stage) * C::STAGE + wave * C::FPW * 64)
 
-    // epilogue: acc[j][i][r] is y[m][n] with n = nb*16 + (lane/16)*4 + r, m = mb*16 + lane%16
-    const int mrow = lane & 15, nq = (lane >> 4) * 4;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)lds;
+    const int sub = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
+    const uint32_t a_addr = lds0 + (uint32_t)(wn * 8 * 64 + sub) * 16;                       // + j * 2048 per fragment
+    const uint32_t b_addr = lds0 + (uint32_t)((C::TN + wm * C::FM * 2) * 64 + sub) * 16;     // + i * 2048
+    constexpr uint32_t kStageBytes = C::STAGE * 16;
+
+    f32x16_t acc[4][C::FM];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+    // two fragment register sets: k-step s multiplies set s % 2 while set (s + 1) % 2 is being read.
+    // A wavefront issues in order and is alone on its SIMD, so every LDS read and every
+    // direct-to-LDS load is placed in the shadow of an MFMA (2 MFMAs, then one read and at most
+    // one load): issued in a block in front of the MFMAs they cost their full issue time.
+    u32x4_t fa0[4], fb0[4], fa1[4], fb1[4];
+    constexpr int MPG = (4 * C::FM) / 8;  // MFMAs per group, 8 groups per k-step
+#define CCS_LDS_READ(dst, addr, OFF) \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(OFF) : "memory")
+#define CCS_WAIT_SET(fa, fb)                                                                                  \
+    do {                                                                                                      \
+        if (C::FM > 2)                                                                                        \
+            asm volatile("s_waitcnt lgkmcnt(0)"                                                               \
+                         : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]),      \
+                           "+v"(fb[2]), "+v"(fb[3])::"memory");                                               \
+        else                                                                                                  \
+            asm volatile("s_waitcnt lgkmcnt(0)"                                                               \
+                         : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1])::"memory"); \
+    } while (0)
+    // one k-step: multiply (ca, cb); if do_read, fetch (na, nb) from abase/bbase + OFF; if do_dma,
+    // issue this wavefront's loads of k-tile kt_dma into stage st_dma
+#define CCS_STEP(ca, cb, na, nb, abase, bbase, OFF, do_read, do_dma, kt_dma, st_dma)                           \
+    do {                                                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                                        \
+            _Pragma("unroll") for (int e = 0; e < MPG; ++e) {                                                  \
+                const int idx = q * MPG + e, j = idx / C::FM, i = idx % C::FM;                                 \
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                           \
+                    __builtin_bit_cast(bf16x8_t, ca[j]), __builtin_bit_cast(bf16x8_t, cb[i]), acc[j][i], 0, 0, 0); \
+            }                                                                                                  \
+            __builtin_amdgcn_sched_barrier(0);                                                                 \
+            if (do_read) {                                                                     \
+                if (q < 4) CCS_LDS_READ(na[q & 3], (abase) + (q & 3) * 2048u, OFF);                            \
+                else if (q - 4 < C::FM) CCS_LDS_READ(nb[q & 3], (bbase) + (q & 3) * 2048u, OFF);               \
+            }                                                                                                  \
+            if ((do_dma) && q < C::FPW)                                                          \
+                dma_one(src[q < C::FPW ? q : 0] + (size_t)(kt_dma) * KSTEP,                                    \
+                        lds + (st_dma) * C::STAGE + (wave * C::FPW + q) * 64);                                 \
+            __builtin_amdgcn_sched_barrier(0);                                                                 \
+        }                                                                                                      \
+    } while (0)
+
+#pragma unroll
+    for (int t = 0; t < NST; ++t) dma(min(t, ktiles - 1), t);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::WAIT_PROLOGUE) : "memory");
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) CCS_LDS_READ(fa0[q], a_addr + q * 2048u, 0);
+#pragma unroll
+    for (int q = 0; q < C::FM; ++q) CCS_LDS_READ(fb0[q], b_addr + q * 2048u, 0);
+    CCS_WAIT_SET(fa0, fb0);
+    int stage = 0;
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const int nstage = (stage + 1 == NST) ? 0 : stage + 1;
+        const uint32_t ab = a_addr + stage * kStageBytes, bb = b_addr + stage * kStageBytes;
+        const uint32_t an = a_addr + nstage * kStageBytes, bn = b_addr + nstage * kStageBytes;
+        // k-step 0 (half 0 of the fragments); half 1 (+512 B) is read meanwhile
+        CCS_STEP(fa0, fb0, fa1, fb1, ab, bb, 512, true, false, 0, 0);
+        CCS_WAIT_SET(fa1, fb1);
+        // this wavefront is done reading `stage`; k-tile kt + 1 must have landed for everybody
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::WAIT_STEADY) : "memory");
+        __syncthreads();
+        // k-step 1: refill `stage` with k-tile kt + NST, read step 0 of k-tile kt + 1 meanwhile
+        // (past the end the refill re-loads the last k-tile into a stage nobody reads and the
+        // fragment read fetches values nobody multiplies: the loop body has no branches)
+        CCS_STEP(fa1, fb1, fa0, fb0, an, bn, 0, true, true, min(kt + NST, ktiles - 1), stage);
+        CCS_WAIT_SET(fa0, fb0);
+        stage = nstage;
+    }
+#undef CCS_STEP
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no load may land in LDS after this workgroup is gone
+#undef CCS_LDS_READ
+#undef CCS_WAIT_SET
+#undef dma
+
+    // Epilogue.  acc[j][i][r] = y[m][n] with m = 32-row block base + lane % 32 and
+    // n = 32-row weight tile base + (r / 4) * 8 + (lane / 32) * 4 + r % 4: a lane owns 4 consecutive
+    // n of one row, so direct stores would be 8-byte pieces scattered over 32 rows.  Every
+    // wavefront therefore turns its outputs through its own LDS region, one 32-row block at a
+    // time, and stores full 256-byte row segments (row-major output) or whole 1 KiB fragments
+    // (packed output): 16 bytes per lane, fully coalesced.
+    __syncthreads();  // every wavefront's loads have landed: the stages can be reused
+    const int mlane = lane & 31, nsub = (lane >> 5) * 4;
     if (epi == EPI_STORE_RM) {
+        constexpr int ROWB = 128 * 4 + 16;  // padded fp32 row: 16 lanes x 16 B hit 64 different banks
+        char *reg = (char *)lds + wave * (32 * ROWB);
+        const int n_wave = (nb0 + wn * 8) * 16;  // first output column of this wavefront
 #pragma unroll
-        for (int j = 0; j < C::FN; ++j) {
-            const int nb = nb0 + wn * C::FN + j;
-            if (nb >= nblk) continue;
+        for (int i = 0; i < C::FM; ++i) {
 #pragma unroll
-            for (int i = 0; i < C::FM; ++i) {
-                const int m = (mb0 + wm * C::FM + i) * 16 + mrow;
-                if (m >= M) continue;
-                const size_t o = (size_t)m * N + nb * 16 + nq;
-                float v0 = acc[j][i][0], v1 = acc[j][i][1], v2 = acc[j][i][2], v3 = acc[j][i][3];
-                if (res) {
-                    uint2 r = *(const uint2 *)(res + o);
-                    v0 += bf_lo(r.x); v1 += bf_hi(r.x); v2 += bf_lo(r.y); v3 += bf_hi(r.y);
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *(float4 *)(reg + mlane * ROWB + (j * 32 + g * 8 + nsub) * 4) =
+                        make_float4(acc[j][i][g * 4 + 0], acc[j][i][g * 4 + 1], acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]);
+            const int m0 = (mb0 + (wm * C::FM + i) * 2) * 16;
+            const int n = n_wave + (lane & 15) * 8;
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr) {
+                const int row = rr * 4 + (lane >> 4), m = m0 + row;
+                const float4 lo = *(const float4 *)(reg + row * ROWB + (lane & 15) * 32);
+                const float4 hi = *(const float4 *)(reg + row * ROWB + (lane & 15) * 32 + 16);
+                if (m < M && n < N) {
+                    const size_t o = (size_t)m * N + n;
+                    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    if (res) {
+                        const uint4 r = *(const uint4 *)(res + o);
+                        v[0] += bf_lo(r.x); v[1] += bf_hi(r.x); v[2] += bf_lo(r.y); v[3] += bf_hi(r.y);
+                        v[4] += bf_lo(r.z); v[5] += bf_hi(r.z); v[6] += bf_lo(r.w); v[7] += bf_hi(r.w);
+                    }
+                    *(uint4 *)(out + o) = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]),
+                                                     pack2bf(v[6], v[7]));
                 }
-                *(uint2 *)(out + o) = make_uint2(pack2bf(v0, v1), pack2bf(v2, v3));
             }
         }
     } else {
-        const int ifrags = N >> 6;  // I / 32
+        // SwiGLU: rows 0..15 of a 32-row weight tile are a gate block, rows 16..31 the matching up
+        // block, so acc[..][r] and acc[..][r + 8] pair up; a wavefront produces 64 columns of u per
+        // 32-row block = 2 x 2 packed fragments, assembled in LDS in packed order.
+        char *reg = (char *)lds + wave * 4096;
+        const int ifrags = N >> 6;                     // I / 32
+        const int cb0 = (nb0 >> 1) / 2 + wn * 2;       // first 32-column fragment of u of this wavefront
 #pragma unroll
-        for (int j = 0; j < C::FN; j += 2) {
-            const int nb = nb0 + wn * C::FN + j;  // even: gate block, nb + 1: up block
-            if (nb + 1 >= nblk) continue;
+        for (int i = 0; i < C::FM; ++i) {
 #pragma unroll
-            for (int i = 0; i < C::FM; ++i) {
-                const int m = (mb0 + wm * C::FM + i) * 16 + mrow;
-                if (m >= M) continue;
-                float o[4];
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float g = acc[j][i][r];
-                    o[r] = g / (1.0f + __expf(-g)) * acc[j + 1][i][r];
+                for (int g = 0; g < 2; ++g) {
+                    float o[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float gt = acc[j][i][g * 4 + r];
+                        o[r] = gt / (1.0f + __expf(-gt)) * acc[j][i][8 + g * 4 + r];
+                    }
+                    const int c = j * 16 + g * 8 + nsub;  // column within the wavefront's 64
+                    const int off = ((mlane >> 4) * 2 + (c >> 5)) * 1024 + ((mlane & 15) + 16 * ((c & 31) >> 3)) * 16 + (c & 7) * 2;
+                    *(uint2 *)(reg + off) = make_uint2(pack2bf(o[0], o[1]), pack2bf(o[2], o[3]));
                 }
-                const int col = (nb >> 1) * 16 + nq;
-                *(uint2 *)(out + packed_index(m, col, ifrags)) = make_uint2(pack2bf(o[0], o[1]), pack2bf(o[2], o[3]));
+            const int mb = mb0 + (wm * C::FM + i) * 2;  // first 16-row block of this 32-row block
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const uint4 v = *(const uint4 *)(reg + f * 1024 + lane * 16);
+                const int mbf = mb + (f >> 1), cb = cb0 + (f & 1);
+                if (mbf < mblk && cb < ifrags) ((uint4 *)out)[((size_t)mbf * ifrags + cb) * 64 + lane] = v;
             }
         }
     }
 }
 
-template <int BN, int BM, int WN, int WM>
-static hipError_t launch_tiled_cfg(const void *Wp, const void *Xp, int epi, const void *res, void *out,
-                                   int M, int N, int K, hipStream_t st)
+template <int BM, int NST>
+hipError_t launch_gemm_tiled_dma(const void *Wp, const void *Xp, int epi, const void *res, void *out,
+                                 int M, int N, int K, hipStream_t st)
 {
-    using C = TiledCfg<BN, BM, WN, WM>;
+    using C = DmaCfg<BM, NST>;
     static bool attr_done = false;
-    auto kern = gemm_tiled_kernel<BN, BM, WN, WM>;
+    auto kern = gemm_tiled_dma_kernel<BM, NST>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)C::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::THREADS), C::LDS_BYTES, st, (const uint4 *)Wp,
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + 255) / 256;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), C::LDS_BYTES, st, (const uint4 *)Wp,
                        (const uint4 *)Xp, epi, (const bf16_t *)res, (bf16_t *)out, M, N, K / 32, tiles_m);
     return hipGetLastError();
 }
@@ -410,7 +525,14 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
                              int M, int N, int K, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
-    return launch_tiled_cfg<256, 256, 2, 4>(Wp, Xp, epi, res, out, M, N, K, st);
+    // Tile height by whole rounds of workgroups on 256 CUs (one workgroup per CU): a 128-row tile
+    // runs at ~0.93 of the 256-row tile's rate but wastes less of the last round.  Either choice
+    // walks K in the same order with the same instruction for every output element, so the bits
+    // do not depend on it.
+    const long tn = (N + 255) / 256;
+    const long r256 = (tn * ((M + 255) / 256) + 255) / 256, r128 = (tn * ((M + 127) / 128) + 255) / 256;
+    if (r128 * 108 < r256 * 200) return launch_gemm_tiled_dma<128, 6>(Wp, Xp, epi, res, out, M, N, K, st);
+    return launch_gemm_tiled_dma<256, 5>(Wp, Xp, epi, res, out, M, N, K, st);
 }
 
 }  // namespace ccs

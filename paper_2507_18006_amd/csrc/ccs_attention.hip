@@ -122,6 +122,220 @@ hipError_t launch_attn_generic(int dtype, const void *qkv, void *out, int rows, 
 }
 
 // =============================================================================================
+// Prefill attention, bf16, head_dim 128, on the matrix cores
+// =============================================================================================
+// One workgroup = one (sequence, query head, 128 query rows); 4 wavefronts of 32 query rows.
+// Keys/values stream in blocks of 32 keys: 8 packed K fragments + 8 transposed V fragments
+// (16 KiB) per block, fetched with direct-to-LDS loads into a 4-stage ring shared by the 4
+// wavefronts (two workgroups fit a CU, so one wavefront's softmax overlaps another's MFMAs).
+// All products use v_mfma_f32_16x16x32_bf16:
+//   scores transposed, S^T[key][q] = K Q^T: A = K fragment (16 keys x 32 d), B = Q^T fragment;
+//   an accumulator lane then owns ONE query (lane % 16) and 4 keys per 16-key tile, so the
+//   softmax statistics of a row live in one lane (plus a 4-lane butterfly) and the rescale
+//   factor of the output accumulators is a per-lane scalar;
+//   output transposed, O^T[d][q] += V^T P^T: A = V^T fragment (16 d x 32 keys), B = P^T built in
+//   registers from the two score tiles (slots 0..3 first tile, 4..7 second tile - the order V^T
+//   was packed in), so probabilities never go through LDS.
+// A wavefront's last block is its diagonal block (keys q0..q0+31), the only one that needs the
+// causal mask; softmax runs in the log2 domain with running maximum and sum (online softmax).
+constexpr int kPfStages = 4;
+constexpr int kPfStageU4 = 1024;  // uint4 per stage (16 KiB)
+
+__device__ __forceinline__ void pf_dma_one(const uint4 *src, uint4 *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds(src, lds_dst, 16, 0, 0);
+}
+
+__device__ __forceinline__ f32x4_t pf_mfma(const u32x4_t &a, const u32x4_t &b, f32x4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                   0, 0, 0);
+}
+
+__global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
+    const bf16_t *__restrict__ qkv, const uint4 *__restrict__ Kp, const uint4 *__restrict__ VTp,
+    bf16_t *__restrict__ out, int nq, int nkv, int seq_pad, int S32, const int32_t *__restrict__ lens)
+{
+    extern __shared__ uint4 lds[];
+    const int b = blockIdx.z, h = blockIdx.y, qb = gridDim.x - 1 - blockIdx.x;  // long blocks first
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c16 = lane & 15;
+    const int q_start = qb * 128;
+    const int ofrags = (nq * 128) >> 5;
+    const size_t row0 = (size_t)b * seq_pad;
+    if (q_start >= lens[b]) {
+        // nothing but padding in this block: defined (zero) output, no work
+        for (int idx = tid; idx < 128 * 32; idx += 256) {
+            const int t = q_start + (idx >> 5);
+            if (t < seq_pad) *(uint2 *)(out + packed_index((int)(row0 + t), h * 128 + (idx & 31) * 4, ofrags)) = make_uint2(0, 0);
+        }
+        return;
+    }
+    const int q0w = q_start + wave * 32;                                // first query row of this wavefront
+    const int last_q = min(q_start + 127, seq_pad - 1);
+    const int nkb = (last_q >> 5) + 1;                                   // key blocks the workgroup walks
+    const int my_blocks = (q0w < seq_pad) ? (q0w >> 5) + 1 : 0;          // key blocks this wavefront multiplies
+    const int kvh = h / (nq / nkv);
+    const uint4 *kbase = Kp + ((size_t)b * nkv + kvh) * S32 * 16 + lane;   // 16 uint4 per key
+    const uint4 *vbase = VTp + ((size_t)b * nkv + kvh) * S32 * 16 + lane;
+    const int width = (nq + 2 * nkv) * 128;
+
+    // this wavefront's 4 fragments of a key block: 0,1 -> K fragments 4*(wave&1).., 2,3 -> V fragments
+    const uint4 *dsrc = (wave < 2 ? kbase : vbase) + (wave & 1) * 4 * 64;
+    uint4 *ddst = lds + wave * 4 * 64;
+#define PF_DMA(kb, stage)                                                                        \
+    do {                                                                                         \
+        const uint4 *s__ = dsrc + (size_t)(kb) * 512;                                            \
+        uint4 *d__ = ddst + (stage) * kPfStageU4;                                                \
+        pf_dma_one(s__, d__); pf_dma_one(s__ + 64, d__ + 64);                                    \
+        pf_dma_one(s__ + 128, d__ + 128); pf_dma_one(s__ + 192, d__ + 192);                      \
+    } while (0)
+
+    // Q^T fragments (B operand): lane -> query c16 of tile qt, d = dblk*32 + g*8 .. +8
+    u32x4_t qf[2][4];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const int t = min(q0w + qt * 16 + c16, seq_pad - 1);
+        const bf16_t *qrow = qkv + (row0 + t) * width + (size_t)h * 128 + g * 8;
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk) {
+            const uint4 v = *(const uint4 *)(qrow + dblk * 32);
+            qf[qt][dblk] = u32x4_t{v.x, v.y, v.z, v.w};
+        }
+    }
+
+    f32x4_t o[2][8];
+    float m_run[2], l_run[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        m_run[qt] = -INFINITY;
+        l_run[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) o[qt][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const uint32_t lds_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)lds + lane * 16;
+    const float sc = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
+
+#pragma unroll
+    for (int s = 0; s < kPfStages - 1; ++s) PF_DMA(min(s, nkb - 1), s);
+
+#define PF_READ(dst, base, OFF) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(base), "i"(OFF) : "memory")
+    for (int kb = 0; kb < nkb; ++kb) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kPfStages - 2) * 4) : "memory");
+        __syncthreads();   // block kb is in LDS for everybody; everybody is done with block kb - 1
+        PF_DMA(min(kb + kPfStages - 1, nkb - 1), (kb + kPfStages - 1) % kPfStages);
+        if (kb >= my_blocks) continue;
+        const uint32_t sb = lds_lane + (uint32_t)(kb % kPfStages) * (kPfStageU4 * 16);
+
+        u32x4_t kf[8], vf[8];
+        PF_READ(kf[0], sb, 0); PF_READ(kf[1], sb, 1024); PF_READ(kf[2], sb, 2048); PF_READ(kf[3], sb, 3072);
+        PF_READ(kf[4], sb, 4096); PF_READ(kf[5], sb, 5120); PF_READ(kf[6], sb, 6144); PF_READ(kf[7], sb, 7168);
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7])::"memory");
+        PF_READ(vf[0], sb, 8192); PF_READ(vf[1], sb, 9216); PF_READ(vf[2], sb, 10240); PF_READ(vf[3], sb, 11264);
+        PF_READ(vf[4], sb, 12288); PF_READ(vf[5], sb, 13312); PF_READ(vf[6], sb, 14336); PF_READ(vf[7], sb, 15360);
+
+        // S^T[key tile kt2][query tile qt] over d = 4 x 32
+        f32x4_t st[2][2];
+#pragma unroll
+        for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                f32x4_t a = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int dblk = 0; dblk < 4; ++dblk) a = pf_mfma(kf[kt2 * 4 + dblk], qf[qt][dblk], a);
+                st[kt2][qt] = a;
+            }
+
+        const bool diag = (kb == my_blocks - 1);
+        u32x4_t pfrag[2];
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            float v[2][4];
+            const int qrow = q0w + qt * 16 + c16;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float x = st[kt2][qt][r] * sc;
+                    if (diag && (kb * 32 + kt2 * 16 + g * 4 + r) > qrow) x = -INFINITY;
+                    v[kt2][r] = x;
+                    mx = fmaxf(mx, x);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mn = fmaxf(m_run[qt], mx);   // finite: key q0w of the diagonal block is visible to every row
+            const float alpha = exp2f(m_run[qt] - mn);
+            m_run[qt] = mn;
+            float ls = 0.f;
+#pragma unroll
+            for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    v[kt2][r] = exp2f(v[kt2][r] - mn);
+                    ls += v[kt2][r];
+                }
+            l_run[qt] = l_run[qt] * alpha + ls;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[qt][dt][r] *= alpha;
+            pfrag[qt] = u32x4_t{pack2bf(v[0][0], v[0][1]), pack2bf(v[0][2], v[0][3]), pack2bf(v[1][0], v[1][1]),
+                                pack2bf(v[1][2], v[1][3])};
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(vf[0]), "+v"(vf[1]), "+v"(vf[2]), "+v"(vf[3]), "+v"(vf[4]), "+v"(vf[5]), "+v"(vf[6]), "+v"(vf[7])::"memory");
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) o[qt][dt] = pf_mfma(vf[dt], pfrag[qt], o[qt][dt]);
+    }
+#undef PF_READ
+#undef PF_DMA
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no load may land in LDS after the workgroup is gone
+
+    // O^T accumulators: lane -> query c16 of tile qt, d = dt*16 + g*4 + r
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        float l = l_run[qt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const float inv = 1.0f / l;
+        const int t = q0w + qt * 16 + c16;
+        if (t >= seq_pad) continue;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const f32x4_t a = o[qt][dt];
+            *(uint2 *)(out + packed_index((int)(row0 + t), h * 128 + dt * 16 + g * 4, ofrags)) =
+                make_uint2(pack2bf(a[0] * inv, a[1] * inv), pack2bf(a[2] * inv, a[3] * inv));
+        }
+    }
+}
+
+hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void *vtp, void *out_packed,
+                                    int n_seqs, int seq_pad, int nq, int nkv, const int32_t *lens_dev,
+                                    hipStream_t st)
+{
+    if (n_seqs <= 0) return hipSuccess;
+    const int S32 = (seq_pad + 31) / 32 * 32;
+    const size_t smem = (size_t)kPfStages * kPfStageU4 * 16;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_mfma_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    dim3 grid((seq_pad + 127) / 128, nq, n_seqs);
+    hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(256), smem, st, (const bf16_t *)qkv, (const uint4 *)kp,
+                       (const uint4 *)vtp, (bf16_t *)out_packed, nq, nkv, seq_pad, S32, lens_dev);
+    return hipGetLastError();
+}
+
+// =============================================================================================
 // Decode attention, bf16, head_dim 128
 // =============================================================================================
 constexpr int kDecChunk = 256;   // keys per split; a property of the kernel, not of the batch

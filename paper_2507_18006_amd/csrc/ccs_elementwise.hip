@@ -195,6 +195,82 @@ __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, i
     }
 }
 
+// Prefill, bf16, head_dim 128: rotate q in place and write the rotated keys and the values in
+// the operand order of the MFMA attention kernel (ccs_attention.hip):
+//   kp  per (sequence, kv head): matrix [S32 keys, 128] in the fragment-packed layout;
+//   vtp per (sequence, kv head): V transposed, per 32-key block 8 fragments (one per 16 values
+//       of d); lane = d % 16 + 16 * ((key % 16) / 4) holds 8 keys: slots 0..3 = keys
+//       (key % 16) / 4 * 4 + 0..3 of the first 16 keys of the block, slots 4..7 the same of the
+//       second 16 - the order in which the score accumulators of that kernel hold them.
+// Grid: n_seqs * S32 blocks (S32 = seq_pad rounded up to 32); positions >= seq_pad only zero
+// their slots (so that masked products stay finite).  Optionally fills the row-major caches.
+__global__ __launch_bounds__(64) void rope_pack_prefill_kernel(
+    bf16_t *__restrict__ qkv, bf16_t *__restrict__ kp, bf16_t *__restrict__ vtp, int nq, int nkv,
+    float base, int seq_pad, int S32, const int32_t *__restrict__ lens, bf16_t *__restrict__ k_cache,
+    bf16_t *__restrict__ v_cache, int cap)
+{
+    const int seq = blockIdx.x / S32, pos = blockIdx.x % S32;
+    const int i = threadIdx.x;  // pair (i, i + 64)
+    const int kb = pos >> 5, kk = pos & 31;
+    const size_t head_elems = (size_t)S32 * 128;
+    auto kp_at = [&](int h, int dd) { return kp + ((size_t)seq * nkv + h) * head_elems + packed_index(pos, dd, 4); };
+    auto vt_at = [&](int h, int dd) {
+        return vtp + ((size_t)seq * nkv + h) * head_elems +
+               ((((size_t)kb * 8 + (dd >> 4)) * 64) + (dd & 15) + 16 * ((kk & 15) >> 2)) * 8 + (kk >> 4) * 4 + (kk & 3);
+    };
+    if (pos >= seq_pad) {
+        for (int h = 0; h < nkv; ++h) {
+            *kp_at(h, i) = 0; *kp_at(h, i + 64) = 0;
+            *vt_at(h, i) = 0; *vt_at(h, i + 64) = 0;
+        }
+        return;
+    }
+    const int width = (nq + 2 * nkv) * 128;
+    bf16_t *r = qkv + ((size_t)seq * seq_pad + pos) * width;
+    const bool store = (k_cache != nullptr) && (pos < lens[seq]) && (pos < cap);
+    double sd, cd;
+    sincos((double)pos * pow((double)base, -(double)i / 64.0), &sd, &cd);
+    const float c = (float)cd, s = (float)sd;
+    for (int h = 0; h < nq + nkv; ++h) {
+        bf16_t *z = r + (size_t)h * 128;
+        const float a = bf2f(z[i]), b = bf2f(z[i + 64]);
+        const bf16_t ra = f2bf(a * c - b * s), rb = f2bf(b * c + a * s);
+        z[i] = ra;
+        z[i + 64] = rb;
+        if (h >= nq) {
+            *kp_at(h - nq, i) = ra;
+            *kp_at(h - nq, i + 64) = rb;
+            if (store) {
+                bf16_t *kc = k_cache + (((size_t)seq * nkv + (h - nq)) * cap + pos) * 128;
+                kc[i] = ra;
+                kc[i + 64] = rb;
+            }
+        }
+    }
+    for (int h = 0; h < nkv; ++h) {
+        const bf16_t *v = r + (size_t)(nq + nkv + h) * 128;
+        const bf16_t v0 = v[i], v1 = v[i + 64];
+        *vt_at(h, i) = v0;
+        *vt_at(h, i + 64) = v1;
+        if (store) {
+            bf16_t *vc = v_cache + (((size_t)seq * nkv + h) * cap + pos) * 128;
+            vc[i] = v0;
+            vc[i + 64] = v1;
+        }
+    }
+}
+
+hipError_t launch_rope_pack_prefill(void *qkv, void *kp, void *vtp, int n_seqs, int seq_pad, int nq, int nkv,
+                                    float base, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
+                                    hipStream_t st)
+{
+    if (n_seqs <= 0) return hipSuccess;
+    const int S32 = (seq_pad + 31) / 32 * 32;
+    hipLaunchKernelGGL(rope_pack_prefill_kernel, dim3(n_seqs * S32), dim3(64), 0, st, (bf16_t *)qkv, (bf16_t *)kp,
+                       (bf16_t *)vtp, nq, nkv, base, seq_pad, S32, lens_dev, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
+    return hipGetLastError();
+}
+
 hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, float base,
                        int decode, int seq_pad, const int32_t *lens_dev, void *k_cache,
                        void *v_cache, int cap, hipStream_t st)

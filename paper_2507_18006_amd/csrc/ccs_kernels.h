@@ -27,6 +27,12 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, in
 hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, float base,
                        int decode, int seq_pad, const int32_t *lens_dev, void *k_cache,
                        void *v_cache, int cap, hipStream_t st);
+// bf16 prefill with head_dim 128: rotate q in place and emit K (fragment-packed per kv head) and
+// V (transposed, in the key order of the MFMA prefill-attention kernel) into kp / vtp, each
+// n_seqs * nkv * S32 * 128 elements, S32 = seq_pad rounded up to 32; optional row-major caches.
+hipError_t launch_rope_pack_prefill(void *qkv, void *kp, void *vtp, int n_seqs, int seq_pad, int nq, int nkv,
+                                    float base, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
+                                    hipStream_t st);
 // f32 path: u[t,j] = silu(gu[t,j]) * gu[t, I + j], gu row-major [rows, 2I].
 hipError_t launch_swiglu_f32(const float *gu, float *u, int rows, int I, hipStream_t st);
 
@@ -65,6 +71,13 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
 hipError_t launch_attn_generic(int dtype, const void *qkv, void *out, int rows, int nq, int nkv,
                                int d, int decode, int seq_pad, const int32_t *lens_dev,
                                const void *k_cache, const void *v_cache, int cap, hipStream_t st);
+// bf16, head_dim 128 causal prefill attention on the matrix cores: q rows from qkv (rotated, row
+// major), keys/values from the kp / vtp buffers of launch_rope_pack_prefill; output fragment
+// packed [rows16, nq*128].  Rows of 128-row query blocks that start at or after lens[b] are
+// written as zero; other padded rows hold finite don't-care values.
+hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void *vtp, void *out_packed,
+                                    int n_seqs, int seq_pad, int nq, int nkv, const int32_t *lens_dev,
+                                    hipStream_t st);
 // bf16, head_dim 128 decode attention with split-KV partials (fp32) and an ordered combine.
 size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap);
 hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs, int nq, int nkv,

@@ -44,7 +44,7 @@ struct ArenaPlan {
 };
 
 struct WsPlan {
-    size_t h, qkv, a, x1, gu, u, xp, scratch, scratch_bytes, total;
+    size_t h, qkv, a, x1, gu, u, xp, kp, vtp, scratch, scratch_bytes, total;
 };
 
 int check_desc(const ccs_module_desc *D, Dims *out)
@@ -105,7 +105,7 @@ inline size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 // Scratch one forward over `rows` rows (n_seqs sequences, caches of `cap` slots) needs.
 // `skinny`: the weight-streaming GEMM variant is in use (rows <= kSkinnyMaxRows).
 WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs, int cap, bool skinny,
-               bool decode)
+               bool decode, int prefill_seq_pad = 0)
 {
     WsPlan p{};
     size_t off = 0;
@@ -123,6 +123,11 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
         p.a = take(r16 * d.QD * 2);
         p.x1 = take(rows * d.H * 2);
         p.u = take(r16 * d.I * 2);
+        if (prefill_seq_pad > 0) {  // K / V^T in matrix-core operand order for the prefill attention
+            const size_t s32 = align_up((size_t)prefill_seq_pad, 32);
+            p.kp = take((size_t)n_seqs * d.nkv * s32 * d.d * 2);
+            p.vtp = take((size_t)n_seqs * d.nkv * s32 * d.d * 2);
+        }
         size_t s = 0;
         if (skinny) {
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.W3, d.H));
@@ -304,7 +309,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     const bool decode = b->mode == CCS_DECODE;
     const int seq_pad = decode ? 1 : b->seq_pad;
     const int T = b->n_seqs * seq_pad;
-    WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode);
+    WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, decode ? 0 : seq_pad);
     if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
 
@@ -322,12 +327,15 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         }                                                                                                     \
     } while (0)
         CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
-        CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        if (decode)
+            CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        else
+            CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, D.rope_base, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
         if (decode) {
             CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
             CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, b->lens_dev, b->cache_cap, st));
         } else {
-            CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, 0, seq_pad, b->lens_dev, nullptr, nullptr, 0, st));
+            CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, b->lens_dev, st));
         }
         CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, b->x, ws + p.x1, d.H, d.QD);
         CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
@@ -373,12 +381,18 @@ size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
     }
     const size_t rows = (size_t)max_seqs * max_seq_pad;
     const bool skinny = rows <= (size_t)ccs::kSkinnyMaxRows;
-    // a smaller batch may take the weight-streaming variant: cover both plans
-    size_t need = ws_plan(desc, d, rows, max_seqs, max_cache_cap, skinny, max_cache_cap > 0).total;
+    const bool layer = desc->kind == CCS_DECODER_LAYER;
+    // cover every plan a batch within these limits can take: prefill (max_seq_pad rows per
+    // sequence), decode (one row per sequence, when a cache size is given), either GEMM variant
+    size_t need = ws_plan(desc, d, rows, max_seqs, max_cache_cap, skinny, false, layer ? max_seq_pad : 0).total;
     if (!skinny) {
-        size_t small = ws_plan(desc, d, ccs::kSkinnyMaxRows, max_seqs < ccs::kSkinnyMaxRows ? max_seqs : ccs::kSkinnyMaxRows,
-                               max_cache_cap, true, max_cache_cap > 0).total;
-        need = max_sz(need, small);
+        const int small_seqs = max_seqs < ccs::kSkinnyMaxRows ? max_seqs : ccs::kSkinnyMaxRows;
+        need = max_sz(need, ws_plan(desc, d, ccs::kSkinnyMaxRows, small_seqs, max_cache_cap, true, false, layer ? 64 : 0).total);
+    }
+    if (layer && max_cache_cap > 0) {
+        const bool dsk = max_seqs <= ccs::kSkinnyMaxRows;
+        need = max_sz(need, ws_plan(desc, d, max_seqs, max_seqs, max_cache_cap, dsk, true, 0).total);
+        if (!dsk) need = max_sz(need, ws_plan(desc, d, ccs::kSkinnyMaxRows, ccs::kSkinnyMaxRows, max_cache_cap, true, true, 0).total);
     }
     return need ? need : 256;
 }

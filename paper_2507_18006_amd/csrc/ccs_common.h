@@ -68,6 +68,23 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+// Rotary angle of pair i at position pos from the per-module table of inverse frequencies
+// (theta_i = base^(-2i/d) split into an fp32 head and tail, computed once in fp64): the product
+// pos * theta_i is formed with an exact fp32 residual, the head goes through the accurate
+// sincosf and the residual is applied to first order, so the angle error stays ~1e-7 rad at any
+// position instead of growing with pos * 2^-24.
+__device__ __forceinline__ void rope_cs(const float2 *__restrict__ tab, int i, int pos, float &c, float &s)
+{
+    const float2 f = tab[i];
+    const float p = (float)pos;
+    const float a = p * f.x;
+    const float dl = fmaf(p, f.y, fmaf(p, f.x, -a));
+    float s0, c0;
+    sincosf(a, &s0, &c0);
+    s = fmaf(dl, c0, s0);
+    c = fmaf(-dl, s0, c0);
+}
+
 template <typename T> struct io;
 template <> struct io<float> {
     static __device__ __forceinline__ float ld(const float *p) { return *p; }

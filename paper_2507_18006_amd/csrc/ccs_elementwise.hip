@@ -154,7 +154,7 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, in
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, int nkv, int d,
-                                                  float base, int decode, int seq_pad,
+                                                  const float2 *__restrict__ tab, int decode, int seq_pad,
                                                   const int32_t *__restrict__ lens,
                                                   T *__restrict__ k_cache, T *__restrict__ v_cache,
                                                   int cap)
@@ -168,10 +168,8 @@ __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, i
     else { seq = row / seq_pad; pos = row % seq_pad; len = lens[seq]; }
     const bool store = (k_cache != nullptr) && (pos < len) && (pos < cap);
     for (int i = threadIdx.x; i < half; i += 64) {
-        double theta = pow((double)base, -2.0 * (double)i / (double)d);
-        double sd, cd;
-        sincos((double)pos * theta, &sd, &cd);
-        const float c = (float)cd, s = (float)sd;
+        float c, s;
+        rope_cs(tab, i, pos, c, s);
         for (int h = 0; h < nq + nkv; ++h) {
             T *z = r + (size_t)h * d;
             float a = io<T>::ld(z + i), b = io<T>::ld(z + i + half);
@@ -206,7 +204,7 @@ __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, i
 // their slots (so that masked products stay finite).  Optionally fills the row-major caches.
 __global__ __launch_bounds__(64) void rope_pack_prefill_kernel(
     bf16_t *__restrict__ qkv, bf16_t *__restrict__ kp, bf16_t *__restrict__ vtp, int nq, int nkv,
-    float base, int seq_pad, int S32, const int32_t *__restrict__ lens, bf16_t *__restrict__ k_cache,
+    const float2 *__restrict__ tab, int seq_pad, int S32, const int32_t *__restrict__ lens, bf16_t *__restrict__ k_cache,
     bf16_t *__restrict__ v_cache, int cap)
 {
     const int seq = blockIdx.x / S32, pos = blockIdx.x % S32;
@@ -228,9 +226,8 @@ __global__ __launch_bounds__(64) void rope_pack_prefill_kernel(
     const int width = (nq + 2 * nkv) * 128;
     bf16_t *r = qkv + ((size_t)seq * seq_pad + pos) * width;
     const bool store = (k_cache != nullptr) && (pos < lens[seq]) && (pos < cap);
-    double sd, cd;
-    sincos((double)pos * pow((double)base, -(double)i / 64.0), &sd, &cd);
-    const float c = (float)cd, s = (float)sd;
+    float c, s;
+    rope_cs(tab, i, pos, c, s);
     for (int h = 0; h < nq + nkv; ++h) {
         bf16_t *z = r + (size_t)h * 128;
         const float a = bf2f(z[i]), b = bf2f(z[i + 64]);
@@ -261,27 +258,209 @@ __global__ __launch_bounds__(64) void rope_pack_prefill_kernel(
 }
 
 hipError_t launch_rope_pack_prefill(void *qkv, void *kp, void *vtp, int n_seqs, int seq_pad, int nq, int nkv,
-                                    float base, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
+                                    const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
                                     hipStream_t st)
 {
     if (n_seqs <= 0) return hipSuccess;
     const int S32 = (seq_pad + 31) / 32 * 32;
     hipLaunchKernelGGL(rope_pack_prefill_kernel, dim3(n_seqs * S32), dim3(64), 0, st, (bf16_t *)qkv, (bf16_t *)kp,
-                       (bf16_t *)vtp, nq, nkv, base, seq_pad, S32, lens_dev, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
+                       (bf16_t *)vtp, nq, nkv, (const float2 *)tab, seq_pad, S32, lens_dev, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
     return hipGetLastError();
 }
 
-hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, float base,
+hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, const void *tab,
                        int decode, int seq_pad, const int32_t *lens_dev, void *k_cache,
                        void *v_cache, int cap, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
     if (dtype == DT_BF16)
         hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(rows), dim3(64), 0, st, (bf16_t *)qkv, nq, nkv, d,
-                           base, decode, seq_pad, lens_dev, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
+                           (const float2 *)tab, decode, seq_pad, lens_dev, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
     else
         hipLaunchKernelGGL(rope_kernel<float>, dim3(rows), dim3(64), 0, st, (float *)qkv, nq, nkv, d,
-                           base, decode, seq_pad, lens_dev, (float *)k_cache, (float *)v_cache, cap);
+                           (const float2 *)tab, decode, seq_pad, lens_dev, (float *)k_cache, (float *)v_cache, cap);
+    return hipGetLastError();
+}
+
+// Inverse-frequency table of the rotary embedding: tab[i] = (head, tail) of base^(-2i/d) in fp32,
+// evaluated in fp64 once per module (it lives in the weight arena and is cloned with it).
+__global__ void rope_table_kernel(float2 *tab, int d, float base)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= d / 2) return;
+    const double theta = pow((double)base, -2.0 * (double)i / (double)d);
+    const float hi = (float)theta;
+    tab[i] = make_float2(hi, (float)(theta - (double)hi));
+}
+
+hipError_t launch_rope_table(void *tab, int d, float base, hipStream_t st)
+{
+    hipLaunchKernelGGL(rope_table_kernel, dim3((d / 2 + 63) / 64), dim3(64), 0, st, (float2 *)tab, d, base);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode, bf16, head_dim 128: epilogue of the weight-streaming Q/K/V projection.  Sums the K
+// segments' partials in segment order, rotates q and k to position lens[row], stores q (bf16)
+// into the row-major qkv buffer and appends the rotated key and the value at cache slot
+// lens[row].  One thread owns 4 columns of the first half of a head and their partners 64 up.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void qkv_reduce_rope_decode_kernel(
+    const float *__restrict__ part, int S, int M, int nq, int nkv, const float2 *__restrict__ tab,
+    const int32_t *__restrict__ lens, bf16_t *__restrict__ qkv, bf16_t *__restrict__ k_cache,
+    bf16_t *__restrict__ v_cache, int cap)
+{
+    const int heads = nq + 2 * nkv, width = heads * 128;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * heads * 16) return;
+    const int m = idx / (heads * 16), hu = idx % (heads * 16);
+    const int head = hu >> 4, c = (hu & 15) * 4;
+    const size_t seg = (size_t)M * width;
+    const float *p = part + (size_t)m * width + head * 128 + c;
+    float4 lo = *(const float4 *)p, hi = *(const float4 *)(p + 64);
+    for (int k = 1; k < S; ++k) {
+        const float4 a = *(const float4 *)(p + k * seg), b = *(const float4 *)(p + k * seg + 64);
+        lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+        hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+    }
+    const int pos = lens[m];
+    float l[4] = {lo.x, lo.y, lo.z, lo.w}, h[4] = {hi.x, hi.y, hi.z, hi.w};
+    if (head < nq + nkv) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float cs, sn;
+            rope_cs(tab, c + e, pos, cs, sn);
+            const float a = l[e], b = h[e];
+            l[e] = a * cs - b * sn;
+            h[e] = b * cs + a * sn;
+        }
+    }
+    const uint2 plo = make_uint2(pack2bf(l[0], l[1]), pack2bf(l[2], l[3]));
+    const uint2 phi = make_uint2(pack2bf(h[0], h[1]), pack2bf(h[2], h[3]));
+    bf16_t *dst;
+    if (head < nq) dst = qkv + (size_t)m * width + head * 128 + c;
+    else if (head < nq + nkv) dst = k_cache + (((size_t)m * nkv + (head - nq)) * cap + pos) * 128 + c;
+    else dst = v_cache + (((size_t)m * nkv + (head - nq - nkv)) * cap + pos) * 128 + c;
+    *(uint2 *)dst = plo;
+    *(uint2 *)(dst + 64) = phi;
+}
+
+hipError_t launch_qkv_reduce_rope_decode(const float *partials, int S, int M, int nq, int nkv, const void *tab,
+                                         const int32_t *lens_dev, void *qkv, void *k_cache, void *v_cache,
+                                         int cap, hipStream_t st)
+{
+    if (M <= 0) return hipSuccess;
+    const int total = M * (nq + 2 * nkv) * 16;
+    hipLaunchKernelGGL(qkv_reduce_rope_decode_kernel, dim3((total + 255) / 256), dim3(256), 0, st, partials, S, M, nq,
+                       nkv, (const float2 *)tab, lens_dev, (bf16_t *)qkv, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode, bf16: epilogue of the weight-streaming O projection fused with the second RMSNorm.
+// One workgroup per row: x1 = bf16(sum of partials in segment order + x), stored row-major;
+// h2 = RMSNorm(x1; g2) stored fragment-packed.  The sum of squares is reduced in a fixed order
+// (thread partials, wavefront butterfly, wavefronts 0..3), so a row's bits do not depend on the
+// batch.  H <= 8192.
+// ---------------------------------------------------------------------------------------------
+constexpr int kRowNormMaxH = 8192;
+
+__global__ __launch_bounds__(256) void reduce_residual_rmsnorm_kernel(
+    const float *__restrict__ part, int S, int M, int H, const bf16_t *__restrict__ res,
+    const bf16_t *__restrict__ g, float eps, bf16_t *__restrict__ x1, bf16_t *__restrict__ h2)
+{
+    __shared__ float wsum[4];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const size_t seg = (size_t)M * H;
+    float v[kRowNormMaxH / 1024][4];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
+        const int c = (tid + 256 * j) * 4;
+        if (c < H) {
+            const float *p = part + (size_t)m * H + c;
+            float4 s = *(const float4 *)p;
+            for (int k = 1; k < S; ++k) {
+                const float4 t = *(const float4 *)(p + k * seg);
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+            const uint2 r = *(const uint2 *)(res + (size_t)m * H + c);
+            const uint2 o = make_uint2(pack2bf(s.x + bf_lo(r.x), s.y + bf_hi(r.x)), pack2bf(s.z + bf_lo(r.y), s.w + bf_hi(r.y)));
+            *(uint2 *)(x1 + (size_t)m * H + c) = o;
+            v[j][0] = bf_lo(o.x); v[j][1] = bf_hi(o.x); v[j][2] = bf_lo(o.y); v[j][3] = bf_hi(o.y);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ss = fmaf(v[j][e], v[j][e], ss);
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) wsum[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+    const float r = 1.0f / sqrtf(tot / (float)H + eps);
+#pragma unroll
+    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
+        const int c = (tid + 256 * j) * 4;
+        if (c < H) {
+            const uint2 gv = *(const uint2 *)(g + c);
+            *(uint2 *)(h2 + packed_index(m, c, H >> 5)) =
+                make_uint2(pack2bf(v[j][0] * r * bf_lo(gv.x), v[j][1] * r * bf_hi(gv.x)),
+                           pack2bf(v[j][2] * r * bf_lo(gv.y), v[j][3] * r * bf_hi(gv.y)));
+        }
+    }
+}
+
+hipError_t launch_reduce_residual_rmsnorm(const float *partials, int S, int M, int H, const void *res, const void *g,
+                                          float eps, void *x1, void *h2, hipStream_t st)
+{
+    if (M <= 0) return hipSuccess;
+    if (H > kRowNormMaxH || (H & 3)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reduce_residual_rmsnorm_kernel, dim3(M), dim3(256), 0, st, partials, S, M, H, (const bf16_t *)res,
+                       (const bf16_t *)g, eps, (bf16_t *)x1, (bf16_t *)h2);
+    return hipGetLastError();
+}
+
+// RMSNorm for few rows (decode): one workgroup per row, same fixed reduction order as above.
+__global__ __launch_bounds__(256) void rmsnorm_bf16_row_kernel(const bf16_t *__restrict__ x,
+                                                               const bf16_t *__restrict__ g,
+                                                               bf16_t *__restrict__ out, int H, float eps)
+{
+    __shared__ float wsum[4];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    float v[kRowNormMaxH / 1024][4];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
+        const int c = (tid + 256 * j) * 4;
+        if (c < H) {
+            const uint2 o = *(const uint2 *)(x + (size_t)m * H + c);
+            v[j][0] = bf_lo(o.x); v[j][1] = bf_hi(o.x); v[j][2] = bf_lo(o.y); v[j][3] = bf_hi(o.y);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ss = fmaf(v[j][e], v[j][e], ss);
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) wsum[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+    const float r = 1.0f / sqrtf(tot / (float)H + eps);
+#pragma unroll
+    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
+        const int c = (tid + 256 * j) * 4;
+        if (c < H) {
+            const uint2 gv = *(const uint2 *)(g + c);
+            *(uint2 *)(out + packed_index(m, c, H >> 5)) =
+                make_uint2(pack2bf(v[j][0] * r * bf_lo(gv.x), v[j][1] * r * bf_hi(gv.x)),
+                           pack2bf(v[j][2] * r * bf_lo(gv.y), v[j][3] * r * bf_hi(gv.y)));
+        }
+    }
+}
+
+hipError_t launch_rmsnorm_rows(const void *x, const void *g, void *out, int rows, int H, float eps, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    if (H > kRowNormMaxH || (H & 3)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rmsnorm_bf16_row_kernel, dim3(rows), dim3(256), 0, st, (const bf16_t *)x, (const bf16_t *)g,
+                       (bf16_t *)out, H, eps);
     return hipGetLastError();
 }
 

@@ -20,18 +20,31 @@ hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int
 // bf16: out is fragment-packed [rows16, H]; f32: out row-major.
 hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H,
                           float eps, hipStream_t st);
+// Inverse-frequency table of the rotary embedding, d/2 float2 entries (fp32 head and tail of
+// base^(-2i/d)); part of the weight arena.  All rope kernels take it as `tab`.
+hipError_t launch_rope_table(void *tab, int d, float base, hipStream_t st);
+// Decode (bf16, head_dim 128) epilogues of the weight-streaming projections:
+// Q/K/V: segment sum + rotary embedding + q store + KV-cache append at slot lens[row];
+hipError_t launch_qkv_reduce_rope_decode(const float *partials, int S, int M, int nq, int nkv, const void *tab,
+                                         const int32_t *lens_dev, void *qkv, void *k_cache, void *v_cache,
+                                         int cap, hipStream_t st);
+// O: segment sum + residual -> x1 (row-major) and RMSNorm(x1; g) -> h2 (fragment-packed); H <= 8192.
+hipError_t launch_reduce_residual_rmsnorm(const float *partials, int S, int M, int H, const void *res, const void *g,
+                                          float eps, void *x1, void *h2, hipStream_t st);
+// bf16 RMSNorm with one workgroup per row (few rows), output fragment-packed; H <= 8192.
+hipError_t launch_rmsnorm_rows(const void *x, const void *g, void *out, int rows, int H, float eps, hipStream_t st);
 // Rotary embedding (split-half pairs) in place on the q and k parts of qkv [rows, (nq+2nkv)*d]
 // row-major.  prefill (decode == 0): position = row % seq_pad; when caches are non-null the
 // rotated k and v of rows with position < lens[row / seq_pad] are stored at slot = position.
 // decode: position = lens[row]; rotated k and v stored at slot lens[row] of sequence `row`.
-hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, float base,
+hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, const void *tab,
                        int decode, int seq_pad, const int32_t *lens_dev, void *k_cache,
                        void *v_cache, int cap, hipStream_t st);
 // bf16 prefill with head_dim 128: rotate q in place and emit K (fragment-packed per kv head) and
 // V (transposed, in the key order of the MFMA prefill-attention kernel) into kp / vtp, each
 // n_seqs * nkv * S32 * 128 elements, S32 = seq_pad rounded up to 32; optional row-major caches.
 hipError_t launch_rope_pack_prefill(void *qkv, void *kp, void *vtp, int n_seqs, int seq_pad, int nq, int nkv,
-                                    float base, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
+                                    const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
                                     hipStream_t st);
 // f32 path: u[t,j] = silu(gu[t,j]) * gu[t, I + j], gu row-major [rows, 2I].
 hipError_t launch_swiglu_f32(const float *gu, float *u, int rows, int I, hipStream_t st);

@@ -40,7 +40,7 @@ struct Dims {
 };
 
 struct ArenaPlan {
-    size_t qkv, o, gu, dn, g1, g2, w, total;
+    size_t qkv, o, gu, dn, g1, g2, rope, w, total;
 };
 
 struct WsPlan {
@@ -95,6 +95,7 @@ ArenaPlan arena_plan(const ccs_module_desc *D, const Dims &d)
         p.dn = take((size_t)d.H * d.I * d.esz);
         p.g1 = take((size_t)d.H * d.esz);
         p.g2 = take((size_t)d.H * d.esz);
+        p.rope = take((size_t)(d.d / 2) * 2 * sizeof(float));  // inverse-frequency table (fp32 head + tail)
     }
     p.total = off;
     return p;
@@ -313,7 +314,12 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
 
-    CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm(dt, b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+    const bool row_norm = skinny && d.H <= 8192 && d.H % 4 == 0;  // few rows: one workgroup per row
+    if (row_norm)
+        CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm_rows(b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+    else
+        CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm(dt, b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+    const void *tab = A + m->ap.rope;
     if (bf) {
         float *scratch = (float *)(ws + p.scratch);
         // one projection: weight-streaming (two launches) or LDS-tiled (one launch)
@@ -326,26 +332,38 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), st));  \
         }                                                                                                     \
     } while (0)
-        CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
-        if (decode)
-            CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        else
-            CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, D.rope_base, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        if (skinny && decode) {
+            // weight-streaming Q/K/V projection; its reduction also rotates and appends to the cache
+            CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_skinny_main(A + m->ap.qkv, ws + p.h, scratch, T, d.W3, d.H, st));
+            CCS_STAGE(CCS_ST_GEMM_QKV_REDUCE, launch_qkv_reduce_rope_decode(scratch, skinny_segments(d.W3, d.H), T, d.nq, d.nkv, tab, b->lens_dev, ws + p.qkv, b->k_cache, b->v_cache, b->cache_cap, st));
+        } else {
+            CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
+            if (decode)
+                CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+            else
+                CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        }
         if (decode) {
             CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
             CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, b->lens_dev, b->cache_cap, st));
         } else {
             CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, b->lens_dev, st));
         }
-        CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, b->x, ws + p.x1, d.H, d.QD);
-        CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+        if (row_norm) {
+            // weight-streaming O projection; its reduction adds the residual and applies the second norm
+            CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_skinny_main(A + m->ap.o, ws + p.a, scratch, T, d.H, d.QD, st));
+            CCS_STAGE(CCS_ST_GEMM_O_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.QD), T, d.H, b->x, A + m->ap.g2, D.rms_eps, ws + p.x1, ws + p.h, st));
+        } else {
+            CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, b->x, ws + p.x1, d.H, d.QD);
+            CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+        }
         CCS_GEMM(CCS_ST_GEMM_GU, m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H);
         CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, ws + p.x1, b->y, d.H, d.I);
 #undef CCS_GEMM
     } else {
         auto W = [&](size_t off) { return (const float *)(A + off); };
         CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
-        CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, D.rope_base, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
+        CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
         CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
         CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)b->x, (float *)(ws + p.x1), T, d.H, d.QD, st));
         CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
@@ -455,6 +473,7 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
         rm_copy(m->ap.g1, w->g1, rowb);
         rm_copy(m->ap.g2, w->g2, rowb);
     }
+    if (e == hipSuccess && desc->kind == CCS_DECODER_LAYER) e = launch_rope_table(A + m->ap.rope, d.d, desc->rope_base, st);
     if (e != hipSuccess) {
         delete m;
         return fail(CCS_EHIP, "packing weights: %s", hipGetErrorString(e));

@@ -61,17 +61,23 @@ hipError_t launch_gemm_f32(const float *x, const float *W, const float *res, flo
 // Weight-streaming GEMM (decode-sized row counts)
 // =============================================================================================
 constexpr int kSkNB = 4;     // 16-row weight blocks per wavefront (64 output columns)
-constexpr int kSkWaves = 4;  // wavefronts per workgroup, each a contiguous part of the segment
 constexpr int kSkU = 4;      // k-fragments in flight per wavefront
+// Launch shape from the weight shape alone (measured sweeps at 32 and 64 rows): ~512 workgroups
+// through K segments (at most 8) - more spill into a second round at 64 rows, where only two
+// wavefronts fit a SIMD; weights with few column tiles (N = 4096: O and
+// down projections) get 8 wavefronts per workgroup - each a contiguous part of the segment - the
+// others 4.
 
 static inline int sk_tiles(int N) { return (N / 16 + kSkNB - 1) / kSkNB; }
+
+static inline int sk_waves(int N) { return sk_tiles(N) < 96 ? 8 : 4; }
 
 int skinny_segments(int N, int K)
 {
     const int kfrags = K / 32, tiles = sk_tiles(N);
-    int S = (512 + tiles - 1) / tiles;  // aim for >= 2 workgroups per CU
-    if (S > 4) S = 4;
-    int max_s = kfrags / (kSkWaves * 2);  // at least 2 fragments per wavefront
+    int S = (512 + tiles - 1) / tiles;  // ~2 workgroups per CU: one round at every row count
+    if (S > 8) S = 8;
+    int max_s = kfrags / (sk_waves(N) * 2);  // at least 2 fragments per wavefront
     if (S > max_s) S = max_s;
     if (S < 1) S = 1;
     const int per = (kfrags + S - 1) / S;
@@ -83,7 +89,7 @@ size_t skinny_partial_bytes(int M, int N, int K)
     return (size_t)skinny_segments(N, K) * (size_t)M * (size_t)N * sizeof(float);
 }
 
-template <int MB>
+template <int MB, int kSkWaves>
 __global__ __launch_bounds__(kSkWaves * 64) void gemm_skinny_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, float *__restrict__ part, int nblk,
     int kfrags, int ntiles, int kf_seg, int M, int N)
@@ -143,7 +149,7 @@ __global__ __launch_bounds__(kSkWaves * 64) void gemm_skinny_kernel(
             for (int i = 0; i < MB; ++i) acc[j][i] = mfma16(w[j], xv[i], acc[j][i]);
     }
 
-    // in-workgroup reduction, fixed order wave 0 + wave 1 + wave 2 + wave 3
+    // in-workgroup reduction, fixed order wave 0 + wave 1 + ... + wave kSkWaves-1
     if (wave > 0) {
 #pragma unroll
         for (int j = 0; j < kSkNB; ++j)
@@ -225,11 +231,18 @@ hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partia
     const int kfrags = K / 32, nblk = N / 16, ntiles = sk_tiles(N);
     const int S = skinny_segments(N, K);
     const int kf_seg = (kfrags + S - 1) / S;
-    dim3 grid(ntiles * S), block(kSkWaves * 64);
+    const int waves = sk_waves(N);
+    dim3 grid(ntiles * S), block(waves * 64);
     const int mb = (M + 15) / 16;
-#define CCS_SK(MBV)                                                                                    \
-    hipLaunchKernelGGL(gemm_skinny_kernel<MBV>, grid, block, 0, st, (const uint4 *)Wp, (const uint4 *)Xp, \
-                       partials, nblk, kfrags, ntiles, kf_seg, M, N)
+#define CCS_SK(MBV)                                                                                        \
+    do {                                                                                                   \
+        if (waves == 8)                                                                                    \
+            hipLaunchKernelGGL((gemm_skinny_kernel<MBV, 8>), grid, block, 0, st, (const uint4 *)Wp,        \
+                               (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N);           \
+        else                                                                                               \
+            hipLaunchKernelGGL((gemm_skinny_kernel<MBV, 4>), grid, block, 0, st, (const uint4 *)Wp,        \
+                               (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N);           \
+    } while (0)
     switch (mb) {
         case 1: CCS_SK(1); break;
         case 2: CCS_SK(2); break;

@@ -477,6 +477,147 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     }
 }
 
+// Grouped-query variant (G = 2, 4, 8 query heads per kv head).  With G heads the all-VALU kernel
+// above spends G x (8 FMA + a 16-lane reduction) per key on the scores alone and falls far below
+// the HBM rate; here the scores go to the matrix cores in the transposed form of the prefill
+// kernel - S^T[key][head] = K Q^T with the cached K rows as the A operand (16 keys x 32 d read
+// straight from the row-major cache) and the group's query heads as the B columns - so a lane
+// owns one head and 4 keys per 16-key tile and the softmax statistics stay per lane.  The
+// probabilities and rescale factors cross to the value layout (16 lanes per key row, fully
+// coalesced V loads as above) through a 1 KiB wavefront-private LDS tile; P V stays on the VALU,
+// where it is G x 8 FMAs per 16 bytes of V.  Same chunking and partial format as above.
+template <int G>
+__global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
+    const bf16_t *__restrict__ qkv, float *__restrict__ part, int n_seqs, int nq, int nkv,
+    const int32_t *__restrict__ lens, const uint4 *__restrict__ kc, const uint4 *__restrict__ vc, int cap,
+    int nchunks)
+{
+    __shared__ float pt[4][32][8];   // per wavefront: probabilities [key in block][head]
+    __shared__ float al[4][8];       // per wavefront: rescale factor per head
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const long unit = (long)blockIdx.x * 4 + wv;
+    if (unit >= (long)n_seqs * nkv * nchunks) return;
+    const int chunk = (int)(unit % nchunks);
+    const int kvh = (int)((unit / nchunks) % nkv);
+    const int b = (int)(unit / ((long)nchunks * nkv));
+    const int n_keys = lens[b] + 1;
+    const int j0 = chunk * kDecChunk;
+    if (j0 >= n_keys) return;
+    const int j1 = min(n_keys, j0 + kDecChunk);
+    const int width = (nq + 2 * nkv) * 128;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const float sc = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
+
+    // Q^T fragments: lane -> head column c16 (zero beyond the group), d = dblk*32 + g4*8 .. +8
+    u32x4_t qf[4];
+#pragma unroll
+    for (int dblk = 0; dblk < 4; ++dblk) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (c16 < G) v = *(const uint4 *)(qkv + (size_t)b * width + (size_t)(kvh * G + c16) * 128 + dblk * 32 + g4 * 8);
+        qf[dblk] = u32x4_t{v.x, v.y, v.z, v.w};
+    }
+    const uint4 *kb = kc + ((size_t)b * nkv + kvh) * cap * 16;   // 16 uint4 per cached row
+    const uint4 *vb = vc + ((size_t)b * nkv + kvh) * cap * 16 + lane;
+
+    float m_run = -INFINITY, l_run = 0.f;   // of head c16 (score layout)
+    float acc[G][8];                         // value layout: d = c16*8 .. +8, key row g4
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[g][c] = 0.f;
+
+    for (int jb = j0; jb < j1; jb += 32) {
+        uint4 kf[2][4], vv[8];
+#pragma unroll
+        for (int kt2 = 0; kt2 < 2; ++kt2) {
+            const int key = min(jb + kt2 * 16 + c16, j1 - 1);   // rows past the end are masked below
+#pragma unroll
+            for (int dblk = 0; dblk < 4; ++dblk) kf[kt2][dblk] = ld_stream(kb + (size_t)key * 16 + dblk * 4 + g4);
+        }
+#pragma unroll
+        for (int it = 0; it < 8; ++it)
+            vv[it] = (jb + it * 4 + g4 < j1) ? ld_stream(vb + (size_t)(jb + it * 4) * 16) : make_uint4(0, 0, 0, 0);
+
+        float x[2][4];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kt2 = 0; kt2 < 2; ++kt2) {
+            f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int dblk = 0; dblk < 4; ++dblk)
+                st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[kt2][dblk]),
+                                                             __builtin_bit_cast(bf16x8_t, qf[dblk]), st, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float v = (jb + kt2 * 16 + g4 * 4 + r < j1) ? st[r] * sc : -INFINITY;
+                x[kt2][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mn = fmaxf(m_run, mx);   // finite: key jb of this block is valid
+        const float alpha = exp2f(m_run - mn);
+        m_run = mn;
+        float ls = 0.f;
+#pragma unroll
+        for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float pv = exp2f(x[kt2][r] - mn);
+                ls += pv;
+                if (c16 < 8) pt[wv][kt2 * 16 + g4 * 4 + r][c16] = pv;
+            }
+        l_run = l_run * alpha + ls;
+        if (g4 == 0 && c16 < 8) al[wv][c16] = alpha;
+        __builtin_amdgcn_wave_barrier();   // same wavefront: LDS operations execute in program order
+
+        float a_g[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) a_g[g] = al[wv][g];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[g][c] *= a_g[g];
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const float v0 = bf_lo(vv[it].x), v1 = bf_hi(vv[it].x), v2 = bf_lo(vv[it].y), v3 = bf_hi(vv[it].y);
+            const float v4 = bf_lo(vv[it].z), v5 = bf_hi(vv[it].z), v6 = bf_lo(vv[it].w), v7 = bf_hi(vv[it].w);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float pv = pt[wv][it * 4 + g4][g];
+                acc[g][0] = fmaf(pv, v0, acc[g][0]); acc[g][1] = fmaf(pv, v1, acc[g][1]);
+                acc[g][2] = fmaf(pv, v2, acc[g][2]); acc[g][3] = fmaf(pv, v3, acc[g][3]);
+                acc[g][4] = fmaf(pv, v4, acc[g][4]); acc[g][5] = fmaf(pv, v5, acc[g][5]);
+                acc[g][6] = fmaf(pv, v6, acc[g][6]); acc[g][7] = fmaf(pv, v7, acc[g][7]);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    // the four key groups of a head hold partial sums of its probabilities; the four key rows of
+    // the value layout hold partial value sums: merge both with the fixed butterfly
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (g4 == 0 && c16 < G) {
+        float *p = part + (((size_t)b * nq + kvh * G + c16) * nchunks + chunk) * kDecPart;
+        p[0] = m_run;
+        p[1] = l_run;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            acc[g][c] += __shfl_xor(acc[g][c], 16, 64);
+            acc[g][c] += __shfl_xor(acc[g][c], 32, 64);
+        }
+        if (g4 == 0) {
+            float *p = part + (((size_t)b * nq + kvh * G + g) * nchunks + chunk) * kDecPart;
+            *(float4 *)(p + 4 + c16 * 8) = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
+            *(float4 *)(p + 8 + c16 * 8) = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
+        }
+    }
+}
+
 // Merge the chunk partials of one (sequence, head) in chunk order; thread c owns value c.
 __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restrict__ part,
                                                            bf16_t *__restrict__ out, int nq,
@@ -507,14 +648,18 @@ hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs,
 #define CCS_DEC(GV, ITV)                                                                                   \
     hipLaunchKernelGGL((attn_decode_kernel<GV, ITV>), grid, block, 0, st, (const bf16_t *)qkv, partials,   \
                        n_seqs, nq, nkv, lens_dev, (const uint4 *)k_cache, (const uint4 *)v_cache, cap, nchunks)
+#define CCS_GQA(GV)                                                                                        \
+    hipLaunchKernelGGL((attn_decode_gqa_kernel<GV>), grid, block, 0, st, (const bf16_t *)qkv, partials, n_seqs, \
+                       nq, nkv, lens_dev, (const uint4 *)k_cache, (const uint4 *)v_cache, cap, nchunks)
     switch (G) {
         case 1: CCS_DEC(1, 16); break;
-        case 2: CCS_DEC(2, 8); break;
-        case 4: CCS_DEC(4, 4); break;
-        case 8: CCS_DEC(8, 4); break;
+        case 2: CCS_GQA(2); break;
+        case 4: CCS_GQA(4); break;
+        case 8: CCS_GQA(8); break;
         default: return hipErrorInvalidValue;
     }
 #undef CCS_DEC
+#undef CCS_GQA
     return hipGetLastError();
 }
 

@@ -173,7 +173,9 @@ class Module:
         self.torch_dtype = torch.bfloat16 if desc.dtype == CCS_BF16 else torch.float32
         self.arenas = [self._alloc(self.arena_bytes)]
         self.workspaces = [self._alloc(self.ws_bytes)]
-        self.streams = [torch.cuda.Stream(device=self.device)]
+        # replica 0 lives on the stream that is current at creation: a replicated forward issued
+        # from that stream then needs no fork/join events for it (and none at all at k = 1)
+        self.streams = [torch.cuda.current_stream(self.device)]
         cw = ccs_weights()
         keep = []
         for name, t in weights.items():
@@ -183,8 +185,6 @@ class Module:
             setattr(cw, name, t.data_ptr())
         d = desc.c()
         h = ctypes.c_void_p()
-        # the weights may still be in flight on the current stream
-        self.streams[0].wait_stream(torch.cuda.current_stream(self.device))
         _check(self.L.ccs_module_create(ctypes.byref(d), ctypes.byref(cw), self.arenas[0].data_ptr(),
                                         self.workspaces[0].data_ptr(), self.ws_bytes,
                                         self.streams[0].cuda_stream, ctypes.byref(h)))

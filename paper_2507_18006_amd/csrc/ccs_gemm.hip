@@ -256,8 +256,13 @@ hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partia
 hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,
                                      int M, int N, int K, hipStream_t st)
 {
+    return launch_partial_reduce(partials, skinny_segments(N, K), epi, res, out, M, N, st);
+}
+
+hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, int M,
+                                 int N, hipStream_t st)
+{
     if (M <= 0) return hipSuccess;
-    const int S = skinny_segments(N, K);
     const int ncols = (epi == EPI_SWIGLU_PACKED) ? N / 2 : N;
     const int total = M * (ncols / 4);
     hipLaunchKernelGGL(skinny_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, partials, S, M, N,
@@ -327,17 +332,22 @@ __device__ __forceinline__ void dma_issue(const uint4 *const *src, size_t koff, 
 template <int BM, int NST>
 __global__ __launch_bounds__(256) void gemm_tiled_dma_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, int epi, const bf16_t *__restrict__ res,
-    bf16_t *__restrict__ out, int M, int N, int kfrags, int tiles_m)
+    bf16_t *__restrict__ out, int M, int N, int kfrags, int tiles_m, int tiles, float *__restrict__ part,
+    int kt_per_seg)
 {
     using C = DmaCfg<BM, NST>;
     extern __shared__ uint4 lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave & 1, wm = wave >> 1;
-    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    // K segment of this workgroup (one segment unless the launch is split over K: then the
+    // fp32 partial sums of segment `seg` go to part[seg][M][N] and a reduction kernel follows)
+    const int tile_id = blockIdx.x % tiles, seg = blockIdx.x / tiles;
+    const int tm = tile_id % tiles_m, tn = tile_id / tiles_m;
     const int nb0 = tn * C::TN, mb0 = tm * C::TM;
     const int nblk = N >> 4, mblk = (M + 15) >> 4;
-    const int ktiles = kfrags;
+    const int kt0 = seg * kt_per_seg;
+    const int ktiles = min(kfrags, kt0 + kt_per_seg) - kt0;
 
     // fragment f of a stage: f < TN -> weight block nb0 + f, else activation block mb0 + f - TN
     const uint4 *src[C::FPW];
@@ -346,7 +356,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_dma_kernel(
         const int f = wave * C::FPW + i;
         const bool is_x = f >= C::TN;
         const int blk = is_x ? min(mb0 + f - C::TN, mblk - 1) : min(nb0 + f, nblk - 1);
-        src[i] = (is_x ? Xp : Wp) + (size_t)blk * kfrags * 64 + lane;
+        src[i] = (is_x ? Xp : Wp) + ((size_t)blk * kfrags + kt0) * 64 + lane;
     }
     constexpr int KSTEP = 64;  // uint4 per k-tile along one block row
     // (a __device__ helper, not a lambda: the host pass cannot instantiate a lambda that holds the
@@ -449,7 +459,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_dma_kernel(
     // (packed output): 16 bytes per lane, fully coalesced.
     __syncthreads();  // every wavefront's loads have landed: the stages can be reused
     const int mlane = lane & 31, nsub = (lane >> 5) * 4;
-    if (epi == EPI_STORE_RM) {
+    if (epi == EPI_STORE_RM || part != nullptr) {
         constexpr int ROWB = 128 * 4 + 16;  // padded fp32 row: 16 lanes x 16 B hit 64 different banks
         char *reg = (char *)lds + wave * (32 * ROWB);
         const int n_wave = (nb0 + wn * 8) * 16;  // first output column of this wavefront
@@ -468,7 +478,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_dma_kernel(
                 const int row = rr * 4 + (lane >> 4), m = m0 + row;
                 const float4 lo = *(const float4 *)(reg + row * ROWB + (lane & 15) * 32);
                 const float4 hi = *(const float4 *)(reg + row * ROWB + (lane & 15) * 32 + 16);
-                if (m < M && n < N) {
+                if (m < M && n < N && part != nullptr) {
+                    float *o = part + ((size_t)seg * M + m) * N + n;
+                    *(float4 *)o = lo;
+                    *(float4 *)(o + 4) = hi;
+                } else if (m < M && n < N) {
                     const size_t o = (size_t)m * N + n;
                     float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                     if (res) {
@@ -517,7 +531,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_dma_kernel(
 
 template <int BM, int NST>
 hipError_t launch_gemm_tiled_dma(const void *Wp, const void *Xp, int epi, const void *res, void *out,
-                                 int M, int N, int K, hipStream_t st)
+                                 int M, int N, int K, float *part, int S, hipStream_t st)
 {
     using C = DmaCfg<BM, NST>;
     static bool attr_done = false;
@@ -528,24 +542,58 @@ hipError_t launch_gemm_tiled_dma(const void *Wp, const void *Xp, int epi, const 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + 255) / 256;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), C::LDS_BYTES, st, (const uint4 *)Wp,
-                       (const uint4 *)Xp, epi, (const bf16_t *)res, (bf16_t *)out, M, N, K / 32, tiles_m);
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + 255) / 256, tiles = tiles_m * tiles_n;
+    const int kfrags = K / 32, per = (kfrags + S - 1) / S;
+    hipLaunchKernelGGL(kern, dim3(tiles * S), dim3(256), C::LDS_BYTES, st, (const uint4 *)Wp, (const uint4 *)Xp, epi,
+                       (const bf16_t *)res, (bf16_t *)out, M, N, kfrags, tiles_m, tiles, part, per);
     return hipGetLastError();
 }
 
+// K segments of the LDS-tiled GEMM: 1 when the launch fills the GPU; otherwise (few hundred rows
+// against a narrow weight: fewer than 192 workgroup tiles) K is cut to fill whole rounds of CUs.
+// The count is taken from the row count of the FULL batch (variant_rows), never from the slice a
+// replica gets, so every replica count reduces in the same order.
+int tiled_segments(int N, int K, long variant_rows)
+{
+    const long tiles = (long)((N + 255) / 256) * ((variant_rows + 127) / 128);
+    if (tiles >= 192) return 1;
+    const int kfrags = K / 32;
+    // rounds of 256 one-per-CU workgroups, each 1/S of the K loop, plus what the split costs (a
+    // second launch, S partial buffers written and read back)
+    int best = 1;
+    double best_cost = (double)((tiles + 255) / 256);
+    for (int S = 2; S <= 8 && S <= kfrags / 16; ++S) {
+        const double cost = (double)((tiles * S + 255) / 256) / S + 0.08 + 0.02 * (S - 1);
+        if (cost < best_cost) { best_cost = cost; best = S; }
+    }
+    const int per = (kfrags + best - 1) / best;
+    return (kfrags + per - 1) / per;
+}
+
+size_t tiled_partial_bytes(int M, int N, int K, long variant_rows)
+{
+    const int S = tiled_segments(N, K, variant_rows);
+    return S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
+}
+
 hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void *res, void *out,
-                             int M, int N, int K, hipStream_t st)
+                             int M, int N, int K, long variant_rows, float *partials, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
+    const int S = tiled_segments(N, K, variant_rows);
+    if (S > 1) {
+        hipError_t e = launch_gemm_tiled_dma<128, 6>(Wp, Xp, epi, nullptr, nullptr, M, N, K, partials, S, st);
+        if (e != hipSuccess) return e;
+        return launch_partial_reduce(partials, S, epi, res, out, M, N, st);
+    }
     // Tile height by whole rounds of workgroups on 256 CUs (one workgroup per CU): a 128-row tile
     // runs at ~0.93 of the 256-row tile's rate but wastes less of the last round.  Either choice
     // walks K in the same order with the same instruction for every output element, so the bits
     // do not depend on it.
     const long tn = (N + 255) / 256;
     const long r256 = (tn * ((M + 255) / 256) + 255) / 256, r128 = (tn * ((M + 127) / 128) + 255) / 256;
-    if (r128 * 108 < r256 * 200) return launch_gemm_tiled_dma<128, 6>(Wp, Xp, epi, res, out, M, N, K, st);
-    return launch_gemm_tiled_dma<256, 5>(Wp, Xp, epi, res, out, M, N, K, st);
+    if (r128 * 108 < r256 * 200) return launch_gemm_tiled_dma<128, 6>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, st);
+    return launch_gemm_tiled_dma<256, 5>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, st);
 }
 
 }  // namespace ccs

@@ -71,9 +71,17 @@ hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partia
                                    int K, hipStream_t st);
 hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,
                                      int M, int N, int K, hipStream_t st);
-// bf16 LDS-tiled MFMA GEMM for any M; Xp must be readable up to M rounded up to 256 rows.
+// Fixed-order sum of S partial buffers (fp32 [S, M, N]) + epilogue; used by both GEMM variants.
+hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, int M,
+                                 int N, hipStream_t st);
+// bf16 LDS-tiled MFMA GEMM for any M (Xp readable up to M rounded up to 16 rows).  When the batch
+// is too small to fill the GPU, K is cut into tiled_segments(N, K, variant_rows) segments whose
+// partial sums go through `partials` (tiled_partial_bytes) and launch_partial_reduce;
+// variant_rows is the row count of the full batch the launch belongs to.
+int tiled_segments(int N, int K, long variant_rows);
+size_t tiled_partial_bytes(int M, int N, int K, long variant_rows);
 hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void *res, void *out,
-                             int M, int N, int K, hipStream_t st);
+                             int M, int N, int K, long variant_rows, float *partials, hipStream_t st);
 
 // ---- attention (ccs_attention.hip) ---------------------------------------------------------
 // Generic (slow, any head_dim <= 256) softmax attention: one wavefront per query row.

@@ -105,9 +105,11 @@ inline size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 
 // Scratch one forward over `rows` rows (n_seqs sequences, caches of `cap` slots) needs.
 // `skinny`: the weight-streaming GEMM variant is in use (rows <= kSkinnyMaxRows).
+// `vrows`: row count of the full batch (selects the K split of the LDS-tiled GEMM).
 WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs, int cap, bool skinny,
-               bool decode, int prefill_seq_pad = 0)
+               bool decode, int prefill_seq_pad = 0, long vrows = -1)
 {
+    if (vrows < 0) vrows = (long)rows;
     WsPlan p{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -115,7 +117,8 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
     if (D->kind == CCS_LINEAR) {
         if (D->dtype == CCS_BF16) {
             p.xp = take(r16 * d.in_f * 2);
-            p.scratch_bytes = skinny ? ccs::skinny_partial_bytes((int)rows, d.out_f, d.in_f) : 0;
+            p.scratch_bytes = skinny ? ccs::skinny_partial_bytes((int)rows, d.out_f, d.in_f)
+                                     : ccs::tiled_partial_bytes((int)rows, d.out_f, d.in_f, vrows);
             p.scratch = take(p.scratch_bytes);
         }
     } else if (D->dtype == CCS_BF16) {
@@ -135,6 +138,11 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.QD));
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, 2 * d.I, d.H));
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.I));
+        } else {
+            s = max_sz(s, ccs::tiled_partial_bytes((int)rows, d.W3, d.H, vrows));
+            s = max_sz(s, ccs::tiled_partial_bytes((int)rows, d.H, d.QD, vrows));
+            s = max_sz(s, ccs::tiled_partial_bytes((int)rows, 2 * d.I, d.H, vrows));
+            s = max_sz(s, ccs::tiled_partial_bytes((int)rows, d.H, d.I, vrows));
         }
         if (decode) s = max_sz(s, ccs::attn_decode_partial_bytes(n_seqs, d.nq, cap));
         p.scratch_bytes = s;
@@ -295,14 +303,14 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)b->x, (const float *)(A + m->ap.w), nullptr, (float *)b->y, M, d.out_f, d.in_f, st));
             return CCS_OK;
         }
-        WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false);
+        WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false, 0, (long)variant_rows);
         if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
         CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, st));
         if (skinny) {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, st));
             CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_gemm_skinny_reduce((const float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
         } else {
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, (long)variant_rows, (float *)(ws + p.scratch), st));
         }
         return CCS_OK;
     }
@@ -310,7 +318,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     const bool decode = b->mode == CCS_DECODE;
     const int seq_pad = decode ? 1 : b->seq_pad;
     const int T = b->n_seqs * seq_pad;
-    WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, decode ? 0 : seq_pad);
+    WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, decode ? 0 : seq_pad, (long)variant_rows);
     if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
 
@@ -329,7 +337,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             CCS_STAGE(sid, launch_gemm_skinny_main(A + (woff), ws + (xoff), scratch, T, (N), (K), st));        \
             CCS_STAGE((sid) + 1, launch_gemm_skinny_reduce(scratch, (epi), (res), (out), T, (N), (K), st));    \
         } else {                                                                                              \
-            CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), st));  \
+            CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st)); \
         }                                                                                                     \
     } while (0)
         if (skinny && decode) {
@@ -403,6 +411,11 @@ size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
     // cover every plan a batch within these limits can take: prefill (max_seq_pad rows per
     // sequence), decode (one row per sequence, when a cache size is given), either GEMM variant
     size_t need = ws_plan(desc, d, rows, max_seqs, max_cache_cap, skinny, false, layer ? max_seq_pad : 0).total;
+    // smaller batches may split K in the tiled GEMM: the partial buffer grows with the split
+    for (size_t v = 128; v < rows && v <= 4096; v += 128) {
+        const int seqs_v = (int)((v + max_seq_pad - 1) / max_seq_pad);
+        need = max_sz(need, ws_plan(desc, d, v, seqs_v, max_cache_cap, false, false, layer ? max_seq_pad : 0).total);
+    }
     if (!skinny) {
         const int small_seqs = max_seqs < ccs::kSkinnyMaxRows ? max_seqs : ccs::kSkinnyMaxRows;
         need = max_sz(need, ws_plan(desc, d, ccs::kSkinnyMaxRows, small_seqs, max_cache_cap, true, false, layer ? 64 : 0).total);

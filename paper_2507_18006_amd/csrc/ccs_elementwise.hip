@@ -200,59 +200,90 @@ __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, i
 //       of d); lane = d % 16 + 16 * ((key % 16) / 4) holds 8 keys: slots 0..3 = keys
 //       (key % 16) / 4 * 4 + 0..3 of the first 16 keys of the block, slots 4..7 the same of the
 //       second 16 - the order in which the score accumulators of that kernel hold them.
-// Grid: n_seqs * S32 blocks (S32 = seq_pad rounded up to 32); positions >= seq_pad only zero
-// their slots (so that masked products stay finite).  Optionally fills the row-major caches.
-__global__ __launch_bounds__(64) void rope_pack_prefill_kernel(
+// One workgroup = (sequence, block of 32 positions, group of 8 head slots); thread = (position,
+// 8 consecutive d of the first half + their partners 64 up), so every global access is 16 bytes:
+// q in place, K straight into packed chunks, V through a 32 x 128 LDS tile that is read back
+// transposed.  Positions >= seq_pad (S32 = seq_pad rounded up to 32) write zeros, so that
+// masked products stay finite.  Optionally fills the row-major caches.
+constexpr int kRopeHeadsPerGroup = 8;
+
+__global__ __launch_bounds__(256) void rope_pack_prefill_kernel(
     bf16_t *__restrict__ qkv, bf16_t *__restrict__ kp, bf16_t *__restrict__ vtp, int nq, int nkv,
-    const float2 *__restrict__ tab, int seq_pad, int S32, const int32_t *__restrict__ lens, bf16_t *__restrict__ k_cache,
-    bf16_t *__restrict__ v_cache, int cap)
+    const float2 *__restrict__ tab, int seq_pad, int S32, int groups, const int32_t *__restrict__ lens,
+    bf16_t *__restrict__ k_cache, bf16_t *__restrict__ v_cache, int cap)
 {
-    const int seq = blockIdx.x / S32, pos = blockIdx.x % S32;
-    const int i = threadIdx.x;  // pair (i, i + 64)
-    const int kb = pos >> 5, kk = pos & 31;
+    __shared__ bf16_t vt[32][128 + 2];
+    const int blocks_per_seq = (S32 >> 5) * groups;
+    const int seq = blockIdx.x / blocks_per_seq, rem = blockIdx.x % blocks_per_seq;
+    const int kb = rem / groups, hg = rem % groups;
+    const int tid = threadIdx.x, pl = tid >> 3, c = tid & 7;
+    const int pos = kb * 32 + pl;
+    const bool valid = pos < seq_pad;
+    const bool store = valid && (k_cache != nullptr) && (pos < lens[seq]) && (pos < cap);
+    const int slots = nq + 2 * nkv, width = slots * 128;
+    const int h_lo = hg * kRopeHeadsPerGroup, h_hi = min(slots, h_lo + kRopeHeadsPerGroup);
     const size_t head_elems = (size_t)S32 * 128;
-    auto kp_at = [&](int h, int dd) { return kp + ((size_t)seq * nkv + h) * head_elems + packed_index(pos, dd, 4); };
-    auto vt_at = [&](int h, int dd) {
-        return vtp + ((size_t)seq * nkv + h) * head_elems +
-               ((((size_t)kb * 8 + (dd >> 4)) * 64) + (dd & 15) + 16 * ((kk & 15) >> 2)) * 8 + (kk >> 4) * 4 + (kk & 3);
-    };
-    if (pos >= seq_pad) {
-        for (int h = 0; h < nkv; ++h) {
-            *kp_at(h, i) = 0; *kp_at(h, i + 64) = 0;
-            *vt_at(h, i) = 0; *vt_at(h, i + 64) = 0;
-        }
-        return;
+    bf16_t *row = qkv + ((size_t)seq * seq_pad + (valid ? pos : 0)) * width;
+
+    float cs[8], sn[8];
+    if (h_lo < nq + nkv) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) rope_cs(tab, c * 8 + e, pos, cs[e], sn[e]);
     }
-    const int width = (nq + 2 * nkv) * 128;
-    bf16_t *r = qkv + ((size_t)seq * seq_pad + pos) * width;
-    const bool store = (k_cache != nullptr) && (pos < lens[seq]) && (pos < cap);
-    float c, s;
-    rope_cs(tab, i, pos, c, s);
-    for (int h = 0; h < nq + nkv; ++h) {
-        bf16_t *z = r + (size_t)h * 128;
-        const float a = bf2f(z[i]), b = bf2f(z[i + 64]);
-        const bf16_t ra = f2bf(a * c - b * s), rb = f2bf(b * c + a * s);
-        z[i] = ra;
-        z[i + 64] = rb;
-        if (h >= nq) {
-            *kp_at(h - nq, i) = ra;
-            *kp_at(h - nq, i + 64) = rb;
-            if (store) {
-                bf16_t *kc = k_cache + (((size_t)seq * nkv + (h - nq)) * cap + pos) * 128;
-                kc[i] = ra;
-                kc[i + 64] = rb;
+    for (int hs = h_lo; hs < h_hi; ++hs) {
+        bf16_t *z = row + (size_t)hs * 128 + c * 8;
+        uint4 lo = make_uint4(0, 0, 0, 0), hi = make_uint4(0, 0, 0, 0);
+        if (valid) { lo = *(const uint4 *)z; hi = *(const uint4 *)(z + 64); }
+        if (hs < nq + nkv) {
+            const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+            uint32_t ol[4], oh[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float a0 = bf_lo(lw[j]), b0 = bf_lo(hw[j]), a1 = bf_hi(lw[j]), b1 = bf_hi(hw[j]);
+                ol[j] = pack2bf(a0 * cs[2 * j] - b0 * sn[2 * j], a1 * cs[2 * j + 1] - b1 * sn[2 * j + 1]);
+                oh[j] = pack2bf(b0 * cs[2 * j] + a0 * sn[2 * j], b1 * cs[2 * j + 1] + a1 * sn[2 * j + 1]);
             }
-        }
-    }
-    for (int h = 0; h < nkv; ++h) {
-        const bf16_t *v = r + (size_t)(nq + nkv + h) * 128;
-        const bf16_t v0 = v[i], v1 = v[i + 64];
-        *vt_at(h, i) = v0;
-        *vt_at(h, i + 64) = v1;
-        if (store) {
-            bf16_t *vc = v_cache + (((size_t)seq * nkv + h) * cap + pos) * 128;
-            vc[i] = v0;
-            vc[i + 64] = v1;
+            lo = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+            hi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+            if (hs < nq) {
+                if (valid) { *(uint4 *)z = lo; *(uint4 *)(z + 64) = hi; }
+            } else {
+                bf16_t *kh = kp + ((size_t)seq * nkv + (hs - nq)) * head_elems;
+                *(uint4 *)(kh + packed_index(pos, c * 8, 4)) = lo;
+                *(uint4 *)(kh + packed_index(pos, 64 + c * 8, 4)) = hi;
+                if (store) {
+                    bf16_t *kc = k_cache + (((size_t)seq * nkv + (hs - nq)) * cap + pos) * 128 + c * 8;
+                    *(uint4 *)kc = lo;
+                    *(uint4 *)(kc + 64) = hi;
+                }
+            }
+        } else {
+            const int vh = hs - nq - nkv;
+            if (store) {
+                bf16_t *vc = v_cache + (((size_t)seq * nkv + vh) * cap + pos) * 128 + c * 8;
+                *(uint4 *)vc = lo;
+                *(uint4 *)(vc + 64) = hi;
+            }
+            __syncthreads();  // previous head's tile fully read
+            {
+                uint32_t *d0 = (uint32_t *)&vt[pl][c * 8], *d1 = (uint32_t *)&vt[pl][64 + c * 8];
+                d0[0] = lo.x; d0[1] = lo.y; d0[2] = lo.z; d0[3] = lo.w;
+                d1[0] = hi.x; d1[1] = hi.y; d1[2] = hi.z; d1[3] = hi.w;
+            }
+            __syncthreads();
+            uint4 *vth = (uint4 *)(vtp + ((size_t)seq * nkv + vh) * head_elems) + (size_t)kb * 8 * 64;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int q2 = tid + 256 * j, dt = q2 >> 6, ln = q2 & 63;
+                const int dd = dt * 16 + (ln & 15), g = ln >> 4;
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k0 = (e >> 1) * 16 + g * 4 + (e & 1) * 2;   // slots 2e, 2e+1
+                    w[e] = (uint32_t)vt[k0][dd] | ((uint32_t)vt[k0 + 1][dd] << 16);
+                }
+                vth[dt * 64 + ln] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
         }
     }
 }
@@ -263,8 +294,10 @@ hipError_t launch_rope_pack_prefill(void *qkv, void *kp, void *vtp, int n_seqs, 
 {
     if (n_seqs <= 0) return hipSuccess;
     const int S32 = (seq_pad + 31) / 32 * 32;
-    hipLaunchKernelGGL(rope_pack_prefill_kernel, dim3(n_seqs * S32), dim3(64), 0, st, (bf16_t *)qkv, (bf16_t *)kp,
-                       (bf16_t *)vtp, nq, nkv, (const float2 *)tab, seq_pad, S32, lens_dev, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
+    const int groups = (nq + 2 * nkv + kRopeHeadsPerGroup - 1) / kRopeHeadsPerGroup;
+    hipLaunchKernelGGL(rope_pack_prefill_kernel, dim3(n_seqs * (S32 / 32) * groups), dim3(256), 0, st, (bf16_t *)qkv,
+                       (bf16_t *)kp, (bf16_t *)vtp, nq, nkv, (const float2 *)tab, seq_pad, S32, groups, lens_dev,
+                       (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
     return hipGetLastError();
 }
 

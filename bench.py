@@ -167,7 +167,7 @@ def bench_layer(args, name):
     else:
         N, Kd = shapes[dominant]
         fl = 2.0 * rows * N * Kd
-        roof = {"kernel": "gemm_tiled_kernel (gate/up + SwiGLU)", "bound": "mfma",
+        roof = {"kernel": "gemm_tiled_dma_kernel<128,3> (gate/up + SwiGLU)", "bound": "mfma",
                 "achieved": round(fl / dom_s / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(fl / dom_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(name),
                 "algorithmic_flops_per_launch": fl, "rows_executed": rows, "rows_valid": n_tok}

@@ -275,8 +275,9 @@ hipError_t launch_partial_reduce(const float *partials, int S, int epi, const vo
 // =============================================================================================
 // ---------------------------------------------------------------------------------------------
 // Main prefill GEMM: 256 (weight rows) x BM (activation rows, 256 or 128) x 32 (k) workgroup
-// tile, 4 wavefronts (2 x 2), one per SIMD, each owning 128 x BM/2 outputs as accumulator tiles
-// of v_mfma_f32_32x32x16_bf16 (256 or 128 accumulator registers).
+// tile, 4 wavefronts (2 x 2), each owning 128 x BM/2 outputs as accumulator tiles of
+// v_mfma_f32_32x32x16_bf16 (256 or 128 accumulator registers).  The shipped configuration is
+// BM = 128 with a 3-stage ring, which fits two workgroups (two wavefronts per SIMD) on a CU.
 //
 // Packed fragments go global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4: one
 // instruction moves one 1 KiB fragment; no staging registers, no ds_write) into a ring of NST
@@ -330,7 +331,7 @@ __device__ __forceinline__ void dma_issue(const uint4 *const *src, size_t koff, 
 }
 
 template <int BM, int NST>
-__global__ __launch_bounds__(256) void gemm_tiled_dma_kernel(
+__global__ __launch_bounds__(256, (BM == 128 && NST <= 3) ? 2 : 1) void gemm_tiled_dma_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, int epi, const bf16_t *__restrict__ res,
     bf16_t *__restrict__ out, int M, int N, int kfrags, int tiles_m, int tiles, float *__restrict__ part,
     int kt_per_seg)
@@ -582,18 +583,14 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
     if (M <= 0) return hipSuccess;
     const int S = tiled_segments(N, K, variant_rows);
     if (S > 1) {
-        hipError_t e = launch_gemm_tiled_dma<128, 6>(Wp, Xp, epi, nullptr, nullptr, M, N, K, partials, S, st);
+        hipError_t e = launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, nullptr, nullptr, M, N, K, partials, S, st);
         if (e != hipSuccess) return e;
         return launch_partial_reduce(partials, S, epi, res, out, M, N, st);
     }
-    // Tile height by whole rounds of workgroups on 256 CUs (one workgroup per CU): a 128-row tile
-    // runs at ~0.93 of the 256-row tile's rate but wastes less of the last round.  Either choice
-    // walks K in the same order with the same instruction for every output element, so the bits
-    // do not depend on it.
-    const long tn = (N + 255) / 256;
-    const long r256 = (tn * ((M + 255) / 256) + 255) / 256, r128 = (tn * ((M + 127) / 128) + 255) / 256;
-    if (r128 * 108 < r256 * 200) return launch_gemm_tiled_dma<128, 6>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, st);
-    return launch_gemm_tiled_dma<256, 5>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, st);
+    // 256 x 128 tiles, 3-stage ring (72 KiB): two workgroups share a CU, so one's epilogue and
+    // prologue run under the other's main loop - measured 5-20 % faster than one 256 x 256 or
+    // 256 x 128 workgroup per CU with a deeper ring on every projection shape of the 13B layer.
+    return launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, st);
 }
 
 }  // namespace ccs

@@ -159,7 +159,7 @@ def bench_layer(args, name):
     m.destroy()
 
     if decode:
-        roof = {"kernel": "attn_decode_kernel", "bound": "hbm",
+        roof = {"kernel": "attn_decode_mfma_kernel", "bound": "hbm",
                 "achieved": round(kv_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(kv_bytes / dom_s / 1e9 / HBM_PEAK_GBPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(name),

@@ -348,153 +348,137 @@ size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap)
     return (size_t)n_seqs * nq * dec_chunks(cap) * kDecPart * sizeof(float);
 }
 
-__device__ __forceinline__ float row16_sum(float v)
+// ---------------------------------------------------------------------------------------------
+// Decode attention with both products on the matrix cores (any group size G <= 8).
+// One wavefront = one (sequence, kv head, chunk of kDecChunk keys); it serves the G query heads of
+// the group at once, so K and V are read exactly once.  Scores are computed transposed, as in the
+// prefill kernel: S^T[key][head] = K Q^T with 16 cached K rows x 32 d read straight from the
+// row-major cache as the A operand and the group's query heads as the B columns (columns >= G
+// are zero), so an accumulator lane owns ONE head and 4 keys per 16-key tile and the softmax
+// statistics (log2 domain, running maximum and sum) stay per lane.  Each chunk writes a partial
+// (max, sum, 128 unnormalised values) per head; attn_combine_kernel merges them in chunk order.
+// The value product needs V^T as an operand - for a fixed d, 8 consecutive KEYS per lane - while
+// the cache holds rows of d: the 32 x 128 block of V goes global -> LDS with direct-to-LDS loads
+// (row-major, 16-byte pieces XOR-swizzled by the row so that the reads below touch every bank
+// twice, the minimum) and comes back transposed with ds_read_b64_tr_b16: inside each group of 16
+// lanes lane i supplies the address of 4 values (row i/4, columns 4(i%4)..) and lane j receives
+// column j of those 4 rows.  With rows 4g..4g+3 (then 16+4g..) for lane group g this is exactly
+// the A operand of O^T[d][head] += V^T P^T whose 8 contraction slots of group g are the keys
+// 4g..4g+3, 16+4g..16+4g+3 - the keys whose scores the same lanes already hold, so P^T is built
+// in registers, the rescale factor is a per-lane scalar and nothing but V crosses LDS.
+// A wavefront owns one (sequence, kv head, chunk) and a private double buffer (2 x 8 KiB): the
+// loads of block i + 1 (K to registers, V to LDS) are in flight while block i is multiplied.
+// No load is outstanding when the loop ends (each block waits for its successor's loads).
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void dm_issue_v(const uint4 *__restrict__ vrow, int jb, int j1, int lane, uint4 *stage)
 {
-    v += __shfl_xor(v, 1, 64);
-    v += __shfl_xor(v, 2, 64);
-    v += __shfl_xor(v, 4, 64);
-    v += __shfl_xor(v, 8, 64);
-    return v;
-}
-
-template <int G, int IT>
-__global__ __launch_bounds__(256) void attn_decode_kernel(
-    const bf16_t *__restrict__ qkv, float *__restrict__ part, int n_seqs, int nq, int nkv,
-    const int32_t *__restrict__ lens, const uint4 *__restrict__ kc, const uint4 *__restrict__ vc, int cap,
-    int nchunks)
-{
-    const int lane = threadIdx.x & 63;
-    const long unit = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (unit >= (long)n_seqs * nkv * nchunks) return;
-    const int chunk = (int)(unit % nchunks);
-    const int kvh = (int)((unit / nchunks) % nkv);
-    const int b = (int)(unit / ((long)nchunks * nkv));
-    const int n_keys = lens[b] + 1;
-    const int j0 = chunk * kDecChunk;
-    if (j0 >= n_keys) return;
-    const int j1 = min(n_keys, j0 + kDecChunk);
-    const int width = (nq + 2 * nkv) * 128;
-    const int dpart = lane & 15, krow = lane >> 4;
-    // softmax in the log2 domain: s' = (q.k) * log2(e)/sqrt(128)
-    const float qscale = 1.4426950408889634f * 0.08838834764831845f;
-
-    float q[G][8];
+    // instruction t fills LDS rows 4t..4t+3 of the stage: lane -> row 4t + lane/16, piece lane%16,
+    // which holds global piece (lane%16) ^ (2 * (row % 8))
+    const int r4 = lane >> 4, pc = lane & 15;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const uint4 v = *(const uint4 *)(qkv + (size_t)b * width + (size_t)(kvh * G + g) * 128 + dpart * 8);
-        q[g][0] = bf_lo(v.x) * qscale; q[g][1] = bf_hi(v.x) * qscale;
-        q[g][2] = bf_lo(v.y) * qscale; q[g][3] = bf_hi(v.y) * qscale;
-        q[g][4] = bf_lo(v.z) * qscale; q[g][5] = bf_hi(v.z) * qscale;
-        q[g][6] = bf_lo(v.w) * qscale; q[g][7] = bf_hi(v.w) * qscale;
-    }
-    const uint4 *kb = kc + ((size_t)b * nkv + kvh) * cap * 16 + lane;
-    const uint4 *vb = vc + ((size_t)b * nkv + kvh) * cap * 16 + lane;
-
-    float m[G], l[G], acc[G][8];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        m[g] = -INFINITY;
-        l[g] = 0.f;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[g][c] = 0.f;
-    }
-
-    for (int jb = j0; jb < j1; jb += 4 * IT) {
-        uint4 kk[IT], vv[IT];
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const int j = jb + it * 4 + krow;
-            kk[it] = (j < j1) ? ld_stream(kb + (size_t)(jb + it * 4) * 16) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const int j = jb + it * 4 + krow;
-            vv[it] = (j < j1) ? ld_stream(vb + (size_t)(jb + it * 4) * 16) : make_uint4(0, 0, 0, 0);
-        }
-        float s[IT][G];
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const float k0 = bf_lo(kk[it].x), k1 = bf_hi(kk[it].x), k2 = bf_lo(kk[it].y), k3 = bf_hi(kk[it].y);
-            const float k4 = bf_lo(kk[it].z), k5 = bf_hi(kk[it].z), k6 = bf_lo(kk[it].w), k7 = bf_hi(kk[it].w);
-            const bool valid = (jb + it * 4 + krow) < j1;
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float a = q[g][0] * k0;
-                a = fmaf(q[g][1], k1, a); a = fmaf(q[g][2], k2, a); a = fmaf(q[g][3], k3, a);
-                a = fmaf(q[g][4], k4, a); a = fmaf(q[g][5], k5, a); a = fmaf(q[g][6], k6, a);
-                a = fmaf(q[g][7], k7, a);
-                a = row16_sum(a);
-                s[it][g] = valid ? a : -INFINITY;
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float mb = s[0][g];
-#pragma unroll
-            for (int it = 1; it < IT; ++it) mb = fmaxf(mb, s[it][g]);
-            mb = fmaxf(mb, __shfl_xor(mb, 16, 64));
-            mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
-            const float mn = fmaxf(m[g], mb);  // finite: this sub-block holds at least one valid key
-            const float alpha = exp2f(m[g] - mn);
-            m[g] = mn;
-            l[g] *= alpha;
-#pragma unroll
-            for (int c = 0; c < 8; ++c) acc[g][c] *= alpha;
-#pragma unroll
-            for (int it = 0; it < IT; ++it) s[it][g] = exp2f(s[it][g] - mn);
-        }
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const float v0 = bf_lo(vv[it].x), v1 = bf_hi(vv[it].x), v2 = bf_lo(vv[it].y), v3 = bf_hi(vv[it].y);
-            const float v4 = bf_lo(vv[it].z), v5 = bf_hi(vv[it].z), v6 = bf_lo(vv[it].w), v7 = bf_hi(vv[it].w);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float p = s[it][g];
-                l[g] += p;
-                acc[g][0] = fmaf(p, v0, acc[g][0]); acc[g][1] = fmaf(p, v1, acc[g][1]);
-                acc[g][2] = fmaf(p, v2, acc[g][2]); acc[g][3] = fmaf(p, v3, acc[g][3]);
-                acc[g][4] = fmaf(p, v4, acc[g][4]); acc[g][5] = fmaf(p, v5, acc[g][5]);
-                acc[g][6] = fmaf(p, v6, acc[g][6]); acc[g][7] = fmaf(p, v7, acc[g][7]);
-            }
-        }
-    }
-    // merge the four key rows of the wavefront (fixed butterfly), then lanes 0..15 hold the chunk result
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        l[g] += __shfl_xor(l[g], 16, 64);
-        l[g] += __shfl_xor(l[g], 32, 64);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            acc[g][c] += __shfl_xor(acc[g][c], 16, 64);
-            acc[g][c] += __shfl_xor(acc[g][c], 32, 64);
-        }
-        if (krow == 0) {
-            float *p = part + (((size_t)b * nq + kvh * G + g) * nchunks + chunk) * kDecPart;
-            if (dpart == 0) { p[0] = m[g]; p[1] = l[g]; }
-            *(float4 *)(p + 4 + dpart * 8) = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
-            *(float4 *)(p + 8 + dpart * 8) = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
-        }
+    for (int t = 0; t < 8; ++t) {
+        const int R = 4 * t + r4;
+        const int c = pc ^ (((4 * (t & 1)) + r4) << 1);
+        const int row = min(jb + R, j1 - 1);   // rows past the end repeat the last key (weight 0)
+        __builtin_amdgcn_global_load_lds(vrow + (size_t)row * 16 + c, stage + t * 64, 16, 0, 0);
     }
 }
 
-// Grouped-query variant (G = 2, 4, 8 query heads per kv head).  With G heads the all-VALU kernel
-// above spends G x (8 FMA + a 16-lane reduction) per key on the scores alone and falls far below
-// the HBM rate; here the scores go to the matrix cores in the transposed form of the prefill
-// kernel - S^T[key][head] = K Q^T with the cached K rows as the A operand (16 keys x 32 d read
-// straight from the row-major cache) and the group's query heads as the B columns - so a lane
-// owns one head and 4 keys per 16-key tile and the softmax statistics stay per lane.  The
-// probabilities and rescale factors cross to the value layout (16 lanes per key row, fully
-// coalesced V loads as above) through a 1 KiB wavefront-private LDS tile; P V stays on the VALU,
-// where it is G x 8 FMAs per 16 bytes of V.  Same chunking and partial format as above.
+// K rows go to registers with hand-issued loads and hand-placed waits: left to the compiler, the
+// wait for them lands behind the loads of the next block (it waits for everything outstanding).
+__device__ __forceinline__ void dm_load_k(const uint4 *__restrict__ krow, int jb, int j1, int c16, int g4,
+                                          u32x4_t (&kf)[2][4])
+{
+#pragma unroll
+    for (int kt2 = 0; kt2 < 2; ++kt2) {
+        const int key = min(jb + kt2 * 16 + c16, j1 - 1);   // rows past the end are masked by the caller
+        const uint4 *p = krow + (size_t)key * 16 + g4;
+        asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(kf[kt2][0]) : "v"(p) : "memory");
+        asm volatile("global_load_dwordx4 %0, %1, off offset:64 nt" : "=v"(kf[kt2][1]) : "v"(p) : "memory");
+        asm volatile("global_load_dwordx4 %0, %1, off offset:128 nt" : "=v"(kf[kt2][2]) : "v"(p) : "memory");
+        asm volatile("global_load_dwordx4 %0, %1, off offset:192 nt" : "=v"(kf[kt2][3]) : "v"(p) : "memory");
+    }
+}
+
+// everything this wavefront has in flight (K registers named here, V in LDS) has landed
+__device__ __forceinline__ void dm_wait_all(u32x4_t (&kf)[2][4])
+{
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(kf[0][0]), "+v"(kf[0][1]), "+v"(kf[0][2]), "+v"(kf[0][3]), "+v"(kf[1][0]), "+v"(kf[1][1]),
+                   "+v"(kf[1][2]), "+v"(kf[1][3])::"memory");
+}
+
+#define DM_TR(dst, addr, OFF) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(OFF) : "memory")
+
+template <int STAGE>
+__device__ __forceinline__ void dm_block(const u32x4_t (&kf)[2][4], const u32x4_t (&qf)[4], const uint32_t (&vaddr)[8],
+                                         int jb, int j1, int g4, float sc, float &m_run, float &l_run,
+                                         f32x4_t (&o)[8])
+{
+    u32x2_t va[8][2];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        DM_TR(va[dt][0], vaddr[dt], STAGE * 8192);
+        DM_TR(va[dt][1], vaddr[dt], STAGE * 8192 + 4096);
+    }
+    float x[2][4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt2 = 0; kt2 < 2; ++kt2) {
+        f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk)
+            st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[kt2][dblk]),
+                                                         __builtin_bit_cast(bf16x8_t, qf[dblk]), st, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float v = (jb + kt2 * 16 + g4 * 4 + r < j1) ? st[r] * sc : -INFINITY;
+            x[kt2][r] = v;
+            mx = fmaxf(mx, v);
+        }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m_run, mx);   // finite: key jb of this block is valid
+    const float alpha = exp2f(m_run - mn);
+    m_run = mn;
+    float ls = 0.f;
+#pragma unroll
+    for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            x[kt2][r] = exp2f(x[kt2][r] - mn);
+            ls += x[kt2][r];
+        }
+    l_run = l_run * alpha + ls;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[dt][r] *= alpha;
+    const u32x4_t pfrag = u32x4_t{pack2bf(x[0][0], x[0][1]), pack2bf(x[0][2], x[0][3]), pack2bf(x[1][0], x[1][1]),
+                                  pack2bf(x[1][2], x[1][3])};
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]), "+v"(va[2][0]), "+v"(va[2][1]),
+                   "+v"(va[3][0]), "+v"(va[3][1]), "+v"(va[4][0]), "+v"(va[4][1]), "+v"(va[5][0]), "+v"(va[5][1]),
+                   "+v"(va[6][0]), "+v"(va[6][1]), "+v"(va[7][0]), "+v"(va[7][1])::"memory");
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        const u32x4_t a = u32x4_t{va[dt][0].x, va[dt][0].y, va[dt][1].x, va[dt][1].y};
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                        __builtin_bit_cast(bf16x8_t, pfrag), o[dt], 0, 0, 0);
+    }
+}
+
 template <int G>
-__global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
+__global__ __launch_bounds__(256, 2) void attn_decode_mfma_kernel(
     const bf16_t *__restrict__ qkv, float *__restrict__ part, int n_seqs, int nq, int nkv,
     const int32_t *__restrict__ lens, const uint4 *__restrict__ kc, const uint4 *__restrict__ vc, int cap,
     int nchunks)
 {
-    __shared__ float pt[4][32][8];   // per wavefront: probabilities [key in block][head]
-    __shared__ float al[4][8];       // per wavefront: rescale factor per head
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    extern __shared__ uint4 lds[];   // 4 wavefronts x 2 stages x 8 KiB
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long unit = (long)blockIdx.x * 4 + wv;
     if (unit >= (long)n_seqs * nkv * nchunks) return;
     const int chunk = (int)(unit % nchunks);
@@ -516,107 +500,63 @@ __global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
         if (c16 < G) v = *(const uint4 *)(qkv + (size_t)b * width + (size_t)(kvh * G + c16) * 128 + dblk * 32 + g4 * 8);
         qf[dblk] = u32x4_t{v.x, v.y, v.z, v.w};
     }
-    const uint4 *kb = kc + ((size_t)b * nkv + kvh) * cap * 16;   // 16 uint4 per cached row
-    const uint4 *vb = vc + ((size_t)b * nkv + kvh) * cap * 16 + lane;
+    const uint4 *krow = kc + ((size_t)b * nkv + kvh) * cap * 16;   // 16 uint4 per cached row
+    const uint4 *vrow = vc + ((size_t)b * nkv + kvh) * cap * 16;
+    uint4 *stage0 = lds + wv * 1024, *stage1 = stage0 + 512;
 
-    float m_run = -INFINITY, l_run = 0.f;   // of head c16 (score layout)
-    float acc[G][8];                         // value layout: d = c16*8 .. +8, key row g4
+    // transposing-read addresses inside a stage: rows 4*g4 + c16/4 (+16 by immediate), 8 bytes at
+    // column 16*dt + 4*(c16%4) of the swizzled row
+    uint32_t vaddr[8];
+    {
+        const int R = g4 * 4 + (c16 >> 2);
+        const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)stage0 + R * 256 +
+                              ((c16 >> 1) & 1) * 16 + (c16 & 1) * 8;
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[g][c] = 0.f;
-
-    for (int jb = j0; jb < j1; jb += 32) {
-        uint4 kf[2][4], vv[8];
-#pragma unroll
-        for (int kt2 = 0; kt2 < 2; ++kt2) {
-            const int key = min(jb + kt2 * 16 + c16, j1 - 1);   // rows past the end are masked below
-#pragma unroll
-            for (int dblk = 0; dblk < 4; ++dblk) kf[kt2][dblk] = ld_stream(kb + (size_t)key * 16 + dblk * 4 + g4);
-        }
-#pragma unroll
-        for (int it = 0; it < 8; ++it)
-            vv[it] = (jb + it * 4 + g4 < j1) ? ld_stream(vb + (size_t)(jb + it * 4) * 16) : make_uint4(0, 0, 0, 0);
-
-        float x[2][4];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kt2 = 0; kt2 < 2; ++kt2) {
-            f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int dblk = 0; dblk < 4; ++dblk)
-                st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[kt2][dblk]),
-                                                             __builtin_bit_cast(bf16x8_t, qf[dblk]), st, 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float v = (jb + kt2 * 16 + g4 * 4 + r < j1) ? st[r] * sc : -INFINITY;
-                x[kt2][r] = v;
-                mx = fmaxf(mx, v);
-            }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mn = fmaxf(m_run, mx);   // finite: key jb of this block is valid
-        const float alpha = exp2f(m_run - mn);
-        m_run = mn;
-        float ls = 0.f;
-#pragma unroll
-        for (int kt2 = 0; kt2 < 2; ++kt2)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float pv = exp2f(x[kt2][r] - mn);
-                ls += pv;
-                if (c16 < 8) pt[wv][kt2 * 16 + g4 * 4 + r][c16] = pv;
-            }
-        l_run = l_run * alpha + ls;
-        if (g4 == 0 && c16 < 8) al[wv][c16] = alpha;
-        __builtin_amdgcn_wave_barrier();   // same wavefront: LDS operations execute in program order
-
-        float a_g[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) a_g[g] = al[wv][g];
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) acc[g][c] *= a_g[g];
-#pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const float v0 = bf_lo(vv[it].x), v1 = bf_hi(vv[it].x), v2 = bf_lo(vv[it].y), v3 = bf_hi(vv[it].y);
-            const float v4 = bf_lo(vv[it].z), v5 = bf_hi(vv[it].z), v6 = bf_lo(vv[it].w), v7 = bf_hi(vv[it].w);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float pv = pt[wv][it * 4 + g4][g];
-                acc[g][0] = fmaf(pv, v0, acc[g][0]); acc[g][1] = fmaf(pv, v1, acc[g][1]);
-                acc[g][2] = fmaf(pv, v2, acc[g][2]); acc[g][3] = fmaf(pv, v3, acc[g][3]);
-                acc[g][4] = fmaf(pv, v4, acc[g][4]); acc[g][5] = fmaf(pv, v5, acc[g][5]);
-                acc[g][6] = fmaf(pv, v6, acc[g][6]); acc[g][7] = fmaf(pv, v7, acc[g][7]);
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
+        for (int dt = 0; dt < 8; ++dt) vaddr[dt] = base + ((dt ^ (R & 7)) << 5);
     }
-    // the four key groups of a head hold partial sums of its probabilities; the four key rows of
-    // the value layout hold partial value sums: merge both with the fixed butterfly
+
+    float m_run = -INFINITY, l_run = 0.f;   // of head c16
+    f32x4_t o[8];                            // O^T: head c16, d = dt*16 + g4*4 + r
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    u32x4_t ka[2][4], kb2[2][4];
+    dm_load_k(krow, j0, j1, c16, g4, ka);
+    dm_issue_v(vrow, j0, j1, lane, stage0);
+    dm_wait_all(ka);
+    for (int jb = j0;; jb += 64) {
+        const bool more1 = jb + 32 < j1;
+        if (more1) {
+            dm_load_k(krow, jb + 32, j1, c16, g4, kb2);
+            dm_issue_v(vrow, jb + 32, j1, lane, stage1);
+        }
+        dm_block<0>(ka, qf, vaddr, jb, j1, g4, sc, m_run, l_run, o);
+        if (!more1) break;
+        dm_wait_all(kb2);
+        const bool more2 = jb + 64 < j1;
+        if (more2) {
+            dm_load_k(krow, jb + 64, j1, c16, g4, ka);
+            dm_issue_v(vrow, jb + 64, j1, lane, stage0);
+        }
+        dm_block<1>(kb2, qf, vaddr, jb + 32, j1, g4, sc, m_run, l_run, o);
+        if (!more2) break;
+        dm_wait_all(ka);
+    }
+
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
-    if (g4 == 0 && c16 < G) {
+    if (c16 < G) {
         float *p = part + (((size_t)b * nq + kvh * G + c16) * nchunks + chunk) * kDecPart;
-        p[0] = m_run;
-        p[1] = l_run;
-    }
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            acc[g][c] += __shfl_xor(acc[g][c], 16, 64);
-            acc[g][c] += __shfl_xor(acc[g][c], 32, 64);
-        }
         if (g4 == 0) {
-            float *p = part + (((size_t)b * nq + kvh * G + g) * nchunks + chunk) * kDecPart;
-            *(float4 *)(p + 4 + c16 * 8) = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
-            *(float4 *)(p + 8 + c16 * 8) = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
+            p[0] = m_run;
+            p[1] = l_run;
         }
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+            *(float4 *)(p + 4 + dt * 16 + g4 * 4) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
     }
 }
+#undef DM_TR
 
 // Merge the chunk partials of one (sequence, head) in chunk order; thread c owns value c.
 __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restrict__ part,
@@ -645,20 +585,26 @@ hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs,
     const int nchunks = dec_chunks(cap), G = nq / nkv;
     const long units = (long)n_seqs * nkv * nchunks;
     dim3 grid((unsigned)((units + 3) / 4)), block(256);
-#define CCS_DEC(GV, ITV)                                                                                   \
-    hipLaunchKernelGGL((attn_decode_kernel<GV, ITV>), grid, block, 0, st, (const bf16_t *)qkv, partials,   \
-                       n_seqs, nq, nkv, lens_dev, (const uint4 *)k_cache, (const uint4 *)v_cache, cap, nchunks)
 #define CCS_GQA(GV)                                                                                        \
-    hipLaunchKernelGGL((attn_decode_gqa_kernel<GV>), grid, block, 0, st, (const bf16_t *)qkv, partials, n_seqs, \
-                       nq, nkv, lens_dev, (const uint4 *)k_cache, (const uint4 *)v_cache, cap, nchunks)
+    do {                                                                                                   \
+        static bool attr_done = false;                                                                     \
+        if (!attr_done) {                                                                                  \
+            hipError_t e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<GV>,                  \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 65536);         \
+            if (e != hipSuccess) return e;                                                                 \
+            attr_done = true;                                                                              \
+        }                                                                                                  \
+        hipLaunchKernelGGL((attn_decode_mfma_kernel<GV>), grid, block, 65536, st, (const bf16_t *)qkv,     \
+                           partials, n_seqs, nq, nkv, lens_dev, (const uint4 *)k_cache,                    \
+                           (const uint4 *)v_cache, cap, nchunks);                                          \
+    } while (0)
     switch (G) {
-        case 1: CCS_DEC(1, 16); break;
+        case 1: CCS_GQA(1); break;
         case 2: CCS_GQA(2); break;
         case 4: CCS_GQA(4); break;
         case 8: CCS_GQA(8); break;
         default: return hipErrorInvalidValue;
     }
-#undef CCS_DEC
 #undef CCS_GQA
     return hipGetLastError();
 }

@@ -55,6 +55,22 @@ __host__ __device__ __forceinline__ size_t packed_index(int r, int k, int kfrags
     return ((((size_t)(r >> 4) * kfrags + (k >> 5)) * 64) + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
 }
 
+// Weights use the same fragments in a grouped order: the 16-row blocks are taken in groups of
+// kWGroup (128 rows; the block count is padded to a multiple, padding fragments are zero) and
+// fragment (nb, kb) sits at ((nb / kWGroup) * K/32 + kb) * kWGroup + nb % kWGroup.  The fragments
+// of one group for one k-step are then one contiguous 8 KiB piece and consecutive k-steps follow
+// each other, which is what a weight-streaming wavefront reads.
+constexpr int kWGroup = 8;
+__host__ __device__ __forceinline__ size_t weight_fragment(int nb, int kb, int kfrags)
+{
+    return ((size_t)(nb / kWGroup) * kfrags + kb) * kWGroup + (nb % kWGroup);
+}
+__host__ __device__ __forceinline__ size_t packed_weight_bytes(int N, int K)
+{
+    const size_t nblk = ((size_t)(N + 15) / 16 + kWGroup - 1) / kWGroup * kWGroup;
+    return nblk * 16 * (size_t)K * 2;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

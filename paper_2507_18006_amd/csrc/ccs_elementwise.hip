@@ -46,12 +46,12 @@ hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st
 }
 
 // ---------------------------------------------------------------------------------------------
-// Weight packing (module_create): row-major [N, K] bf16 -> fragment-packed.  One thread per
-// 16-byte chunk (8 consecutive k of one row).
+// Packing: row-major [N, K] bf16 -> fragment-packed (activations) or grouped fragment-packed
+// (weights, module_create).  One thread per 16-byte chunk (8 consecutive k of one row).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4 *__restrict__ src,
                                                         uint4 *__restrict__ dst, int N, int K,
-                                                        int blk_stride, int blk_offset)
+                                                        int blk_stride, int blk_offset, int grouped)
 {
     const int kchunks = K >> 3;
     const size_t total = (size_t)N * kchunks;
@@ -59,19 +59,19 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4 *__restrict_
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         int n = (int)(i / kchunks), kc = (int)(i % kchunks);
         int nb = (n >> 4) * blk_stride + blk_offset;
-        size_t o = (((size_t)nb * kfrags + (kc >> 2)) * 64) + (n & 15) + 16 * (kc & 3);
-        dst[o] = src[i];
+        const size_t frag = grouped ? weight_fragment(nb, kc >> 2, kfrags) : (size_t)nb * kfrags + (kc >> 2);
+        dst[frag * 64 + (n & 15) + 16 * (kc & 3)] = src[i];
     }
 }
 
 hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int blk_stride,
-                            int blk_offset, hipStream_t st)
+                            int blk_offset, bool grouped, hipStream_t st)
 {
     size_t total = (size_t)N * (K / 8);
     if (!total) return hipSuccess;
     int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
     hipLaunchKernelGGL(pack_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src,
-                       (uint4 *)dst_packed, N, K, blk_stride, blk_offset);
+                       (uint4 *)dst_packed, N, K, blk_stride, blk_offset, grouped ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -60,24 +60,26 @@ hipError_t launch_gemm_f32(const float *x, const float *W, const float *res, flo
 // =============================================================================================
 // Weight-streaming GEMM (decode-sized row counts)
 // =============================================================================================
-constexpr int kSkNB = 4;     // 16-row weight blocks per wavefront (64 output columns)
-constexpr int kSkU = 4;      // k-fragments in flight per wavefront
-// Launch shape from the weight shape alone (measured sweeps at 32 and 64 rows): ~512 workgroups
-// through K segments (at most 8) - more spill into a second round at 64 rows, where only two
-// wavefronts fit a SIMD; weights with few column tiles (N = 4096: O and
-// down projections) get 8 wavefronts per workgroup - each a contiguous part of the segment - the
-// others 4.
+constexpr int kSkNB = kWGroup;   // 16-row weight blocks per wavefront: one block group (128 output columns)
+constexpr int kSkU = 2;          // most k-steps (8 KiB of weights each) per register set of a wavefront
+// The grouped weight layout makes the 8 fragments a wavefront needs for one k-step one
+// contiguous 8 KiB piece, and consecutive k-steps consecutive pieces (measured on a 940 MB
+// weight, loads only: 6.8 TB/s against 5.9 TB/s for 8 separate 1 KiB streams and 7.0 TB/s for a
+// flat read).  128 output columns per wavefront also halve the activation fragments (L2 hits)
+// fetched per weight byte against 64 columns; at 64 rows those cost 20 % of the rate before.
+// Launch shape from the weight shape alone.  Measured sweeps (32 and 64 rows, 33 MB to 940 MB
+// weights): four wavefronts per workgroup, each a contiguous quarter of the K segment, and about
+// one workgroup per CU - long streams per wavefront beat more, shorter ones (every wavefront
+// pays a pipeline fill and an epilogue) - so K is cut into floor(256 / tiles) segments.
+constexpr int kSkWaves = 4;
 
 static inline int sk_tiles(int N) { return (N / 16 + kSkNB - 1) / kSkNB; }
-
-static inline int sk_waves(int N) { return sk_tiles(N) < 96 ? 8 : 4; }
 
 int skinny_segments(int N, int K)
 {
     const int kfrags = K / 32, tiles = sk_tiles(N);
-    int S = (512 + tiles - 1) / tiles;  // ~2 workgroups per CU: one round at every row count
-    if (S > 8) S = 8;
-    int max_s = kfrags / (sk_waves(N) * 2);  // at least 2 fragments per wavefront
+    int S = 256 / tiles;
+    int max_s = kfrags / (kSkWaves * kSkU * 2);  // at least two full register sets per wavefront
     if (S > max_s) S = max_s;
     if (S < 1) S = 1;
     const int per = (kfrags + S - 1) / S;
@@ -89,27 +91,56 @@ size_t skinny_partial_bytes(int M, int N, int K)
     return (size_t)skinny_segments(N, K) * (size_t)M * (size_t)N * sizeof(float);
 }
 
-template <int MB, int kSkWaves>
-__global__ __launch_bounds__(kSkWaves * 64) void gemm_skinny_kernel(
+// hand-issued 16-byte loads (OFF: immediate byte offset, at most 4095) and the wait that makes
+// a register set usable: nothing may read the registers between the two
+template <int OFF>
+__device__ __forceinline__ void sk_ld_nt(u32x4_t &dst, const uint4 *p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off offset:%2 nt" : "=v"(dst) : "v"(p), "i"(OFF) : "memory");
+}
+__device__ __forceinline__ void sk_ld(u32x4_t &dst, const uint4 *p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+// all loads but the CNT issued last have landed (loads return in order)
+template <int CNT>
+__device__ __forceinline__ void sk_wait_older(u32x4_t (&r)[CNT])
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CNT) : "memory");
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) asm volatile("" : "+v"(r[i]));
+}
+template <int CNT>
+__device__ __forceinline__ void sk_wait_all(u32x4_t (&r)[CNT])
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) asm volatile("" : "+v"(r[i]));
+}
+__device__ __forceinline__ f32x4_t mfma16x(const u32x4_t &a, const u32x4_t &b, f32x4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+// (3 or 4 row blocks: 128 accumulator registers plus two 2-step register sets need more than 256
+// registers, so one workgroup per CU; measured faster than 1-step sets at two workgroups per CU)
+template <int MB>
+__global__ __launch_bounds__(kSkWaves * 64, MB <= 2 ? 2 : 1) void gemm_skinny_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, float *__restrict__ part, int nblk,
     int kfrags, int ntiles, int kf_seg, int M, int N)
 {
-    __shared__ float red[kSkWaves - 1][kSkNB * MB * 4][64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    extern __shared__ float red[];   // two buffers of MB*16 padded rows
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int tile = blockIdx.x % ntiles, seg = blockIdx.x / ntiles;
-    const int nb0 = tile * kSkNB;
     const int seg_lo = seg * kf_seg;
     const int seg_hi = min(kfrags, seg_lo + kf_seg);
     const int per_wave = (seg_hi - seg_lo + kSkWaves - 1) / kSkWaves;
     const int kb_lo = min(seg_hi, seg_lo + wave * per_wave);
     const int kb_hi = min(seg_hi, kb_lo + per_wave);
 
-    const uint4 *wp[kSkNB];
-#pragma unroll
-    for (int j = 0; j < kSkNB; ++j) {
-        int nb = min(nb0 + j, nblk - 1);  // clamped blocks are computed and dropped
-        wp[j] = Wp + (size_t)nb * kfrags * 64 + lane;
-    }
+    // fragment (j, kb) of this tile's block group: wp + (kb * kSkNB + j) * 64
+    const uint4 *wp = Wp + (size_t)tile * kfrags * (kSkNB * 64) + lane;
     const uint4 *xp[MB];
 #pragma unroll
     for (int i = 0; i < MB; ++i) xp[i] = Xp + (size_t)i * kfrags * 64 + lane;
@@ -120,66 +151,75 @@ __global__ __launch_bounds__(kSkWaves * 64) void gemm_skinny_kernel(
 #pragma unroll
         for (int i = 0; i < MB; ++i) acc[j][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    int kb = kb_lo;
-    for (; kb + kSkU <= kb_hi; kb += kSkU) {
-        uint4 w[kSkU][kSkNB], xv[kSkU][MB];
-#pragma unroll
-        for (int u = 0; u < kSkU; ++u) {
-#pragma unroll
-            for (int j = 0; j < kSkNB; ++j) w[u][j] = ld_stream(wp[j] + (size_t)(kb + u) * 64);
-#pragma unroll
-            for (int i = 0; i < MB; ++i) xv[u][i] = xp[i][(size_t)(kb + u) * 64];
+    // Two register sets of U k-steps each, rolling: while one set is multiplied the other is in
+    // flight, and a set is reloaded as soon as its MFMAs have issued (a wavefront that only loads,
+    // waits and multiplies leaves the memory system idle during its MFMA phase).  The loop body
+    // has no branch around a load - past the end a set re-loads the last k-step (a cache hit) and
+    // is not multiplied - so that the compiler's wait counts stay exact.
+    constexpr int U = kSkU;
+    uint4 w0[U][kSkNB], x0[U][MB], w1[U][kSkNB], x1[U][MB];
+    const int n_sets = (kb_hi - kb_lo + U - 1) / U;
+#define SK_LOAD(W_, X_, SET)                                                                              \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
+        const int kk = min(kb_lo + (SET) * U + u, kb_hi - 1);                                             \
+        _Pragma("unroll") for (int j = 0; j < kSkNB; ++j) W_[u][j] = ld_stream(wp + ((size_t)kk * kSkNB + j) * 64); \
+        _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * 64];                 \
+    }
+#define SK_MUL(W_, X_, SET)                                                                               \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
+        if (kb_lo + (SET) * U + u < kb_hi) {                                                              \
+            _Pragma("unroll") for (int j = 0; j < kSkNB; ++j)                                              \
+                _Pragma("unroll") for (int i = 0; i < MB; ++i) acc[j][i] = mfma16(W_[u][j], X_[u][i], acc[j][i]); \
+        }                                                                                                 \
+    }
+    if (n_sets > 0) {
+        SK_LOAD(w0, x0, 0);
+        SK_LOAD(w1, x1, 1);
+        for (int i = 0; i < n_sets; i += 2) {
+            SK_MUL(w0, x0, i);
+            SK_LOAD(w0, x0, i + 2);
+            SK_MUL(w1, x1, i + 1);
+            SK_LOAD(w1, x1, i + 3);
         }
-#pragma unroll
-        for (int u = 0; u < kSkU; ++u)
-#pragma unroll
-            for (int j = 0; j < kSkNB; ++j)
-#pragma unroll
-                for (int i = 0; i < MB; ++i) acc[j][i] = mfma16(w[u][j], xv[u][i], acc[j][i]);
     }
-    for (; kb < kb_hi; ++kb) {
-        uint4 w[kSkNB], xv[MB];
-#pragma unroll
-        for (int j = 0; j < kSkNB; ++j) w[j] = ld_stream(wp[j] + (size_t)kb * 64);
-#pragma unroll
-        for (int i = 0; i < MB; ++i) xv[i] = xp[i][(size_t)kb * 64];
-#pragma unroll
-        for (int j = 0; j < kSkNB; ++j)
-#pragma unroll
-            for (int i = 0; i < MB; ++i) acc[j][i] = mfma16(w[j], xv[i], acc[j][i]);
-    }
+#undef SK_LOAD
+#undef SK_MUL
 
-    // in-workgroup reduction, fixed order wave 0 + wave 1 + ... + wave kSkWaves-1
-    if (wave > 0) {
+    // In-workgroup reduction and store through two LDS buffers of row-major [row][128 columns]
+    // outputs (rows padded to 528 bytes: conflict-free 16-byte accesses): wavefronts 2, 3 write
+    // their accumulators, wavefronts 0, 1 add them to their own (0 + 2, 1 + 3) and write the
+    // sums; then every thread adds the two buffers for its outputs and stores them - a wavefront
+    // writes whole 512-byte row segments.  The order (0 + 2) + (1 + 3) is fixed.
+    constexpr int ROWF = kSkNB * 16 + 4;   // floats per padded row
+    constexpr int BUF = MB * 16 * ROWF;    // floats per buffer
+    float *slot = red + (wave & 1) * BUF + (lane & 15) * ROWF + (lane >> 4) * 4;   // + i * 16 * ROWF + j * 16
+    if (wave >= 2) {
 #pragma unroll
         for (int j = 0; j < kSkNB; ++j)
 #pragma unroll
             for (int i = 0; i < MB; ++i)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) red[wave - 1][(j * MB + i) * 4 + r][lane] = acc[j][i][r];
+                *(float4 *)(slot + i * 16 * ROWF + j * 16) = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
     }
     __syncthreads();
-    if (wave == 0) {
+    if (wave < 2) {
 #pragma unroll
-        for (int j = 0; j < kSkNB; ++j) {
-            const int nb = nb0 + j;
+        for (int j = 0; j < kSkNB; ++j)
 #pragma unroll
             for (int i = 0; i < MB; ++i) {
-                float v[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float s = acc[j][i][r];
-#pragma unroll
-                    for (int w = 0; w < kSkWaves - 1; ++w) s += red[w][(j * MB + i) * 4 + r][lane];
-                    v[r] = s;
-                }
-                const int m = i * 16 + (lane & 15);
-                if (nb < nblk && m < M) {
-                    float4 *dst = (float4 *)(part + ((size_t)seg * M + m) * N + nb * 16 + (lane >> 4) * 4);
-                    *dst = make_float4(v[0], v[1], v[2], v[3]);
-                }
+                float4 *p = (float4 *)(slot + i * 16 * ROWF + j * 16);
+                const float4 t = *p;
+                *p = make_float4(acc[j][i][0] + t.x, acc[j][i][1] + t.y, acc[j][i][2] + t.z, acc[j][i][3] + t.w);
             }
-        }
+    }
+    __syncthreads();
+    constexpr int QUADS = MB * 16 * (kSkNB * 4);   // float4 outputs of the tile
+    for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
+        const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
+        float4 v = *(const float4 *)(red + m * ROWF + c);
+        const float4 t = *(const float4 *)(red + BUF + m * ROWF + c);
+        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+        const int n = tile * (kSkNB * 16) + c;
+        if (m < M && n < N) *(float4 *)(part + ((size_t)seg * M + m) * N + n) = v;
     }
 }
 
@@ -223,6 +263,23 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restr
     }
 }
 
+template <int MB>
+static hipError_t sk_launch(dim3 grid, hipStream_t st, const uint4 *Wp, const uint4 *Xp, float *partials, int nblk,
+                            int kfrags, int ntiles, int kf_seg, int M, int N)
+{
+    constexpr int kLds = 2 * MB * 16 * (kSkNB * 16 + 4) * (int)sizeof(float);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_skinny_kernel<MB>), grid, dim3(kSkWaves * 64), kLds, st, Wp, Xp, partials, nblk, kfrags,
+                       ntiles, kf_seg, M, N);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
                                    int K, hipStream_t st)
 {
@@ -231,18 +288,10 @@ hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partia
     const int kfrags = K / 32, nblk = N / 16, ntiles = sk_tiles(N);
     const int S = skinny_segments(N, K);
     const int kf_seg = (kfrags + S - 1) / S;
-    const int waves = sk_waves(N);
-    dim3 grid(ntiles * S), block(waves * 64);
+    dim3 grid(ntiles * S);
     const int mb = (M + 15) / 16;
-#define CCS_SK(MBV)                                                                                        \
-    do {                                                                                                   \
-        if (waves == 8)                                                                                    \
-            hipLaunchKernelGGL((gemm_skinny_kernel<MBV, 8>), grid, block, 0, st, (const uint4 *)Wp,        \
-                               (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N);           \
-        else                                                                                               \
-            hipLaunchKernelGGL((gemm_skinny_kernel<MBV, 4>), grid, block, 0, st, (const uint4 *)Wp,        \
-                               (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N);           \
-    } while (0)
+#define CCS_SK(MBV) e = sk_launch<MBV>(grid, st, (const uint4 *)Wp, (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N)
+    hipError_t e = hipSuccess;
     switch (mb) {
         case 1: CCS_SK(1); break;
         case 2: CCS_SK(2); break;
@@ -250,7 +299,7 @@ hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partia
         default: CCS_SK(4); break;
     }
 #undef CCS_SK
-    return hipGetLastError();
+    return e;
 }
 
 hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,
@@ -324,10 +373,11 @@ __device__ __forceinline__ void dma_one(const uint4 *src, uint4 *lds_dst)
 }
 
 template <int FPW>
-__device__ __forceinline__ void dma_issue(const uint4 *const *src, size_t koff, uint4 *lds_dst)
+__device__ __forceinline__ void dma_issue(const uint4 *const *src, const int *kstep, int kt, uint4 *lds_dst)
 {
 #pragma unroll
-    for (int i = 0; i < FPW; ++i) __builtin_amdgcn_global_load_lds(src[i] + koff, lds_dst + i * 64, 16, 0, 0);
+    for (int i = 0; i < FPW; ++i)
+        __builtin_amdgcn_global_load_lds(src[i] + (size_t)kt * kstep[i], lds_dst + i * 64, 16, 0, 0);
 }
 
 template <int BM, int NST>
@@ -350,19 +400,21 @@ __global__ __launch_bounds__(256, (BM == 128 && NST <= 3) ? 2 : 1) void gemm_til
     const int kt0 = seg * kt_per_seg;
     const int ktiles = min(kfrags, kt0 + kt_per_seg) - kt0;
 
-    // fragment f of a stage: f < TN -> weight block nb0 + f, else activation block mb0 + f - TN
+    // fragment f of a stage: f < TN -> weight block nb0 + f (grouped weight order: the next k-tile
+    // of a block is kWGroup fragments further), else activation block mb0 + f - TN (plain order)
     const uint4 *src[C::FPW];
+    int kstep[C::FPW];  // uint4 from one k-tile to the next
 #pragma unroll
     for (int i = 0; i < C::FPW; ++i) {
         const int f = wave * C::FPW + i;
         const bool is_x = f >= C::TN;
         const int blk = is_x ? min(mb0 + f - C::TN, mblk - 1) : min(nb0 + f, nblk - 1);
-        src[i] = (is_x ? Xp : Wp) + ((size_t)blk * kfrags + kt0) * 64 + lane;
+        src[i] = is_x ? Xp + ((size_t)blk * kfrags + kt0) * 64 + lane : Wp + weight_fragment(blk, kt0, kfrags) * 64 + lane;
+        kstep[i] = is_x ? 64 : kWGroup * 64;
     }
-    constexpr int KSTEP = 64;  // uint4 per k-tile along one block row
     // (a __device__ helper, not a lambda: the host pass cannot instantiate a lambda that holds the
     // direct-to-LDS builtin and then silently drops the kernel's launch stub)
-#define dma(kt, stage) dma_issue<C::FPW>(src, (size_t)(kt) * KSTEP, lds + (stage) * C::STAGE + wave * C::FPW * 64)
+#define dma(kt, stage) dma_issue<C::FPW>(src, kstep, kt, lds + (stage) * C::STAGE + wave * C::FPW * 64)
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)lds;
     const int sub = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);
@@ -413,7 +465,7 @@ __global__ __launch_bounds__(256, (BM == 128 && NST <= 3) ? 2 : 1) void gemm_til
                 else if (q - 4 < C::FM) CCS_LDS_READ(nb[q & 3], (bbase) + (q & 3) * 2048u, OFF);               \
             }                                                                                                  \
             if ((do_dma) && q < C::FPW)                                                          \
-                dma_one(src[q < C::FPW ? q : 0] + (size_t)(kt_dma) * KSTEP,                                    \
+                dma_one(src[q < C::FPW ? q : 0] + (size_t)(kt_dma) * kstep[q < C::FPW ? q : 0],                \
                         lds + (st_dma) * C::STAGE + (wave * C::FPW + q) * 64);                                 \
             __builtin_amdgcn_sched_barrier(0);                                                                 \
         }                                                                                                      \

@@ -14,8 +14,9 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st);
 // Row-major bf16 [N, K] -> fragment-packed rows; 16-row block nb of the source lands at packed
 // block nb * blk_stride + blk_offset of a packed matrix with K/32 fragments per block row.
+// `grouped`: weight order (groups of 8 blocks, see ccs_common.h); the caller zeroes the padding.
 hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int blk_stride,
-                            int blk_offset, hipStream_t st);
+                            int blk_offset, bool grouped, hipStream_t st);
 // out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g.  x row-major [rows, H].
 // bf16: out is fragment-packed [rows16, H]; f32: out row-major.
 hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H,

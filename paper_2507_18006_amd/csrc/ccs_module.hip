@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "../../include/cocoserve_mi.h"
+#include "ccs_common.h"
 #include "ccs_kernels.h"
 
 namespace {
@@ -86,13 +87,15 @@ ArenaPlan arena_plan(const ccs_module_desc *D, const Dims &d)
     ArenaPlan p{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    // bf16 weights are fragment-packed in groups of 8 row blocks (padded to a whole group)
+    auto wbytes = [&](int N, int K) { return D->dtype == CCS_BF16 ? ccs::packed_weight_bytes(N, K) : (size_t)N * K * 4; };
     if (D->kind == CCS_LINEAR) {
-        p.w = take((size_t)d.out_f * d.in_f * d.esz);
+        p.w = take(wbytes(d.out_f, d.in_f));
     } else {
-        p.qkv = take((size_t)d.W3 * d.H * d.esz);
-        p.o = take((size_t)d.H * d.QD * d.esz);
-        p.gu = take((size_t)2 * d.I * d.H * d.esz);
-        p.dn = take((size_t)d.H * d.I * d.esz);
+        p.qkv = take(wbytes(d.W3, d.H));
+        p.o = take(wbytes(d.H, d.QD));
+        p.gu = take(wbytes(2 * d.I, d.H));
+        p.dn = take(wbytes(d.H, d.I));
         p.g1 = take((size_t)d.H * d.esz);
         p.g2 = take((size_t)d.H * d.esz);
         p.rope = take((size_t)(d.d / 2) * 2 * sizeof(float));  // inverse-frequency table (fp32 head + tail)
@@ -305,7 +308,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         }
         WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false, 0, (long)variant_rows);
         if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
-        CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, st));
+        CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, st));
         if (skinny) {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, st));
             CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_gemm_skinny_reduce((const float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
@@ -459,12 +462,22 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
     hipError_t e = hipSuccess;
     auto rm_copy = [&](size_t off, const void *src, size_t bytes) { if (e == hipSuccess) e = launch_clone(A + off, src, bytes, st); };
     auto pack = [&](size_t off, const void *src, int N, int K, int stride, int blk_off) {
-        if (e == hipSuccess) e = launch_pack_bf16(src, A + off, N, K, stride, blk_off, st);
+        if (e == hipSuccess) e = launch_pack_bf16(src, A + off, N, K, stride, blk_off, true, st);
+    };
+    // padding fragments of a weight whose block count is not a multiple of the group must be zero
+    auto zero_if_padded = [&](size_t off, int N, int K) {
+        if (e == hipSuccess && bf && ccs::packed_weight_bytes(N, K) != (size_t)N * K * 2)
+            e = hipMemsetAsync(A + off, 0, ccs::packed_weight_bytes(N, K), st);
     };
     if (desc->kind == CCS_LINEAR) {
+        zero_if_padded(m->ap.w, d.out_f, d.in_f);
         if (bf) pack(m->ap.w, w->w, d.out_f, d.in_f, 1, 0);
         else rm_copy(m->ap.w, w->w, (size_t)d.out_f * d.in_f * 4);
     } else if (bf) {
+        zero_if_padded(m->ap.qkv, d.W3, d.H);
+        zero_if_padded(m->ap.o, d.H, d.QD);
+        zero_if_padded(m->ap.gu, 2 * d.I, d.H);
+        zero_if_padded(m->ap.dn, d.H, d.I);
         pack(m->ap.qkv, w->wq, d.QD, d.H, 1, 0);
         pack(m->ap.qkv, w->wk, d.KD, d.H, 1, d.QD / 16);
         pack(m->ap.qkv, w->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16);

@@ -393,27 +393,36 @@ hipError_t launch_qkv_reduce_rope_decode(const float *partials, int S, int M, in
 // Decode, bf16: epilogue of the weight-streaming O projection fused with the second RMSNorm.
 // One workgroup per row: x1 = bf16(sum of partials in segment order + x), stored row-major;
 // h2 = RMSNorm(x1; g2) stored fragment-packed.  The sum of squares is reduced in a fixed order
-// (thread partials, wavefront butterfly, wavefronts 0..3), so a row's bits do not depend on the
-// batch.  H <= 8192.
+// (thread partials, wavefront butterfly, wavefronts 0..15), so a row's bits do not depend on the
+// batch.  H <= 8192.  1024 threads per row: one or two 16-byte columns each, segment loads batched.
 // ---------------------------------------------------------------------------------------------
 constexpr int kRowNormMaxH = 8192;
 
-__global__ __launch_bounds__(256) void reduce_residual_rmsnorm_kernel(
+__global__ __launch_bounds__(1024) void reduce_residual_rmsnorm_kernel(
     const float *__restrict__ part, int S, int M, int H, const bf16_t *__restrict__ res,
     const bf16_t *__restrict__ g, float eps, bf16_t *__restrict__ x1, bf16_t *__restrict__ h2)
 {
-    __shared__ float wsum[4];
+    __shared__ float wsum[16];
     const int m = blockIdx.x, tid = threadIdx.x;
     const size_t seg = (size_t)M * H;
-    float v[kRowNormMaxH / 1024][4];
+    float v[kRowNormMaxH / 4096][4];
     float ss = 0.f;
 #pragma unroll
-    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
-        const int c = (tid + 256 * j) * 4;
+    for (int j = 0; j < kRowNormMaxH / 4096; ++j) {
+        const int c = (tid + 1024 * j) * 4;
         if (c < H) {
             const float *p = part + (size_t)m * H + c;
             float4 s = *(const float4 *)p;
-            for (int k = 1; k < S; ++k) {
+            int k = 1;
+            for (; k + 3 < S; k += 4) {   // four loads in flight, added in segment order
+                const float4 t0 = *(const float4 *)(p + k * seg), t1 = *(const float4 *)(p + (k + 1) * seg);
+                const float4 t2 = *(const float4 *)(p + (k + 2) * seg), t3 = *(const float4 *)(p + (k + 3) * seg);
+                s.x += t0.x; s.y += t0.y; s.z += t0.z; s.w += t0.w;
+                s.x += t1.x; s.y += t1.y; s.z += t1.z; s.w += t1.w;
+                s.x += t2.x; s.y += t2.y; s.z += t2.z; s.w += t2.w;
+                s.x += t3.x; s.y += t3.y; s.z += t3.z; s.w += t3.w;
+            }
+            for (; k < S; ++k) {
                 const float4 t = *(const float4 *)(p + k * seg);
                 s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
             }
@@ -428,11 +437,13 @@ __global__ __launch_bounds__(256) void reduce_residual_rmsnorm_kernel(
     ss = wave_sum(ss);
     if ((tid & 63) == 0) wsum[tid >> 6] = ss;
     __syncthreads();
-    const float tot = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+    float tot = wsum[0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) tot += wsum[w];
     const float r = 1.0f / sqrtf(tot / (float)H + eps);
 #pragma unroll
-    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
-        const int c = (tid + 256 * j) * 4;
+    for (int j = 0; j < kRowNormMaxH / 4096; ++j) {
+        const int c = (tid + 1024 * j) * 4;
         if (c < H) {
             const uint2 gv = *(const uint2 *)(g + c);
             *(uint2 *)(h2 + packed_index(m, c, H >> 5)) =
@@ -447,7 +458,7 @@ hipError_t launch_reduce_residual_rmsnorm(const float *partials, int S, int M, i
 {
     if (M <= 0) return hipSuccess;
     if (H > kRowNormMaxH || (H & 3)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(reduce_residual_rmsnorm_kernel, dim3(M), dim3(256), 0, st, partials, S, M, H, (const bf16_t *)res,
+    hipLaunchKernelGGL(reduce_residual_rmsnorm_kernel, dim3(M), dim3(1024), 0, st, partials, S, M, H, (const bf16_t *)res,
                        (const bf16_t *)g, eps, (bf16_t *)x1, (bf16_t *)h2);
     return hipGetLastError();
 }

@@ -72,6 +72,7 @@ constexpr int kSkU = 2;          // most k-steps (8 KiB of weights each) per reg
 // one workgroup per CU - long streams per wavefront beat more, shorter ones (every wavefront
 // pays a pipeline fill and an epilogue) - so K is cut into floor(256 / tiles) segments.
 constexpr int kSkWaves = 4;
+enum { SK_PARTIALS = 0, SK_STORE_RM = 1, SK_SWIGLU_PACKED = 2 };   // what the kernel writes
 
 static inline int sk_tiles(int N) { return (N / 16 + kSkNB - 1) / kSkNB; }
 
@@ -124,10 +125,10 @@ __device__ __forceinline__ f32x4_t mfma16x(const u32x4_t &a, const u32x4_t &b, f
 
 // (3 or 4 row blocks: 128 accumulator registers plus two 2-step register sets need more than 256
 // registers, so one workgroup per CU; measured faster than 1-step sets at two workgroups per CU)
-template <int MB>
+template <int MB, int EPI>
 __global__ __launch_bounds__(kSkWaves * 64, MB <= 2 ? 2 : 1) void gemm_skinny_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, float *__restrict__ part, int nblk,
-    int kfrags, int ntiles, int kf_seg, int M, int N)
+    int kfrags, int ntiles, int kf_seg, int M, int N, const bf16_t *__restrict__ res, bf16_t *__restrict__ out)
 {
     extern __shared__ float red[];   // two buffers of MB*16 padded rows
     const int lane = threadIdx.x & 63;
@@ -212,14 +213,42 @@ __global__ __launch_bounds__(kSkWaves * 64, MB <= 2 ? 2 : 1) void gemm_skinny_ke
             }
     }
     __syncthreads();
-    constexpr int QUADS = MB * 16 * (kSkNB * 4);   // float4 outputs of the tile
-    for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
-        const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
+    // value of the tile at (row m, column c of 128)
+    auto fetch = [&](int m, int c) -> float4 {
         float4 v = *(const float4 *)(red + m * ROWF + c);
         const float4 t = *(const float4 *)(red + BUF + m * ROWF + c);
         v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
-        const int n = tile * (kSkNB * 16) + c;
-        if (m < M && n < N) *(float4 *)(part + ((size_t)seg * M + m) * N + n) = v;
+        return v;
+    };
+    constexpr int QUADS = MB * 16 * (kSkNB * 4);   // float4 outputs of the tile
+    if (EPI == SK_PARTIALS) {
+        for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
+            const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
+            const int n = tile * (kSkNB * 16) + c;
+            if (m < M && n < N) *(float4 *)(part + ((size_t)seg * M + m) * N + n) = fetch(m, c);
+        }
+    } else if (EPI == SK_STORE_RM) {   // the launch has one K segment: the tile is final
+        for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
+            const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
+            const int n = tile * (kSkNB * 16) + c;
+            if (m >= M || n >= N) continue;
+            float4 v = fetch(m, c);
+            if (res) {
+                const uint2 r = *(const uint2 *)(res + (size_t)m * N + n);
+                v.x += bf_lo(r.x); v.y += bf_hi(r.x); v.z += bf_lo(r.y); v.w += bf_hi(r.y);
+            }
+            *(uint2 *)(out + (size_t)m * N + n) = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
+        }
+    } else {   // SK_SWIGLU_PACKED, one K segment: the tile's 8 weight blocks are 4 (gate, up) pairs, 64 columns of u
+        for (int q = threadIdx.x; q < QUADS / 2; q += kSkWaves * 64) {
+            const int m = q / (kSkNB * 2), pr = (q % (kSkNB * 2)) / 4, c4 = (q % 4) * 4;
+            const int col = (tile * (kSkNB / 2) + pr) * 16 + c4;   // column of u
+            if (m >= M || col >= N / 2) continue;
+            const float4 g = fetch(m, pr * 32 + c4), u = fetch(m, pr * 32 + 16 + c4);
+            const float o0 = g.x / (1.0f + __expf(-g.x)) * u.x, o1 = g.y / (1.0f + __expf(-g.y)) * u.y;
+            const float o2 = g.z / (1.0f + __expf(-g.z)) * u.z, o3 = g.w / (1.0f + __expf(-g.w)) * u.w;
+            *(uint2 *)(out + packed_index(m, col, (N / 2) >> 5)) = make_uint2(pack2bf(o0, o1), pack2bf(o2, o3));
+        }
     }
 }
 
@@ -263,35 +292,49 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restr
     }
 }
 
-template <int MB>
+template <int MB, int EPI>
 static hipError_t sk_launch(dim3 grid, hipStream_t st, const uint4 *Wp, const uint4 *Xp, float *partials, int nblk,
-                            int kfrags, int ntiles, int kf_seg, int M, int N)
+                            int kfrags, int ntiles, int kf_seg, int M, int N, const bf16_t *res, bf16_t *out)
 {
     constexpr int kLds = 2 * MB * 16 * (kSkNB * 16 + 4) * (int)sizeof(float);
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, EPI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((gemm_skinny_kernel<MB>), grid, dim3(kSkWaves * 64), kLds, st, Wp, Xp, partials, nblk, kfrags,
-                       ntiles, kf_seg, M, N);
+    hipLaunchKernelGGL((gemm_skinny_kernel<MB, EPI>), grid, dim3(kSkWaves * 64), kLds, st, Wp, Xp, partials, nblk,
+                       kfrags, ntiles, kf_seg, M, N, res, out);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
-                                   int K, hipStream_t st)
+// With one K segment the kernel applies the epilogue itself (no partial sums, no second kernel);
+// with several it writes partial sums and the caller runs the reduction (launch_gemm_skinny_reduce
+// or a fused one).  *fused tells which.  (Letting the workgroup that completes a tile's last
+// segment do the reduction needs device-scope fences in every workgroup; measured, they cost
+// 25-35 us per launch, several times the reduction kernel they would save.)
+hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, int M, int N, int K, int epi,
+                              const void *res, void *out, bool *fused, hipStream_t st)
 {
+    if (fused) *fused = false;
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows) return hipErrorInvalidValue;
     const int kfrags = K / 32, nblk = N / 16, ntiles = sk_tiles(N);
     const int S = skinny_segments(N, K);
     const int kf_seg = (kfrags + S - 1) / S;
+    const int kind = (S == 1 && epi == EPI_STORE_RM) ? SK_STORE_RM : (S == 1 && epi == EPI_SWIGLU_PACKED) ? SK_SWIGLU_PACKED : SK_PARTIALS;
+    if (fused) *fused = kind != SK_PARTIALS;
     dim3 grid(ntiles * S);
     const int mb = (M + 15) / 16;
-#define CCS_SK(MBV) e = sk_launch<MBV>(grid, st, (const uint4 *)Wp, (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N)
     hipError_t e = hipSuccess;
+#define CCS_SK2(MBV, EPIV) e = sk_launch<MBV, EPIV>(grid, st, (const uint4 *)Wp, (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N, (const bf16_t *)res, (bf16_t *)out)
+#define CCS_SK(MBV)                                         \
+    switch (kind) {                                         \
+        case SK_STORE_RM: CCS_SK2(MBV, SK_STORE_RM); break; \
+        case SK_SWIGLU_PACKED: CCS_SK2(MBV, SK_SWIGLU_PACKED); break; \
+        default: CCS_SK2(MBV, SK_PARTIALS);                 \
+    }
     switch (mb) {
         case 1: CCS_SK(1); break;
         case 2: CCS_SK(2); break;
@@ -299,7 +342,14 @@ hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partia
         default: CCS_SK(4); break;
     }
 #undef CCS_SK
+#undef CCS_SK2
     return e;
+}
+
+hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
+                                   int K, hipStream_t st)
+{
+    return launch_gemm_skinny(Wp, Xp, partials, M, N, K, -1, nullptr, nullptr, nullptr, st);
 }
 
 hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,

@@ -68,6 +68,11 @@ size_t skinny_partial_bytes(int M, int N, int K);
 constexpr int kSkinnyMaxRows = 64;
 // bf16 weight-streaming GEMM for M <= kSkinnyMaxRows rows, two launches: partial sums per K
 // segment into `partials` (fp32 [S, M, N]), then a fixed-order reduction with the epilogue.
+// Weight-streaming GEMM with epilogue `epi` (EPI_*).  When the launch has a single K segment the
+// kernel applies the epilogue itself and *fused is true; otherwise it leaves partial sums in
+// `partials` and the caller follows with launch_gemm_skinny_reduce (or its own fused reduction).
+hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, int M, int N, int K, int epi,
+                              const void *res, void *out, bool *fused, hipStream_t st);
 hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
                                    int K, hipStream_t st);
 hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,

@@ -310,8 +310,9 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
         CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, st));
         if (skinny) {
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, st));
-            CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_gemm_skinny_reduce((const float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+            bool fused = false;
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, EPI_STORE_RM, nullptr, b->y, &fused, st));
+            if (!fused) CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_gemm_skinny_reduce((const float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
         } else {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, (long)variant_rows, (float *)(ws + p.scratch), st));
         }
@@ -337,8 +338,9 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
 #define CCS_GEMM(sid, woff, xoff, epi, res, out, N, K)                                                        \
     do {                                                                                                      \
         if (skinny) {                                                                                         \
-            CCS_STAGE(sid, launch_gemm_skinny_main(A + (woff), ws + (xoff), scratch, T, (N), (K), st));        \
-            CCS_STAGE((sid) + 1, launch_gemm_skinny_reduce(scratch, (epi), (res), (out), T, (N), (K), st));    \
+            bool fused__ = false;                                                                               \
+            CCS_STAGE(sid, launch_gemm_skinny(A + (woff), ws + (xoff), scratch, T, (N), (K), (epi), (res), (out), &fused__, st)); \
+            if (!fused__) CCS_STAGE((sid) + 1, launch_gemm_skinny_reduce(scratch, (epi), (res), (out), T, (N), (K), st)); \
         } else {                                                                                              \
             CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st)); \
         }                                                                                                     \

@@ -92,6 +92,21 @@ def test_bf16_linear_rows_across_variants():
         run_case(workloads.scaled(base, n_seqs=n), [1, 2, 4], seed=n)
 
 
+def test_bf16_weight_block_groups_with_padding():
+    """Weights are packed in groups of 8 row blocks: block counts that are not a multiple of 8
+    (65 blocks; gate/up with 348) exercise the zero padding, odd k-fragment counts the ragged
+    register sets of the weight-streaming GEMM."""
+    base = workloads.scaled(C["C5"], in_features=1056, out_features=1040)
+    for n in (3, 40, 64, 100, 300):
+        run_case(workloads.scaled(base, n_seqs=n), [1, 2], seed=20 + n)
+    dec = workloads.scaled(C["C2"], hidden=1056, n_q_heads=8, n_kv_heads=8, intermediate=2784,
+                           n_seqs=11, len_lo=0, len_hi=300)
+    run_case(dec, [1, 2], seed=31)
+    pre = workloads.scaled(C["C3"], hidden=1056, n_q_heads=8, n_kv_heads=4, intermediate=2784,
+                           n_seqs=3, seq_pad=70, len_lo=9, len_hi=70)
+    run_case(pre, [1, 3], seed=32)
+
+
 # ---------------------------------------------------------------- full-size configs
 def test_c2_llama7b_decode_full():
     run_case(C["C2"], [1, 2, 4])

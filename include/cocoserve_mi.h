@@ -151,10 +151,15 @@ int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice);
 
 /* The replicated forward of Section 3.1: cut the batch into k = ccs_module_replicas(m)
  * contiguous slices [floor(j n / k), floor((j+1) n / k)) - over sequences for a decoder layer,
- * over token rows for a projection - order `caller_stream` -> every replica stream (fork
- * event), run slice j on replica j, and order every replica stream -> `caller_stream` (join
- * events).  Outputs land in `full->y` at their batch positions, so the gather is free.
- * Output rows are bit-identical for every k at a fixed batch. */
+ * over token rows for a projection.  Slice 0 runs on `caller_stream` itself with replica 0's
+ * weights and workspace; for j >= 1 the call orders `caller_stream` -> replica j's stream (fork
+ * event), runs slice j there, and orders that stream -> `caller_stream` (join event).  Outputs
+ * land in `full->y` at their batch positions, so the gather is free.  Output rows are
+ * bit-identical for every k at a fixed batch.  The caller keeps successive uses of replica 0
+ * ordered (same stream, or its own events); work that created or migrated replica 0 must have
+ * completed.  The call only enqueues (kernel launches, event record / wait), so it may be
+ * recorded into a HIP graph by capturing `caller_stream` once every kernel variant it uses
+ * has been launched outside a capture (the first launch of a variant sets a function attribute). */
 int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream);
 
 /* Clone replica `replica`'s packed weights into `dst_arena` (device, arena_bytes) on `stream`

@@ -287,13 +287,14 @@ int check_batch(const ccs_module *m, const ccs_batch *b)
 
 // One replica, one slice.  variant_rows: row count that selects the GEMM variant (the full
 // batch's for a replicated forward, so that every replica count produces the same bits).
-int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows)
+int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows, bool on_caller_stream = false,
+                hipStream_t caller_stream = nullptr)
 {
     using namespace ccs;
     Replica &R = m->rep[r];
     const Dims &d = m->dims;
     const ccs_module_desc &D = m->desc;
-    hipStream_t st = R.stream;
+    hipStream_t st = on_caller_stream ? caller_stream : R.stream;
     if (b->n_seqs == 0) return CCS_OK;
     const bool bf = D.dtype == CCS_BF16;
     const bool skinny = bf && variant_rows <= kSkinnyMaxRows;
@@ -600,7 +601,7 @@ int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_
     const size_t y_row = (m->desc.kind == CCS_LINEAR ? (size_t)d.out_f : (size_t)d.H) * esz;
     const size_t cache_seq = (size_t)d.nkv * (size_t)full->cache_cap * d.d * esz;
 
-    CCS_HIP(hipEventRecord(m->fork, cs));
+    if (k > 1) CCS_HIP(hipEventRecord(m->fork, cs));
     for (int j = 0; j < k; ++j) {
         const long long lo = j * n / k, hi = (j + 1) * n / k;  // slice j = [floor(jn/k), floor((j+1)n/k))
         if (hi == lo) continue;
@@ -615,10 +616,12 @@ int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_
             s.k_cache = (char *)full->k_cache + (size_t)lo * cache_seq;
             s.v_cache = (char *)full->v_cache + (size_t)lo * cache_seq;
         }
-        if (R.stream != cs) CCS_HIP(hipStreamWaitEvent(R.stream, m->fork, 0));
-        rc = forward_one(m, j, &s, full_rows);
+        // slice 0 runs on the caller's stream itself (no events at k = 1); the others fork and join
+        const bool inline_ = (j == 0) || R.stream == cs;
+        if (!inline_) CCS_HIP(hipStreamWaitEvent(R.stream, m->fork, 0));
+        rc = forward_one(m, j, &s, full_rows, inline_, cs);
         if (rc != CCS_OK) return rc;
-        if (R.stream != cs) {
+        if (!inline_) {
             CCS_HIP(hipEventRecord(R.done, R.stream));
             CCS_HIP(hipStreamWaitEvent(cs, R.done, 0));
         }

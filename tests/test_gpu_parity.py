@@ -278,3 +278,41 @@ def test_empty_batches_more_replicas_than_sequences_and_errors():
         m.sync()
     finally:
         m.destroy()
+
+
+def test_forward_split_recorded_in_a_hip_graph_replays_like_eager():
+    """forward_split only enqueues kernels and fork/join events, so a caller may capture it.
+    Replays (with eager work and synchronisation between them, inputs changed in place) must
+    reproduce the eager result of the same inputs bit for bit."""
+    cfg = workloads.scaled(C["C2"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
+                           n_seqs=12, len_lo=10, len_hi=300)
+    m = U.make_module(cfg)
+    try:
+        for k in (1, 3):
+            say(f"[case] graph capture k={k}")
+            m.replicate(k)
+            inps = [workloads.make_inputs(cfg, seed) for seed in (40, 41, 42)]
+            db = U.DeviceBatch(m, cfg, inps[0])
+            m.forward_split(db.batch)          # every kernel variant has run once outside a capture
+            m.sync()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                m.forward_split(db.batch)
+            for rep, inp in enumerate(inps * 2):
+                # eager reference on a second set of buffers (its own caches: decode appends)
+                ref = U.DeviceBatch(m, cfg, inp)
+                m.forward_split(ref.batch)
+                m.sync()
+                db.x.copy_(ref.x)
+                db.k.copy_(U.to_dev(inp.k_cache, cfg)); db.v.copy_(U.to_dev(inp.v_cache, cfg))
+                db.lens_dev.copy_(ref.lens_dev)
+                db.y.zero_()
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(db.y, ref.y), f"k={k} replay {rep} differs from eager"
+                assert torch.equal(db.k, ref.k) and torch.equal(db.v, ref.v)
+    finally:
+        m.destroy()

@@ -2,8 +2,10 @@
  * cocoserve_mi.h - C ABI of the module-replica hot path for AMD Instinct MI355X (gfx950).
  *
  * The library implements the data-parallel core of CoCoServe's module scaling on ONE GPU:
- *   - a *module* is a LLaMA-style decoder layer or a single projection (the paper's module
- *     definition: Section 1, footnote on modules; Section 2.1 lists the projections);
+ *   - a *module* is a LLaMA-style decoder layer, a run of consecutive decoder layers, or a
+ *     single projection (the paper's module definition: Section 1, footnote on modules;
+ *     Section 2.1 lists the projections; Section 3.1: for consecutive replicated layers the
+ *     scatter and gather only happen at the two ends of the run);
  *   - *replication* clones the module's weights and runs the unmodified module on contiguous
  *     slices of the batch (15 requests -> 7 and 8), collecting the outputs in batch order
  *     (Section 3.1 "Replication");
@@ -27,8 +29,9 @@
  *   - Caller-side weights are row-major [out_features, in_features]; a forward computes
  *     y = x W^T, no bias (Section 2.1: projections are linear maps).
  *   - Activations x / y are row-major [rows, features] in the module's dtype.
- *   - KV caches are [n_seqs, n_kv_heads, cache_cap, head_dim] in the module's dtype; keys are
- *     stored after the rotary embedding.
+ *   - KV caches are [n_seqs, n_kv_heads, cache_cap, head_dim] in the module's dtype per layer
+ *     (layer l of a run starts cache_layer_stride bytes after layer l - 1); keys are stored
+ *     after the rotary embedding.
  *   - `ccs_module_create` re-packs the weights into the arena in the library's own streaming
  *     order; a clone is one contiguous copy of `ccs_module_arena_bytes` bytes.
  */
@@ -67,19 +70,24 @@ enum { CCS_MAX_REPLICAS = 16 };
  * rms_eps, rope_base; requires n_q_heads % n_kv_heads == 0 and head_dim even.  The bf16 path
  * additionally needs hidden, n_q_heads*head_dim and intermediate to be multiples of 32,
  * n_kv_heads*head_dim a multiple of 16 and head_dim == 128 (else CCS_EUNSUPPORTED); the f32 path takes
- * any shape with head_dim <= 256.  Linear: in_features, out_features (bf16: in % 32 == 0,
- * out % 16 == 0). */
+ * any shape with head_dim <= 256.  n_layers (0 is read as 1, at most CCS_MAX_LAYERS) makes
+ * the module a run of that many consecutive decoder layers of this shape, each with its own
+ * weights: the output of layer l is the input of layer l + 1 and a replica runs the whole run
+ * on its slice.  Linear: in_features, out_features (bf16: in % 32 == 0, out % 16 == 0). */
+enum { CCS_MAX_LAYERS = 128 };
 typedef struct ccs_module_desc {
     int32_t kind;  /* ccs_kind */
     int32_t dtype; /* ccs_dtype: storage type of weights, activations and caches */
     int32_t hidden, n_q_heads, n_kv_heads, head_dim, intermediate;
     int32_t in_features, out_features;
     float rms_eps, rope_base;
+    int32_t n_layers; /* decoder layers in the run; 0 or 1: a single layer */
 } ccs_module_desc;
 
 /* Device pointers to the caller's weights in the module's dtype, row-major [out, in].
  * Decoder layer: wq [n_q*d, H], wk/wv [n_kv*d, H], wo [H, n_q*d], wgate/wup [I, H],
  * wdown [H, I], g1/g2 [H] (RMSNorm gains).  Linear: w [out, in]; the others are ignored.
+ * A run of n_layers layers takes an array of n_layers of these, first layer first.
  * Read only during ccs_module_create. */
 typedef struct ccs_weights {
     const void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown, *g1, *g2;
@@ -97,6 +105,9 @@ typedef struct ccs_weights {
  *            required.  lens itself is not advanced by the library.
  *   ROWS:    x is [n_seqs, in_features], y is [n_seqs, out_features]; seq_pad, lens and the
  *            caches are ignored.
+ * A run of layers: every layer has caches of this shape; k_cache / v_cache point at the first
+ * layer's and layer l's start cache_layer_stride BYTES further each (at least the bytes of one
+ * layer's cache for the WHOLE batch the slice belongs to; ignored for a single layer).
  * lens_host and lens_dev hold the same n_seqs values (host copy for validation and launch
  * planning, device copy for the kernels).  n_seqs == 0 is a legal no-op. */
 typedef struct ccs_batch {
@@ -108,6 +119,7 @@ typedef struct ccs_batch {
     const int32_t *lens_dev;  /* device */
     void *k_cache, *v_cache;  /* device */
     int32_t cache_cap;
+    int64_t cache_layer_stride; /* bytes between consecutive layers' caches (runs of layers) */
 } ccs_batch;
 
 /* Bytes of one replica's packed weights (what a clone copies); 0 if the desc is invalid.
@@ -121,7 +133,8 @@ size_t ccs_module_arena_bytes(const ccs_module_desc *desc);
 size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
                                   int32_t max_seq_pad, int32_t max_cache_cap);
 
-/* Create a module with ONE instance (replica 0, "the original"): packs `weights` (device) into
+/* Create a module with ONE instance (replica 0, "the original"): packs `weights` (host array of
+ * max(1, n_layers) structs holding device pointers) into
  * `arena0` (device, >= ccs_module_arena_bytes, 256-byte aligned) on `stream`, and remembers
  * `workspace0` (device, workspace_bytes long, 256-byte aligned) and `stream` as replica 0's.
  * The caller's weight buffers may be released after the stream has been synchronised.

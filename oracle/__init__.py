@@ -180,6 +180,26 @@ def decoder_layer_decode(desc: LayerDesc, w: dict, x, lens, k_cache, v_cache):
     return y
 
 
+def decoder_stack_prefill(desc: LayerDesc, layers, x, lens, k_caches=None, v_caches=None):
+    """A run of consecutive decoder layers (Section 3.1): layer l's output is layer l + 1's
+    input.  layers: list of weight dicts; optional caches [L, B, n_kv, cap, d], one per layer."""
+    y = _f32(x)
+    for l, w in enumerate(layers):
+        kc = None if k_caches is None else k_caches[l]
+        vc = None if v_caches is None else v_caches[l]
+        y = decoder_layer_prefill(desc, w, y, lens, kc, vc)
+    return y
+
+
+def decoder_stack_decode(desc: LayerDesc, layers, x, lens, k_caches, v_caches):
+    """One decode step through a run of layers; caches [L, B, n_kv, cap, d] updated in place
+    (every layer appends its own key / value at slot lens[b])."""
+    y = _f32(x)
+    for l, w in enumerate(layers):
+        y = decoder_layer_decode(desc, w, y, lens, k_caches[l], v_caches[l])
+    return y
+
+
 def forward_split(forward_slice, n: int, k: int):
     """The replicated forward as the paper states it: cut [0, n) into k contiguous slices,
     run the unmodified module on each, put the outputs back in order.

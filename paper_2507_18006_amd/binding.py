@@ -43,7 +43,8 @@ class ccs_module_desc(ctypes.Structure):
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("intermediate", ctypes.c_int32),
                 ("in_features", ctypes.c_int32), ("out_features", ctypes.c_int32),
-                ("rms_eps", ctypes.c_float), ("rope_base", ctypes.c_float)]
+                ("rms_eps", ctypes.c_float), ("rope_base", ctypes.c_float),
+                ("n_layers", ctypes.c_int32)]
 
 
 class ccs_weights(ctypes.Structure):
@@ -56,7 +57,7 @@ class ccs_batch(ctypes.Structure):
                 ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
                 ("lens_host", ctypes.c_void_p), ("lens_dev", ctypes.c_void_p),
                 ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
-                ("cache_cap", ctypes.c_int32)]
+                ("cache_cap", ctypes.c_int32), ("cache_layer_stride", ctypes.c_int64)]
 
 
 _lib = None
@@ -125,11 +126,12 @@ class ModuleDesc:
     out_features: int = 0
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    n_layers: int = 1
 
     def c(self) -> ccs_module_desc:
         return ccs_module_desc(self.kind, self.dtype, self.hidden, self.n_q_heads, self.n_kv_heads,
                                self.head_dim, self.intermediate, self.in_features, self.out_features,
-                               self.rms_eps, self.rope_base)
+                               self.rms_eps, self.rope_base, self.n_layers)
 
 
 def module_arena_bytes(desc: ModuleDesc) -> int:
@@ -176,16 +178,19 @@ class Module:
         # replica 0 lives on the stream that is current at creation: a replicated forward issued
         # from that stream then needs no fork/join events for it (and none at all at k = 1)
         self.streams = [torch.cuda.current_stream(self.device)]
-        cw = ccs_weights()
-        keep = []
-        for name, t in weights.items():
-            if t.dtype != self.torch_dtype or not t.is_cuda or not t.is_contiguous():
-                raise ValueError(f"weight {name}: need a contiguous {self.torch_dtype} CUDA tensor")
-            keep.append(t)
-            setattr(cw, name, t.data_ptr())
+        # one dict of tensors, or a list of them for a run of n_layers decoder layers
+        layers = list(weights) if isinstance(weights, (list, tuple)) else [weights]
+        if len(layers) != max(1, desc.n_layers):
+            raise ValueError(f"need the weights of {max(1, desc.n_layers)} layers, got {len(layers)}")
+        cw = (ccs_weights * len(layers))()
+        for l, wl in enumerate(layers):
+            for name, t in wl.items():
+                if t.dtype != self.torch_dtype or not t.is_cuda or not t.is_contiguous():
+                    raise ValueError(f"weight {name}: need a contiguous {self.torch_dtype} CUDA tensor")
+                setattr(cw[l], name, t.data_ptr())
         d = desc.c()
         h = ctypes.c_void_p()
-        _check(self.L.ccs_module_create(ctypes.byref(d), ctypes.byref(cw), self.arenas[0].data_ptr(),
+        _check(self.L.ccs_module_create(ctypes.byref(d), cw, self.arenas[0].data_ptr(),
                                         self.workspaces[0].data_ptr(), self.ws_bytes,
                                         self.streams[0].cuda_stream, ctypes.byref(h)))
         self.handle = h
@@ -217,12 +222,17 @@ class Module:
     # -- batches --------------------------------------------------------------------------------
     def batch(self, mode: int, x, y, lens_host=None, lens_dev=None, k_cache=None, v_cache=None,
               seq_pad: int = 1):
-        """Marshal tensors into a ccs_batch.  x: prefill [B,S,H] / decode [B,H] / rows [T,in]."""
+        """Marshal tensors into a ccs_batch.  x: prefill [B,S,H] / decode [B,H] / rows [T,in];
+        caches [B, n_kv, cap, d], or [n_layers, B, n_kv, cap, d] for a run of layers."""
         n_seqs = x.shape[0]
-        cap = 0 if k_cache is None else k_cache.shape[2]
+        cap, stride = 0, 0
+        if k_cache is not None:
+            cap = k_cache.shape[-2]
+            if k_cache.dim() == 5:
+                stride = k_cache.stride(0) * k_cache.element_size()
         b = ccs_batch(mode, n_seqs, seq_pad, _ptr(x), _ptr(y),
                       None if lens_host is None else lens_host.data_ptr(), _ptr(lens_dev),
-                      _ptr(k_cache), _ptr(v_cache), cap)
+                      _ptr(k_cache), _ptr(v_cache), cap, stride)
         b._keep = (x, y, lens_host, lens_dev, k_cache, v_cache)
         return b
 

@@ -37,15 +37,18 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Dims {
     int H, nq, nkv, d, I, QD, KD, W3;  // W3 = QD + 2 KD
     int in_f, out_f;
+    int L;  // decoder layers in the run (1 for a single layer or a projection)
     size_t esz;
 };
 
 struct ArenaPlan {
-    size_t qkv, o, gu, dn, g1, g2, rope, w, total;
+    size_t qkv, o, gu, dn, g1, g2, rope, w;  // offsets inside one layer
+    size_t layer;                            // bytes of one layer (256-byte multiple)
+    size_t total;                            // layers * layer
 };
 
 struct WsPlan {
-    size_t h, qkv, a, x1, gu, u, xp, kp, vtp, scratch, scratch_bytes, total;
+    size_t h, qkv, a, x1, gu, u, xp, kp, vtp, xa, xb, scratch, scratch_bytes, total;  // xa, xb: activations between layers of a run
 };
 
 int check_desc(const ccs_module_desc *D, Dims *out)
@@ -54,7 +57,10 @@ int check_desc(const ccs_module_desc *D, Dims *out)
     if (D->dtype != CCS_F32 && D->dtype != CCS_BF16) return fail(CCS_EINVAL, "unknown dtype %d", D->dtype);
     Dims d{};
     d.esz = D->dtype == CCS_BF16 ? 2 : 4;
+    d.L = 1;
+    if (D->n_layers < 0 || D->n_layers > CCS_MAX_LAYERS) return fail(CCS_EINVAL, "n_layers must be in [0, %d]", (int)CCS_MAX_LAYERS);
     if (D->kind == CCS_DECODER_LAYER) {
+        d.L = D->n_layers > 1 ? D->n_layers : 1;
         if (D->hidden <= 0 || D->n_q_heads <= 0 || D->n_kv_heads <= 0 || D->head_dim <= 0 || D->intermediate <= 0)
             return fail(CCS_EINVAL, "decoder-layer dimensions must be positive");
         if (D->n_q_heads % D->n_kv_heads) return fail(CCS_EINVAL, "n_q_heads %% n_kv_heads != 0");
@@ -71,6 +77,7 @@ int check_desc(const ccs_module_desc *D, Dims *out)
             if (G != 1 && G != 2 && G != 4 && G != 8) return fail(CCS_EUNSUPPORTED, "bf16 path: n_q/n_kv must be 1, 2, 4 or 8");
         }
     } else if (D->kind == CCS_LINEAR) {
+        if (D->n_layers > 1) return fail(CCS_EINVAL, "n_layers applies to decoder layers only");
         if (D->in_features <= 0 || D->out_features <= 0) return fail(CCS_EINVAL, "linear dimensions must be positive");
         d.in_f = D->in_features; d.out_f = D->out_features;
         if (D->dtype == CCS_BF16 && (d.in_f % 32 || d.out_f % 16))
@@ -100,7 +107,8 @@ ArenaPlan arena_plan(const ccs_module_desc *D, const Dims &d)
         p.g2 = take((size_t)d.H * d.esz);
         p.rope = take((size_t)(d.d / 2) * 2 * sizeof(float));  // inverse-frequency table (fp32 head + tail)
     }
-    p.total = off;
+    p.layer = off;
+    p.total = off * (size_t)d.L;
     return p;
 }
 
@@ -135,6 +143,10 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
             p.kp = take((size_t)n_seqs * d.nkv * s32 * d.d * 2);
             p.vtp = take((size_t)n_seqs * d.nkv * s32 * d.d * 2);
         }
+        if (d.L > 1) {
+            p.xa = take(rows * d.H * 2);
+            p.xb = take(rows * d.H * 2);
+        }
         size_t s = 0;
         if (skinny) {
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.W3, d.H));
@@ -157,6 +169,10 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
         p.x1 = take(rows * d.H * 4);
         p.gu = take(rows * 2 * d.I * 4);
         p.u = take(rows * d.I * 4);
+        if (d.L > 1) {
+            p.xa = take(rows * d.H * 4);
+            p.xb = take(rows * d.H * 4);
+        }
     }
     p.total = off;
     return p;
@@ -281,7 +297,11 @@ int check_batch(const ccs_module *m, const ccs_batch *b)
         }
         if (m->desc.dtype == CCS_F32 && b->cache_cap > 8192) return fail(CCS_EUNSUPPORTED, "f32 decode: cache_cap > 8192");
     }
-    (void)d;
+    if (d.L > 1 && b->k_cache) {
+        const long long one = (long long)b->n_seqs * d.nkv * b->cache_cap * d.d * (long long)d.esz;
+        if (b->cache_layer_stride < one) return fail(CCS_EINVAL, "cache_layer_stride %lld is less than one layer's cache (%lld bytes)", (long long)b->cache_layer_stride, one);
+        if (b->cache_layer_stride % 16) return fail(CCS_EINVAL, "cache_layer_stride must be a multiple of 16 bytes");
+    }
     return CCS_OK;
 }
 
@@ -299,9 +319,10 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     const bool bf = D.dtype == CCS_BF16;
     const bool skinny = bf && variant_rows <= kSkinnyMaxRows;
     char *ws = (char *)R.ws;
-    const char *A = (const char *)R.arena;
+    const char *A0 = (const char *)R.arena;
 
     if (D.kind == CCS_LINEAR) {
+        const char *A = A0;
         const int M = b->n_seqs;
         if (!bf) {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)b->x, (const float *)(A + m->ap.w), nullptr, (float *)b->y, M, d.out_f, d.in_f, st));
@@ -326,64 +347,88 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, decode ? 0 : seq_pad, (long)variant_rows);
     if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
-
     const bool row_norm = skinny && d.H <= 8192 && d.H % 4 == 0;  // few rows: one workgroup per row
-    if (row_norm)
-        CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm_rows(b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
-    else
-        CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm(dt, b->x, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
-    const void *tab = A + m->ap.rope;
-    if (bf) {
-        float *scratch = (float *)(ws + p.scratch);
-        // one projection: weight-streaming (two launches) or LDS-tiled (one launch)
+
+    // A run of layers: layer l reads x_in and writes x_out, ping-ponging between two workspace
+    // buffers; the first layer reads the batch's x, the last writes its y (Section 3.1: inside a
+    // run of consecutive layers nothing is scattered or gathered).
+    bool h_ready = false;   // h already holds RMSNorm_1 of x_in (fused into the previous layer's last reduction)
+    for (int l = 0; l < d.L; ++l) {
+        const char *A = A0 + (size_t)l * m->ap.layer;
+        const void *x_in = l == 0 ? b->x : (const void *)(ws + ((l & 1) ? p.xa : p.xb));
+        void *x_out = l == d.L - 1 ? b->y : (void *)(ws + ((l & 1) ? p.xb : p.xa));
+        void *kc = b->k_cache ? (char *)b->k_cache + (size_t)l * (size_t)b->cache_layer_stride : nullptr;
+        void *vc = b->v_cache ? (char *)b->v_cache + (size_t)l * (size_t)b->cache_layer_stride : nullptr;
+        const bool last = l == d.L - 1;
+
+        if (!h_ready) {
+            if (row_norm)
+                CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm_rows(x_in, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+            else
+                CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm(dt, x_in, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+        }
+        h_ready = false;
+        const void *tab = A + m->ap.rope;
+        if (bf) {
+            float *scratch = (float *)(ws + p.scratch);
+            // one projection: weight-streaming (one or two launches) or LDS-tiled (one launch)
 #define CCS_GEMM(sid, woff, xoff, epi, res, out, N, K)                                                        \
     do {                                                                                                      \
         if (skinny) {                                                                                         \
-            bool fused__ = false;                                                                               \
+            bool fused__ = false;                                                                             \
             CCS_STAGE(sid, launch_gemm_skinny(A + (woff), ws + (xoff), scratch, T, (N), (K), (epi), (res), (out), &fused__, st)); \
             if (!fused__) CCS_STAGE((sid) + 1, launch_gemm_skinny_reduce(scratch, (epi), (res), (out), T, (N), (K), st)); \
         } else {                                                                                              \
             CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st)); \
         }                                                                                                     \
     } while (0)
-        if (skinny && decode) {
-            // weight-streaming Q/K/V projection; its reduction also rotates and appends to the cache
-            CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_skinny_main(A + m->ap.qkv, ws + p.h, scratch, T, d.W3, d.H, st));
-            CCS_STAGE(CCS_ST_GEMM_QKV_REDUCE, launch_qkv_reduce_rope_decode(scratch, skinny_segments(d.W3, d.H), T, d.nq, d.nkv, tab, b->lens_dev, ws + p.qkv, b->k_cache, b->v_cache, b->cache_cap, st));
-        } else {
-            CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
-            if (decode)
-                CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-            else
-                CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        }
-        if (decode) {
-            CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-            CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, b->lens_dev, b->cache_cap, st));
-        } else {
-            CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, b->lens_dev, st));
-        }
-        if (row_norm) {
-            // weight-streaming O projection; its reduction adds the residual and applies the second norm
-            CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_skinny_main(A + m->ap.o, ws + p.a, scratch, T, d.H, d.QD, st));
-            CCS_STAGE(CCS_ST_GEMM_O_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.QD), T, d.H, b->x, A + m->ap.g2, D.rms_eps, ws + p.x1, ws + p.h, st));
-        } else {
-            CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, b->x, ws + p.x1, d.H, d.QD);
-            CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
-        }
-        CCS_GEMM(CCS_ST_GEMM_GU, m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H);
-        CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, ws + p.x1, b->y, d.H, d.I);
+            if (skinny && decode) {
+                // weight-streaming Q/K/V projection; its reduction also rotates and appends to the cache
+                CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_skinny_main(A + m->ap.qkv, ws + p.h, scratch, T, d.W3, d.H, st));
+                CCS_STAGE(CCS_ST_GEMM_QKV_REDUCE, launch_qkv_reduce_rope_decode(scratch, skinny_segments(d.W3, d.H), T, d.nq, d.nkv, tab, b->lens_dev, ws + p.qkv, kc, vc, b->cache_cap, st));
+            } else {
+                CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
+                if (decode)
+                    CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
+                else
+                    CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, b->lens_dev, kc, vc, b->cache_cap, st));
+            }
+            if (decode) {
+                CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
+                CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, b->lens_dev, b->cache_cap, st));
+            } else {
+                CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, b->lens_dev, st));
+            }
+            if (row_norm) {
+                // weight-streaming O projection; its reduction adds the residual and applies the second norm
+                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_skinny_main(A + m->ap.o, ws + p.a, scratch, T, d.H, d.QD, st));
+                CCS_STAGE(CCS_ST_GEMM_O_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.QD), T, d.H, x_in, A + m->ap.g2, D.rms_eps, ws + p.x1, ws + p.h, st));
+            } else {
+                CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, x_in, ws + p.x1, d.H, d.QD);
+                CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+            }
+            CCS_GEMM(CCS_ST_GEMM_GU, m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H);
+            if (row_norm && !last) {
+                // inside a run: the down projection's reduction adds the residual and already applies
+                // the next layer's first norm (same kernel as after the O projection)
+                CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.dn, ws + p.u, scratch, T, d.H, d.I, st));
+                CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.I), T, d.H, ws + p.x1, A + m->ap.layer + m->ap.g1, D.rms_eps, x_out, ws + p.h, st));
+                h_ready = true;
+            } else {
+                CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, ws + p.x1, x_out, d.H, d.I);
+            }
 #undef CCS_GEMM
-    } else {
-        auto W = [&](size_t off) { return (const float *)(A + off); };
-        CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
-        CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, b->k_cache, b->v_cache, b->cache_cap, st));
-        CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)b->x, (float *)(ws + p.x1), T, d.H, d.QD, st));
-        CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
-        CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.gu), nullptr, (float *)(ws + p.gu), T, 2 * d.I, d.H, st));
-        CCS_STAGE(CCS_ST_GEMM_GU_REDUCE, launch_swiglu_f32((const float *)(ws + p.gu), (float *)(ws + p.u), T, d.I, st));
-        CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)(ws + p.u), W(m->ap.dn), (const float *)(ws + p.x1), (float *)b->y, T, d.H, d.I, st));
+        } else {
+            auto W = [&](size_t off) { return (const float *)(A + off); };
+            CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
+            CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
+            CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
+            CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)x_in, (float *)(ws + p.x1), T, d.H, d.QD, st));
+            CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+            CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.gu), nullptr, (float *)(ws + p.gu), T, 2 * d.I, d.H, st));
+            CCS_STAGE(CCS_ST_GEMM_GU_REDUCE, launch_swiglu_f32((const float *)(ws + p.gu), (float *)(ws + p.u), T, d.I, st));
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)(ws + p.u), W(m->ap.dn), (const float *)(ws + p.x1), (float *)x_out, T, d.H, d.I, st));
+        }
     }
     return CCS_OK;
 }
@@ -447,8 +492,10 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
     if (((uintptr_t)arena0 & 255) || ((uintptr_t)workspace0 & 255)) return fail(CCS_EINVAL, "arena0 / workspace0 must be 256-byte aligned");
     if (desc->kind == CCS_LINEAR) {
         if (!w->w) return fail(CCS_EINVAL, "weights.w is null");
-    } else if (!w->wq || !w->wk || !w->wv || !w->wo || !w->wgate || !w->wup || !w->wdown || !w->g1 || !w->g2) {
-        return fail(CCS_EINVAL, "a decoder-layer weight pointer is null");
+    } else {
+        for (int l = 0; l < d.L; ++l)
+            if (!w[l].wq || !w[l].wk || !w[l].wv || !w[l].wo || !w[l].wgate || !w[l].wup || !w[l].wdown || !w[l].g1 || !w[l].g2)
+                return fail(CCS_EINVAL, "a weight pointer of layer %d is null", l);
     }
     int ndev = 0;
     CCS_HIP(hipGetDeviceCount(&ndev));
@@ -460,49 +507,52 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
     m->dims = d;
     m->ap = arena_plan(desc, d);
     hipStream_t st = (hipStream_t)stream;
-    char *A = (char *)arena0;
     const bool bf = desc->dtype == CCS_BF16;
     hipError_t e = hipSuccess;
-    auto rm_copy = [&](size_t off, const void *src, size_t bytes) { if (e == hipSuccess) e = launch_clone(A + off, src, bytes, st); };
-    auto pack = [&](size_t off, const void *src, int N, int K, int stride, int blk_off) {
-        if (e == hipSuccess) e = launch_pack_bf16(src, A + off, N, K, stride, blk_off, true, st);
-    };
-    // padding fragments of a weight whose block count is not a multiple of the group must be zero
-    auto zero_if_padded = [&](size_t off, int N, int K) {
-        if (e == hipSuccess && bf && ccs::packed_weight_bytes(N, K) != (size_t)N * K * 2)
-            e = hipMemsetAsync(A + off, 0, ccs::packed_weight_bytes(N, K), st);
-    };
-    if (desc->kind == CCS_LINEAR) {
-        zero_if_padded(m->ap.w, d.out_f, d.in_f);
-        if (bf) pack(m->ap.w, w->w, d.out_f, d.in_f, 1, 0);
-        else rm_copy(m->ap.w, w->w, (size_t)d.out_f * d.in_f * 4);
-    } else if (bf) {
-        zero_if_padded(m->ap.qkv, d.W3, d.H);
-        zero_if_padded(m->ap.o, d.H, d.QD);
-        zero_if_padded(m->ap.gu, 2 * d.I, d.H);
-        zero_if_padded(m->ap.dn, d.H, d.I);
-        pack(m->ap.qkv, w->wq, d.QD, d.H, 1, 0);
-        pack(m->ap.qkv, w->wk, d.KD, d.H, 1, d.QD / 16);
-        pack(m->ap.qkv, w->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16);
-        pack(m->ap.o, w->wo, d.H, d.QD, 1, 0);
-        pack(m->ap.gu, w->wgate, d.I, d.H, 2, 0);  // gate blocks even, up blocks odd
-        pack(m->ap.gu, w->wup, d.I, d.H, 2, 1);
-        pack(m->ap.dn, w->wdown, d.H, d.I, 1, 0);
-        rm_copy(m->ap.g1, w->g1, (size_t)d.H * 2);
-        rm_copy(m->ap.g2, w->g2, (size_t)d.H * 2);
-    } else {
-        const size_t rowb = (size_t)d.H * 4;
-        rm_copy(m->ap.qkv, w->wq, d.QD * rowb);
-        rm_copy(m->ap.qkv + d.QD * rowb, w->wk, d.KD * rowb);
-        rm_copy(m->ap.qkv + (d.QD + d.KD) * rowb, w->wv, d.KD * rowb);
-        rm_copy(m->ap.o, w->wo, (size_t)d.H * d.QD * 4);
-        rm_copy(m->ap.gu, w->wgate, d.I * rowb);
-        rm_copy(m->ap.gu + d.I * rowb, w->wup, d.I * rowb);
-        rm_copy(m->ap.dn, w->wdown, (size_t)d.H * d.I * 4);
-        rm_copy(m->ap.g1, w->g1, rowb);
-        rm_copy(m->ap.g2, w->g2, rowb);
+    for (int l = 0; l < d.L; ++l) {
+        char *A = (char *)arena0 + (size_t)l * m->ap.layer;
+        const ccs_weights *wl = w + l;
+        auto rm_copy = [&](size_t off, const void *src, size_t bytes) { if (e == hipSuccess) e = launch_clone(A + off, src, bytes, st); };
+        auto pack = [&](size_t off, const void *src, int N, int K, int stride, int blk_off) {
+            if (e == hipSuccess) e = launch_pack_bf16(src, A + off, N, K, stride, blk_off, true, st);
+        };
+        // padding fragments of a weight whose block count is not a multiple of the group must be zero
+        auto zero_if_padded = [&](size_t off, int N, int K) {
+            if (e == hipSuccess && bf && ccs::packed_weight_bytes(N, K) != (size_t)N * K * 2)
+                e = hipMemsetAsync(A + off, 0, ccs::packed_weight_bytes(N, K), st);
+        };
+        if (desc->kind == CCS_LINEAR) {
+            zero_if_padded(m->ap.w, d.out_f, d.in_f);
+            if (bf) pack(m->ap.w, wl->w, d.out_f, d.in_f, 1, 0);
+            else rm_copy(m->ap.w, wl->w, (size_t)d.out_f * d.in_f * 4);
+        } else if (bf) {
+            zero_if_padded(m->ap.qkv, d.W3, d.H);
+            zero_if_padded(m->ap.o, d.H, d.QD);
+            zero_if_padded(m->ap.gu, 2 * d.I, d.H);
+            zero_if_padded(m->ap.dn, d.H, d.I);
+            pack(m->ap.qkv, wl->wq, d.QD, d.H, 1, 0);
+            pack(m->ap.qkv, wl->wk, d.KD, d.H, 1, d.QD / 16);
+            pack(m->ap.qkv, wl->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16);
+            pack(m->ap.o, wl->wo, d.H, d.QD, 1, 0);
+            pack(m->ap.gu, wl->wgate, d.I, d.H, 2, 0);  // gate blocks even, up blocks odd
+            pack(m->ap.gu, wl->wup, d.I, d.H, 2, 1);
+            pack(m->ap.dn, wl->wdown, d.H, d.I, 1, 0);
+            rm_copy(m->ap.g1, wl->g1, (size_t)d.H * 2);
+            rm_copy(m->ap.g2, wl->g2, (size_t)d.H * 2);
+        } else {
+            const size_t rowb = (size_t)d.H * 4;
+            rm_copy(m->ap.qkv, wl->wq, d.QD * rowb);
+            rm_copy(m->ap.qkv + d.QD * rowb, wl->wk, d.KD * rowb);
+            rm_copy(m->ap.qkv + (d.QD + d.KD) * rowb, wl->wv, d.KD * rowb);
+            rm_copy(m->ap.o, wl->wo, (size_t)d.H * d.QD * 4);
+            rm_copy(m->ap.gu, wl->wgate, d.I * rowb);
+            rm_copy(m->ap.gu + d.I * rowb, wl->wup, d.I * rowb);
+            rm_copy(m->ap.dn, wl->wdown, (size_t)d.H * d.I * 4);
+            rm_copy(m->ap.g1, wl->g1, rowb);
+            rm_copy(m->ap.g2, wl->g2, rowb);
+        }
+        if (e == hipSuccess && desc->kind == CCS_DECODER_LAYER) e = launch_rope_table(A + m->ap.rope, d.d, desc->rope_base, st);
     }
-    if (e == hipSuccess && desc->kind == CCS_DECODER_LAYER) e = launch_rope_table(A + m->ap.rope, d.d, desc->rope_base, st);
     if (e != hipSuccess) {
         delete m;
         return fail(CCS_EHIP, "packing weights: %s", hipGetErrorString(e));

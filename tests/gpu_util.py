@@ -16,7 +16,7 @@ def module_desc(cfg: workloads.Config) -> B.ModuleDesc:
         return B.ModuleDesc(kind=B.CCS_LINEAR, dtype=dt, in_features=cfg.in_features, out_features=cfg.out_features)
     return B.ModuleDesc(kind=B.CCS_DECODER_LAYER, dtype=dt, hidden=cfg.hidden, n_q_heads=cfg.n_q_heads,
                         n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, intermediate=cfg.intermediate,
-                        rms_eps=cfg.rms_eps, rope_base=cfg.rope_base)
+                        rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, n_layers=cfg.n_layers)
 
 
 def oracle_desc(cfg: workloads.Config) -> oracle.LayerDesc:
@@ -35,7 +35,7 @@ def to_dev(a: np.ndarray, cfg):
 
 def make_module(cfg, weights=None, seed=0, max_seqs=None, max_seq_pad=None, max_cap=None) -> B.Module:
     w = workloads.make_weights(cfg, seed) if weights is None else weights
-    wd = {k: to_dev(v, cfg) for k, v in w.items()}
+    wd = [{k: to_dev(v, cfg) for k, v in wl.items()} for wl in w] if isinstance(w, list) else {k: to_dev(v, cfg) for k, v in w.items()}
     decode = cfg.mode == "decode"
     m = B.Module(module_desc(cfg), wd,
                  max_seqs=cfg.n_seqs if max_seqs is None else max_seqs,
@@ -63,6 +63,8 @@ class DeviceBatch:
             self.k, self.v = to_dev(inp.k_cache, cfg), to_dev(inp.v_cache, cfg)
         elif with_cache:
             shape = (inp.x.shape[0], cfg.n_kv_heads, with_cache, cfg.head_dim)
+            if cfg.n_layers > 1:
+                shape = (cfg.n_layers,) + shape
             self.k = torch.zeros(shape, dtype=tdtype(cfg), device=DEV)
             self.v = torch.zeros(shape, dtype=tdtype(cfg), device=DEV)
         self.batch = m.batch(mode, self.x, self.y, self.lens_host, self.lens_dev, self.k, self.v,
@@ -98,6 +100,13 @@ def oracle_forward(cfg, seed: int = 0, weights=None, inputs=None, seqs=None, ret
     if cfg.kind == "linear":
         return oracle.linear(inp.x[sel], w["w"])
     d = oracle_desc(cfg)
+    if cfg.n_layers > 1:   # a run of layers; caches [L, B, ...]
+        if cfg.mode == "prefill":
+            return oracle.decoder_stack_prefill(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel])
+        kc = np.ascontiguousarray(inp.k_cache[:, sel]).copy()
+        vc = np.ascontiguousarray(inp.v_cache[:, sel]).copy()
+        y = oracle.decoder_stack_decode(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel], kc, vc)
+        return (y, kc, vc) if return_caches else y
     if cfg.mode == "prefill":
         return oracle.decoder_layer_prefill(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel])
     kc = np.ascontiguousarray(inp.k_cache[sel]).copy()

@@ -107,6 +107,64 @@ def test_bf16_weight_block_groups_with_padding():
     run_case(pre, [1, 3], seed=32)
 
 
+# ---------------------------------------------------------------- runs of consecutive layers
+def test_runs_of_layers_match_the_oracle_and_split_bit_exactly():
+    """A module of several consecutive decoder layers (Section 3.1: inputs are scattered and
+    outputs gathered only at the two ends of the run): every replica runs the whole run on its
+    slice.  Errors of the bf16 path add up over the layers, the bar stays 2e-2."""
+    f32 = workloads.scaled(C["C1"], n_layers=3, n_q_heads=4, n_kv_heads=2, n_seqs=5, seq_pad=24, len_lo=3, len_hi=24)
+    run_case(f32, [1, 2, 3], seed=50)
+    run_case(workloads.scaled(f32, mode="decode", n_seqs=7, seq_pad=1, len_lo=0, len_hi=40), [1, 2, 4], seed=51)
+    dec = workloads.scaled(C["C2"], n_layers=3, hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
+                           n_seqs=15, len_lo=100, len_hi=400)
+    run_case(dec, [1, 2, 4], seed=52)
+    gqa = workloads.scaled(C["C4"], n_layers=2, hidden=1024, n_q_heads=16, n_kv_heads=2, intermediate=1792,
+                           n_seqs=70, len_lo=0, len_hi=200)      # 70 rows: the LDS-tiled GEMMs, decode
+    run_case(gqa, [1, 2], seed=53)
+    pre = workloads.scaled(C["C3"], n_layers=2, hidden=1024, n_q_heads=8, n_kv_heads=4, intermediate=2752,
+                           n_seqs=5, seq_pad=80, len_lo=17, len_hi=80)
+    run_case(pre, [1, 2], seed=54)
+
+
+def test_run_of_layers_fills_and_extends_every_layers_cache():
+    """Prefill a run with caches, then decode one token: equals the oracle's run on the same
+    inputs, cache rows included (each layer's cache is its own)."""
+    cfg = workloads.scaled(C["C3"], n_layers=2, hidden=1024, n_q_heads=8, n_kv_heads=4, intermediate=2752,
+                           n_seqs=3, seq_pad=40, len_lo=5, len_hi=40)
+    import oracle
+    w = workloads.make_weights(cfg, 60)
+    inp = workloads.make_inputs(cfg, 60)
+    cap = 64
+    d = U.oracle_desc(cfg)
+    kc = np.zeros((2, cfg.n_seqs, cfg.n_kv_heads, cap, cfg.head_dim), np.float32)
+    vc = np.zeros_like(kc)
+    oracle.decoder_stack_prefill(d, w, inp.x, inp.lens, kc, vc)
+    xd = workloads.make_inputs(workloads.scaled(cfg, mode="decode", seq_pad=1), 61).x
+    ref = oracle.decoder_stack_decode(d, w, xd, inp.lens, kc, vc)
+    m = U.make_module(cfg, w, max_cap=cap)
+    try:
+        for k in (1, 2):
+            say(f"[case] run of layers prefill -> decode k={k}")
+            m.replicate(k)
+            db = U.DeviceBatch(m, cfg, inp, with_cache=cap)
+            m.forward_split(db.batch)
+            dcfg = workloads.scaled(cfg, mode="decode", seq_pad=1)
+            dd = U.DeviceBatch(m, dcfg, workloads.Inputs(x=xd, lens=inp.lens))
+            dd.k, dd.v = db.k, db.v
+            dd.batch = m.batch(B.CCS_DECODE, dd.x, dd.y, dd.lens_host, dd.lens_dev, db.k, db.v)
+            m.forward_split(dd.batch)
+            y = dd.out()
+            err = U.rel_err(y, ref)
+            say(f"  rel_err={err:.3e}")
+            assert err <= TOL["bf16"]
+            gk = db.k.float().cpu().numpy()
+            for b in range(cfg.n_seqs):
+                n = int(inp.lens[b]) + 1
+                assert U.rel_err(gk[:, b, :, :n], kc[:, b, :, :n]) <= TOL["bf16"]
+    finally:
+        m.destroy()
+
+
 # ---------------------------------------------------------------- full-size configs
 def test_c2_llama7b_decode_full():
     run_case(C["C2"], [1, 2, 4])

@@ -367,3 +367,69 @@ def test_workload_generator_is_seeded_and_storage_exact():
     n = workloads.bursty_token_counts()
     assert len(n) == 200 and min(n) >= 1 and n == workloads.bursty_token_counts()
     assert [workloads.replicas_for_tokens(v) for v in (1, 127, 128, 511, 512)] == [1, 1, 2, 2, 4]
+
+
+# ---------------------------------------------------------------- runs of consecutive layers
+def _stack_cfg(n_layers=2, **kw):
+    base = workloads.scaled(workloads.CONFIGS["C1"], n_q_heads=4, n_kv_heads=2, hidden=64, head_dim=16,
+                            intermediate=96, n_layers=n_layers)
+    return workloads.scaled(base, **kw)
+
+
+def _odesc(cfg):
+    return oracle.LayerDesc(cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.intermediate,
+                            cfg.rms_eps, cfg.rope_base)
+
+
+def test_stack_is_the_composition_of_its_layers_and_one_layer_is_the_layer():
+    """Section 3.1: consecutive layers feed each other, nothing else happens in between."""
+    cfg = _stack_cfg(3, n_seqs=3, seq_pad=9, len_lo=2, len_hi=9)
+    ws = workloads.make_weights(cfg, 7)
+    inp = workloads.make_inputs(cfg, 7)
+    d = _odesc(cfg)
+    y = oracle.decoder_stack_prefill(d, ws, inp.x, inp.lens)
+    z = inp.x
+    for w in ws:
+        z = oracle.decoder_layer_prefill(d, w, z, inp.lens)
+    mask = np.arange(cfg.seq_pad)[None, :] < inp.lens[:, None]
+    assert np.array_equal(y[mask], z[mask])
+    one = oracle.decoder_stack_prefill(d, ws[:1], inp.x, inp.lens)
+    assert np.array_equal(one[mask], oracle.decoder_layer_prefill(d, ws[0], inp.x, inp.lens)[mask])
+    # every layer changes the result (none is skipped)
+    assert not np.allclose(y[mask], oracle.decoder_stack_prefill(d, ws[:2], inp.x, inp.lens)[mask])
+
+
+def test_stack_prefill_then_decode_equals_longer_prefill():
+    """Each layer of the run keeps its own cache: prefilling S tokens and decoding token S + 1
+    through the run gives the last row of prefilling S + 1 tokens."""
+    cfg = _stack_cfg(2, n_seqs=2, seq_pad=7, len_lo=7, len_hi=7)
+    ws = workloads.make_weights(cfg, 11)
+    inp = workloads.make_inputs(cfg, 11)
+    d = _odesc(cfg)
+    S, B, cap = cfg.seq_pad, cfg.n_seqs, 8
+    full = oracle.decoder_stack_prefill(d, ws, inp.x, inp.lens)
+    kc = np.zeros((2, B, cfg.n_kv_heads, cap, cfg.head_dim), np.float32)
+    vc = np.zeros_like(kc)
+    lens_s = np.full(B, S - 1, np.int32)
+    oracle.decoder_stack_prefill(d, ws, np.ascontiguousarray(inp.x[:, :S - 1]), lens_s, kc, vc)
+    y = oracle.decoder_stack_decode(d, ws, np.ascontiguousarray(inp.x[:, S - 1]), lens_s, kc, vc)
+    np.testing.assert_allclose(y, full[:, S - 1], rtol=2e-5, atol=2e-6)
+    # layer 1's cache holds keys of layer 0's OUTPUT, not of x: the two layers' caches differ
+    assert not np.allclose(kc[0], kc[1])
+
+
+def test_stack_split_equals_unsplit():
+    cfg = _stack_cfg(2, mode="decode", n_seqs=5, seq_pad=1, len_lo=0, len_hi=6)
+    ws = workloads.make_weights(cfg, 13)
+    inp = workloads.make_inputs(cfg, 13)
+    d = _odesc(cfg)
+    kc, vc = inp.k_cache.copy(), inp.v_cache.copy()
+    y = oracle.decoder_stack_decode(d, ws, inp.x, inp.lens, kc, vc)
+    parts = []
+    bounds = oracle.split_bounds(cfg.n_seqs, 3)
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        k2 = np.ascontiguousarray(inp.k_cache[:, lo:hi]).copy()
+        v2 = np.ascontiguousarray(inp.v_cache[:, lo:hi]).copy()
+        parts.append(oracle.decoder_stack_decode(d, ws, inp.x[lo:hi], inp.lens[lo:hi], k2, v2))
+        assert np.array_equal(k2, kc[:, lo:hi])
+    assert np.array_equal(np.concatenate(parts), y)

@@ -41,6 +41,7 @@ class Config:
     len_lo: int = 0          # prompt length (prefill) or cached length (decode), inclusive range
     len_hi: int = 0
     replicas: tuple = (1,)
+    n_layers: int = 1        # consecutive decoder layers in the module (a run)
 
     @property
     def cache_cap(self) -> int:
@@ -89,6 +90,12 @@ def make_weights(cfg: Config, seed: int = 0) -> dict:
     g = torch.Generator().manual_seed(seed)
     if cfg.kind == "linear":
         return {"w": _randn(g, (cfg.out_features, cfg.in_features), cfg.dtype, 0.02)}
+    if cfg.n_layers > 1:   # a run of layers: a list, drawn layer after layer from the one generator
+        return [_layer_weights(cfg, g) for _ in range(cfg.n_layers)]
+    return _layer_weights(cfg, g)
+
+
+def _layer_weights(cfg: Config, g) -> dict:
     H, d = cfg.hidden, cfg.head_dim
     QD, KD, I = cfg.n_q_heads * d, cfg.n_kv_heads * d, cfg.intermediate
     w = {}
@@ -119,13 +126,15 @@ def make_inputs(cfg: Config, seed: int = 0) -> Inputs:
         return Inputs(x=_randn(g, (B, cfg.seq_pad, H), cfg.dtype), lens=lens)
     x = _randn(g, (B, H), cfg.dtype)
     shape = (B, cfg.n_kv_heads, cfg.cache_cap, cfg.head_dim)
+    if cfg.n_layers > 1:
+        shape = (cfg.n_layers,) + shape    # one cache per layer of the run
     k = _randn(g, shape, cfg.dtype)
     v = _randn(g, shape, cfg.dtype)
     # slots at and beyond the cached length are not part of the input: zero them so that a
     # reader of a wrong slot is caught
     for b in range(B):
-        k[b, :, lens[b]:, :] = 0.0
-        v[b, :, lens[b]:, :] = 0.0
+        k[..., b, :, lens[b]:, :] = 0.0
+        v[..., b, :, lens[b]:, :] = 0.0
     return Inputs(x=x, lens=lens, k_cache=k, v_cache=v)
 
 

@@ -141,6 +141,31 @@ def bench_layer(args, name):
         sel = slice(b0, b0 + 1)
         parity = U.rel_err(y[sel], U.oracle_forward(cfg, 0, w, inp, seqs=sel), U.valid_mask(cfg, inp.lens[sel]))
 
+    # the same layer inside a run of consecutive layers (one module, scatter / gather only at the
+    # ends of the run): per-layer time with the layer boundaries fused
+    run = None
+    if args.layers > 1:
+        m.destroy()
+        m = None
+        rc = workloads.scaled(cfg, n_layers=args.layers)
+        rw = workloads.make_weights(rc, 0)
+        rm = U.make_module(rc, rw)
+        rdb = U.DeviceBatch(rm, rc, workloads.make_inputs(rc, 0))
+        del rw
+        for _ in range(W):
+            rm.forward_split(rdb.batch)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            rm.forward_split(rdb.batch)
+        torch.cuda.synchronize()
+        t_run = (time.perf_counter() - t0) / K
+        rm.destroy()
+        del rdb
+        run = {"layers": args.layers, "ms_per_step": round(t_run * 1e3, 4),
+               "ms_per_layer": round(t_run / args.layers * 1e3, 4),
+               "layer_tokens_per_s": round(n_tok / (t_run / args.layers), 1)}
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -156,7 +181,8 @@ def bench_layer(args, name):
             reps += 1
         cpu = {"value": round(ctok / (t_cpu / reps), 2), "unit": "tokens/s", "cores": oracle.omp_threads(),
                "kind": "oracle", "sample": f"{what} of {cfg.name}, mean of {reps} passes, fp64 arithmetic"}
-    m.destroy()
+    if m is not None:
+        m.destroy()
 
     if decode:
         roof = {"kernel": "attn_decode_mfma_kernel", "bound": "hbm",
@@ -206,6 +232,7 @@ def bench_layer(args, name):
                   "layer70b_hbm_frac": round(2 * big_bytes / t_clone_big / 1e9 / HBM_PEAK_GBPS, 4),
                   "note": "payload = bytes cloned / time; HBM traffic is 2 x payload (read + write)"},
         "kernels_k1": breakdown,
+        "run_of_layers_k1": run,
         "parity_rel_err_vs_oracle": float(f"{parity:.3e}"),
         "roofline": roof,
         "cpu_baseline": cpu,
@@ -264,6 +291,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=str, default="1,2,4")
     ap.add_argument("--workload", type=str, default="C2", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--layers", type=int, default=4,
+                    help="also time a run of this many consecutive layers as one module (0 or 1: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (replicas are HIP streams of one MI355X, no "

@@ -175,6 +175,14 @@ int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice);
  * has been launched outside a capture (the first launch of a variant sets a function attribute). */
 int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream);
 
+/* The same with uneven shares: slice j is the next counts[j] sequences (rows for a projection),
+ * j = 0 .. k-1 in batch order; counts (host, k entries, >= 0) must add up to full->n_seqs.
+ * Section 4.1, Eq. 1: a replica's share bs_ij follows its capacity, and the layer takes as long
+ * as its slowest replica.  Results are bit-identical to any other partition of the batch.
+ * Errors as ccs_module_forward_split, plus CCS_EINVAL for bad counts. */
+int ccs_module_forward_shares(ccs_module *m, const ccs_batch *full, const int32_t *counts,
+                              void *caller_stream);
+
 /* Clone replica `replica`'s packed weights into `dst_arena` (device, arena_bytes) on `stream`
  * (ordered after that replica's pending work); the source stays in use. */
 int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *stream);

@@ -26,7 +26,7 @@ _STATUS = {0: "CCS_OK", -1: "CCS_EINVAL", -2: "CCS_ESTATE", -3: "CCS_ENOMEM",
 EXPORTS = (
     "ccs_module_arena_bytes", "ccs_module_workspace_bytes", "ccs_module_create",
     "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
-    "ccs_module_forward_split", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
+    "ccs_module_forward_split", "ccs_module_forward_shares", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
     "ccs_module_arena", "ccs_module_profile", "ccs_module_profile_read", "ccs_module_sync", "ccs_module_destroy", "ccs_last_error", "ccs_version",
 )
 
@@ -88,6 +88,7 @@ def lib():
     L.ccs_module_replicas.argtypes = [vp]
     L.ccs_module_forward.argtypes = [vp, i32, ctypes.POINTER(ccs_batch)]
     L.ccs_module_forward_split.argtypes = [vp, ctypes.POINTER(ccs_batch), vp]
+    L.ccs_module_forward_shares.argtypes = [vp, ctypes.POINTER(ccs_batch), ctypes.POINTER(i32), vp]
     L.ccs_module_copy.argtypes = [vp, i32, vp, vp]
     L.ccs_module_migrate.argtypes = [vp, i32, vp, vp]
     L.ccs_cache_copy.argtypes = [vp, vp, sz, vp]
@@ -100,7 +101,7 @@ def lib():
     L.ccs_last_error.restype = ctypes.c_char_p
     L.ccs_version.restype = ctypes.c_char_p
     for name in ("ccs_module_create", "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
-                 "ccs_module_forward_split", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
+                 "ccs_module_forward_split", "ccs_module_forward_shares", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
                  "ccs_module_arena", "ccs_module_profile", "ccs_module_profile_read", "ccs_module_sync", "ccs_module_destroy"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -242,6 +243,14 @@ class Module:
     def forward_split(self, batch: ccs_batch, stream=None):
         s = self._torch.cuda.current_stream(self.device) if stream is None else stream
         _check(self.L.ccs_module_forward_split(self.handle, ctypes.byref(batch), s.cuda_stream))
+
+    def forward_shares(self, batch: ccs_batch, counts, stream=None):
+        """Uneven replicated forward: slice j is the next counts[j] sequences."""
+        s = self._torch.cuda.current_stream(self.device) if stream is None else stream
+        c = (ctypes.c_int32 * len(counts))(*[int(v) for v in counts])
+        if len(counts) != self.replicas():
+            raise ValueError("one count per replica")
+        _check(self.L.ccs_module_forward_shares(self.handle, ctypes.byref(batch), c, s.cuda_stream))
 
     # -- module_copy / module_migrate -----------------------------------------------------------
     def copy(self, replica: int, stream=None):

@@ -633,12 +633,9 @@ int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice)
     return forward_one(m, replica, slice, rows);
 }
 
-int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream)
+// Slice j = sequences [bounds[j], bounds[j + 1]) on replica j; slice 0 on the caller's stream.
+static int forward_bounds(ccs_module *m, const ccs_batch *full, const long long *bounds, hipStream_t cs)
 {
-    if (!m) return fail(CCS_EINVAL, "module is null");
-    int rc = check_batch(m, full);
-    if (rc != CCS_OK) return rc;
-    hipStream_t cs = (hipStream_t)caller_stream;
     const int k = m->k;
     const long long n = full->n_seqs;
     if (n == 0) return CCS_OK;
@@ -653,7 +650,7 @@ int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_
 
     if (k > 1) CCS_HIP(hipEventRecord(m->fork, cs));
     for (int j = 0; j < k; ++j) {
-        const long long lo = j * n / k, hi = (j + 1) * n / k;  // slice j = [floor(jn/k), floor((j+1)n/k))
+        const long long lo = bounds[j], hi = bounds[j + 1];
         if (hi == lo) continue;
         Replica &R = m->rep[j];
         ccs_batch s = *full;
@@ -669,7 +666,7 @@ int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_
         // slice 0 runs on the caller's stream itself (no events at k = 1); the others fork and join
         const bool inline_ = (j == 0) || R.stream == cs;
         if (!inline_) CCS_HIP(hipStreamWaitEvent(R.stream, m->fork, 0));
-        rc = forward_one(m, j, &s, full_rows, inline_, cs);
+        int rc = forward_one(m, j, &s, full_rows, inline_, cs);
         if (rc != CCS_OK) return rc;
         if (!inline_) {
             CCS_HIP(hipEventRecord(R.done, R.stream));
@@ -677,6 +674,34 @@ int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_
         }
     }
     return CCS_OK;
+}
+
+int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    int rc = check_batch(m, full);
+    if (rc != CCS_OK) return rc;
+    long long bounds[CCS_MAX_REPLICAS + 1];
+    const long long n = full->n_seqs;
+    for (int j = 0; j <= m->k; ++j) bounds[j] = j * n / m->k;  // slice j = [floor(jn/k), floor((j+1)n/k))
+    return forward_bounds(m, full, bounds, (hipStream_t)caller_stream);
+}
+
+int ccs_module_forward_shares(ccs_module *m, const ccs_batch *full, const int32_t *counts, void *caller_stream)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    if (!counts) return fail(CCS_EINVAL, "counts is null");
+    int rc = check_batch(m, full);
+    if (rc != CCS_OK) return rc;
+    long long bounds[CCS_MAX_REPLICAS + 1];
+    bounds[0] = 0;
+    for (int j = 0; j < m->k; ++j) {
+        if (counts[j] < 0) return fail(CCS_EINVAL, "counts[%d] = %d is negative", j, counts[j]);
+        bounds[j + 1] = bounds[j] + counts[j];
+    }
+    if (bounds[m->k] != full->n_seqs)
+        return fail(CCS_EINVAL, "counts add up to %lld, the batch has %d", bounds[m->k], full->n_seqs);
+    return forward_bounds(m, full, bounds, (hipStream_t)caller_stream);
 }
 
 int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *stream)

@@ -165,6 +165,34 @@ def test_run_of_layers_fills_and_extends_every_layers_cache():
         m.destroy()
 
 
+def test_uneven_shares_give_the_same_bits_as_any_other_partition():
+    """Eq. 1 of the speed-up model lets replica j of a layer take its own share bs_ij of the
+    batch: any partition of the sequences must reproduce the unsplit result bit for bit."""
+    cfg = workloads.scaled(C["C2"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
+                           n_seqs=15, len_lo=50, len_hi=300)
+    w = workloads.make_weights(cfg, 70)
+    inp = workloads.make_inputs(cfg, 70)
+    ref = U.oracle_forward(cfg, 70, w, inp)
+    m = U.make_module(cfg, w)
+    try:
+        db = U.DeviceBatch(m, cfg, inp)
+        m.forward_split(db.batch)
+        base = db.out().copy()
+        assert U.rel_err(base, ref) <= TOL["bf16"]
+        m.replicate(3)
+        for counts in ([10, 4, 1], [0, 15, 0], [1, 1, 13], [5, 5, 5]):
+            say(f"[case] shares {counts}")
+            db2 = U.DeviceBatch(m, cfg, inp)
+            m.forward_shares(db2.batch, counts)
+            assert np.array_equal(db2.out(), base), f"shares {counts} differ from the unsplit run"
+        for bad in ([10, 4, 2], [16, -1, 0]):
+            with pytest.raises(B.CcsError) as e:
+                m.forward_shares(db.batch, bad)
+            assert e.value.status == B.CCS_EINVAL
+    finally:
+        m.destroy()
+
+
 # ---------------------------------------------------------------- full-size configs
 def test_c2_llama7b_decode_full():
     run_case(C["C2"], [1, 2, 4])

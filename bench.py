@@ -1,17 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the module-replica hot path on ONE MI355X.
 
-Default workload (the one BASELINE's metric is quoted on): a step = one replicated forward
+Default workload (the configuration the headline metric is quoted on): a step = one replicated forward
 (split -> k replica forwards on their streams -> join) of the Llama-2-7B-shaped decoder layer in
-a decode step: batch 32, 1024 cached positions per sequence (BASELINE configs[1]), bf16, seeded
+a decode step: batch 32, 1024 cached positions per sequence (benchmark configuration 1), bf16, seeded
 synthetic tensors resident in HBM before timing starts.  `value` is tokens/s at k = 1; k = 2 and
 k = 4 (same total batch) and the replica-clone rate are reported beside it.  The `roofline`
 object prices the dominant kernel against its roofline (decode attention vs HBM; for the prefill
 workload the gate/up projection vs the bf16 MFMA peak); `cpu_baseline` is the CPU oracle timed
 on this machine's host cores.
 
-`--workload C3|C4|C5` runs the other BASELINE configs the same way (13B prefill, 70B GQA decode,
-bursty down-projection); they are reported in the design doc, not by the driver.
+`--workload C3|C4|C5` runs the other benchmark configurations the same way (13B prefill, 70B GQA
+decode, bursty down-projection).
 
 Prints ONE JSON line.
 """

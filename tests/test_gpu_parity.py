@@ -52,7 +52,7 @@ def run_case(cfg, ks, seed=0, seqs=None):
     return ys
 
 
-# ---------------------------------------------------------------- BASELINE configs[0]: tiny fp32
+# ---------------------------------------------------------------- benchmark configuration 0: tiny fp32
 def test_c1_tiny_fp32_prefill():
     run_case(C["C1"], [1, 2])
 

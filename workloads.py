@@ -51,7 +51,7 @@ class Config:
 
 
 CONFIGS = {
-    # BASELINE configs[0..4]
+    # the five benchmark configurations
     "C1": Config("C1-tiny-f32-prefill", "decoder_layer", "f32", 256, 4, 4, 64, 688,
                  mode="prefill", n_seqs=4, seq_pad=32, len_lo=32, len_hi=32, replicas=(1, 2)),
     "C2": Config("C2-llama2-7b-decode", "decoder_layer", "bf16", 4096, 32, 32, 128, 11008,
@@ -138,7 +138,7 @@ def make_inputs(cfg: Config, seed: int = 0) -> Inputs:
     return Inputs(x=x, lens=lens, k_cache=k, v_cache=v)
 
 
-# ---- bursty single-projection load (BASELINE configs[4]) ------------------------------------
+# ---- bursty single-projection load (benchmark configuration 4) ------------------------------------
 def bursty_token_counts(seed: int = 0, n_batches: int = 200, lam: float = 64.0):
     """Per batch: n = max(1, Poisson(lam)) * f with f uniform on {1, 4, 16}, i.i.d."""
     g = torch.Generator().manual_seed(seed + 2)

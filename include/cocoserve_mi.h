@@ -56,12 +56,17 @@ typedef enum ccs_status {
     CCS_EHIP = -5          /* a HIP runtime call failed; message holds the HIP error string */
 } ccs_status;
 
-typedef enum ccs_kind { CCS_DECODER_LAYER = 0, CCS_LINEAR = 1 } ccs_kind;
+/* Module kinds (Section 3.3, Table 1 analyses the decoder layer, its self-attention and FFN parts and the
+ * single projections as modules of their own).  The two halves of a layer carry their norm and
+ * their residual, so that an attention block followed by an FFN block IS the layer:
+ *   CCS_ATTN_BLOCK: y = x + Attention(RMSNorm(x; g1)) Wo^T   (uses wq, wk, wv, wo, g1; PREFILL / DECODE)
+ *   CCS_FFN_BLOCK:  y = x + (silu(h Wg^T) * (h Wu^T)) Wd^T, h = RMSNorm(x; g2)   (wgate, wup, wdown, g2; ROWS) */
+typedef enum ccs_kind { CCS_DECODER_LAYER = 0, CCS_LINEAR = 1, CCS_ATTN_BLOCK = 2, CCS_FFN_BLOCK = 3 } ccs_kind;
 typedef enum ccs_dtype { CCS_F32 = 0, CCS_BF16 = 1 } ccs_dtype;
 typedef enum ccs_mode {
     CCS_PREFILL = 0, /* whole prompts, causal, right padding masked (Section 2.1 "prefill") */
     CCS_DECODE = 1,  /* one new token per sequence against the KV cache (Section 2.1 "decode") */
-    CCS_ROWS = 2     /* CCS_LINEAR modules: independent token rows */
+    CCS_ROWS = 2     /* CCS_LINEAR and CCS_FFN_BLOCK modules: independent token rows */
 } ccs_mode;
 
 enum { CCS_MAX_REPLICAS = 16 };
@@ -103,8 +108,8 @@ typedef struct ccs_weights {
  *            new token is position lens[b]: its key/value are stored at slot lens[b] and the
  *            query attends over slots 0..lens[b] (cache_cap >= lens[b] + 1).  The caches are
  *            required.  lens itself is not advanced by the library.
- *   ROWS:    x is [n_seqs, in_features], y is [n_seqs, out_features]; seq_pad, lens and the
- *            caches are ignored.
+ *   ROWS:    x is [n_seqs, in_features], y is [n_seqs, out_features] (an FFN block: both
+ *            [n_seqs, hidden]); seq_pad, lens and the caches are ignored.
  * A run of layers: every layer has caches of this shape; k_cache / v_cache point at the first
  * layer's and layer l's start cache_layer_stride BYTES further each (at least the bytes of one
  * layer's cache for the WHOLE batch the slice belongs to; ignored for a single layer).

@@ -136,9 +136,10 @@ def attend(q, keys, vals):
 
 
 # ---- whole modules --------------------------------------------------------------------------
-def decoder_layer_prefill(desc: LayerDesc, w: dict, x, lens, k_cache=None, v_cache=None):
+def decoder_layer_prefill(desc: LayerDesc, w: dict, x, lens, k_cache=None, v_cache=None, attention_only=False):
     """x [B, S, H]; lens [B]; returns y [B, S, H] (padded rows 0).  Optional caches
-    [B, n_kv, cap, d] are filled for positions < lens[b]."""
+    [B, n_kv, cap, d] are filled for positions < lens[b].  attention_only: stop after the
+    attention block (y = x + attention output projection)."""
     x = _f32(x)
     B, S, H = x.shape
     lens = np.ascontiguousarray(lens, dtype=np.int32)
@@ -152,17 +153,17 @@ def decoder_layer_prefill(desc: LayerDesc, w: dict, x, lens, k_cache=None, v_cac
         cap = k_cache.shape[2]
         kp, vp = _p(k_cache), _p(v_cache)
     d = desc.c()
-    rc = lib().orc_decoder_layer_prefill(ctypes.byref(d), ctypes.byref(cw), _p(x), _p(lens),
-                                         ctypes.c_int(B), ctypes.c_int(S), _p(y), kp, vp,
-                                         ctypes.c_int(cap))
+    fn = lib().orc_attention_block_prefill if attention_only else lib().orc_decoder_layer_prefill
+    rc = fn(ctypes.byref(d), ctypes.byref(cw), _p(x), _p(lens), ctypes.c_int(B), ctypes.c_int(S), _p(y), kp, vp,
+            ctypes.c_int(cap))
     if rc != 0:
         raise ValueError("oracle rejected the prefill arguments")
     return y
 
 
-def decoder_layer_decode(desc: LayerDesc, w: dict, x, lens, k_cache, v_cache):
+def decoder_layer_decode(desc: LayerDesc, w: dict, x, lens, k_cache, v_cache, attention_only=False):
     """x [B, H]; lens [B] cached lengths; caches [B, n_kv, cap, d] fp32 updated IN PLACE at
-    slot lens[b]; returns y [B, H]."""
+    slot lens[b]; returns y [B, H].  attention_only: stop after the attention block."""
     x = _f32(x)
     B, H = x.shape
     lens = np.ascontiguousarray(lens, dtype=np.int32)
@@ -172,11 +173,22 @@ def decoder_layer_decode(desc: LayerDesc, w: dict, x, lens, k_cache, v_cache):
     cw, keep = _weights(desc, w)
     y = np.empty_like(x)
     d = desc.c()
-    rc = lib().orc_decoder_layer_decode(ctypes.byref(d), ctypes.byref(cw), _p(x), _p(lens),
-                                        ctypes.c_int(B), _p(k_cache), _p(v_cache),
-                                        ctypes.c_int(cap), _p(y))
+    fn = lib().orc_attention_block_decode if attention_only else lib().orc_decoder_layer_decode
+    rc = fn(ctypes.byref(d), ctypes.byref(cw), _p(x), _p(lens), ctypes.c_int(B), _p(k_cache), _p(v_cache),
+            ctypes.c_int(cap), _p(y))
     if rc != 0:
         raise ValueError("oracle rejected the decode arguments")
+    return y
+
+
+def ffn_block(desc: LayerDesc, w: dict, x):
+    """x [T, H] independent rows: y = x + (silu(h Wg^T) * (h Wu^T)) Wd^T with h = RMSNorm(x; g2)."""
+    x = _f32(x)
+    T, H = x.shape
+    cw, keep = _weights(desc, w)
+    y = np.empty_like(x)
+    d = desc.c()
+    lib().orc_ffn_block(ctypes.byref(d), ctypes.byref(cw), _p(x), ctypes.c_int64(T), _p(y))
     return y
 
 

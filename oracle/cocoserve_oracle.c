@@ -143,26 +143,61 @@ void orc_attend_f64(const double *q, const double *keys, const double *vals, int
 
 static double silu(double z) { return z / (1.0 + exp(-z)); }
 
-/* Steps after attention, shared by prefill and decode because the layer is the
- * same in both phases: x1 = x + a Wo^T; h2 = RMSNorm(x1); u = silu(h2 Wg^T) * (h2 Wu^T);
- * y = x1 + u Wd^T.  rows: T. */
-static void post_attention(const orc_layer_desc *D, const orc_layer_weights *w, const double *x,
-                           const double *a, int64_t T, double *y)
+/* The layer's two halves (Section 3.3, Table 1 treats self-attention and FFN as modules of
+ * their own).  Each half carries its norm and its residual, so the layer is the attention
+ * block followed by the FFN block.  rows: T. */
+/* x1 = x + a Wo^T, a = the attention output of RMSNorm(x; g1) */
+static void attention_output(const orc_layer_desc *D, const orc_layer_weights *w, const double *x,
+                             const double *a, int64_t T, double *x1)
 {
-    int H = D->hidden, I = D->intermediate, QD = D->n_q_heads * D->head_dim;
-    double *x1 = (double *)malloc(sizeof(double) * (size_t)(T * H));
+    int H = D->hidden, QD = D->n_q_heads * D->head_dim;
+    orc_linear_f64(a, w->wo, T, QD, H, x1);
+    for (int64_t i = 0; i < T * H; ++i) x1[i] += x[i];
+}
+
+/* y = x1 + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T, h2 = RMSNorm(x1; g2) */
+static void ffn_block(const orc_layer_desc *D, const orc_layer_weights *w, const double *x1, int64_t T,
+                      double *y)
+{
+    int H = D->hidden, I = D->intermediate;
     double *h2 = (double *)malloc(sizeof(double) * (size_t)(T * H));
     double *gt = (double *)malloc(sizeof(double) * (size_t)(T * I));
     double *up = (double *)malloc(sizeof(double) * (size_t)(T * I));
-    orc_linear_f64(a, w->wo, T, QD, H, x1);
-    for (int64_t i = 0; i < T * H; ++i) x1[i] += x[i];
     orc_rmsnorm_f64(x1, w->g2, D->rms_eps, T, H, h2);
     orc_linear_f64(h2, w->wgate, T, H, I, gt);
     orc_linear_f64(h2, w->wup, T, H, I, up);
     for (int64_t i = 0; i < T * I; ++i) gt[i] = silu(gt[i]) * up[i];
     orc_linear_f64(gt, w->wdown, T, I, H, y);
     for (int64_t i = 0; i < T * H; ++i) y[i] += x1[i];
-    free(x1); free(h2); free(gt); free(up);
+    free(h2); free(gt); free(up);
+}
+
+/* Steps after attention, shared by prefill and decode because the layer is the
+ * same in both phases.  parts: 1 = stop after the attention block (y = x1), 3 = whole layer. */
+static void post_attention(const orc_layer_desc *D, const orc_layer_weights *w, const double *x,
+                           const double *a, int64_t T, double *y, int parts)
+{
+    int H = D->hidden;
+    if (!(parts & 2)) {
+        attention_output(D, w, x, a, T, y);
+        return;
+    }
+    double *x1 = (double *)malloc(sizeof(double) * (size_t)(T * H));
+    attention_output(D, w, x, a, T, x1);
+    ffn_block(D, w, x1, T, y);
+    free(x1);
+}
+
+/* FFN block on independent token rows: x, y [T, H] fp32 */
+void orc_ffn_block(const orc_layer_desc *D, const orc_layer_weights *w, const float *x, int64_t T, float *y)
+{
+    int H = D->hidden;
+    double *xd = (double *)malloc(sizeof(double) * (size_t)(T * H));
+    double *yd = (double *)malloc(sizeof(double) * (size_t)(T * H));
+    for (int64_t i = 0; i < T * H; ++i) xd[i] = (double)x[i];
+    ffn_block(D, w, xd, T, yd);
+    for (int64_t i = 0; i < T * H; ++i) y[i] = (float)yd[i];
+    free(xd); free(yd);
 }
 
 /* ---- decoder layer, prefill phase (Section 2.1) -------------------------- */
@@ -171,9 +206,9 @@ static void post_attention(const orc_layer_desc *D, const orc_layer_weights *w, 
  * keys j <= t (causal), all of which are < lens[b] for a valid t.
  * k_cache/v_cache (optional, [B, n_kv, cap, d] fp32): receive the rotated keys and the
  * values of positions 0..lens[b]-1, which is what a later decode step reads. */
-int orc_decoder_layer_prefill(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
-                              const int32_t *lens, int B, int S, float *y, float *k_cache,
-                              float *v_cache, int cap)
+static int layer_prefill(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
+                         const int32_t *lens, int B, int S, float *y, float *k_cache,
+                         float *v_cache, int cap, int parts)
 {
     int H = D->hidden, d = D->head_dim, nq = D->n_q_heads, nkv = D->n_kv_heads;
     if (nkv <= 0 || nq % nkv || (d & 1)) return -1;
@@ -216,11 +251,26 @@ int orc_decoder_layer_prefill(const orc_layer_desc *D, const orc_layer_weights *
                 attend_one(q + (int64_t)t * QD + hh * d, k + kvh * d, v + kvh * d, t + 1, d, KD,
                            a + (int64_t)t * QD + hh * d, NULL);
             }
-        post_attention(D, w, xd, a, len, yd);
+        post_attention(D, w, xd, a, len, yd, parts);
         for (int64_t i = 0; i < (int64_t)len * H; ++i) yb[i] = (float)yd[i];
         free(xd); free(h); free(q); free(k); free(v); free(a); free(yd);
     }
     return 0;
+}
+
+int orc_decoder_layer_prefill(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
+                              const int32_t *lens, int B, int S, float *y, float *k_cache,
+                              float *v_cache, int cap)
+{
+    return layer_prefill(D, w, x, lens, B, S, y, k_cache, v_cache, cap, 3);
+}
+
+/* the attention block alone: y = x + Attention(RMSNorm(x; g1)) Wo^T */
+int orc_attention_block_prefill(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
+                                const int32_t *lens, int B, int S, float *y, float *k_cache,
+                                float *v_cache, int cap)
+{
+    return layer_prefill(D, w, x, lens, B, S, y, k_cache, v_cache, cap, 1);
 }
 
 /* ---- decoder layer, decode phase (Section 2.1) --------------------------- */
@@ -228,9 +278,9 @@ int orc_decoder_layer_prefill(const orc_layer_desc *D, const orc_layer_weights *
  * (post-rotation keys).  The new token sits at position L_b: its rotated key and its value
  * are stored at cache slot L_b and the query attends over slots 0..L_b (L_b + 1 keys).
  * Caches [B, n_kv, cap, d] fp32 are updated in place; cap >= L_b + 1. */
-int orc_decoder_layer_decode(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
-                             const int32_t *lens, int B, float *k_cache, float *v_cache, int cap,
-                             float *y)
+static int layer_decode(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
+                        const int32_t *lens, int B, float *k_cache, float *v_cache, int cap,
+                        float *y, int parts)
 {
     int H = D->hidden, d = D->head_dim, nq = D->n_q_heads, nkv = D->n_kv_heads;
     if (nkv <= 0 || nq % nkv || (d & 1)) return -1;
@@ -274,10 +324,24 @@ int orc_decoder_layer_decode(const orc_layer_desc *D, const orc_layer_weights *w
             }
             free(kk); free(vv);
         }
-    post_attention(D, w, xd, a, B, yd);
+    post_attention(D, w, xd, a, B, yd, parts);
     for (int64_t i = 0; i < (int64_t)B * H; ++i) y[i] = (float)yd[i];
     free(xd); free(h); free(q); free(k); free(v); free(a); free(yd);
     return 0;
+}
+
+int orc_decoder_layer_decode(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
+                             const int32_t *lens, int B, float *k_cache, float *v_cache, int cap,
+                             float *y)
+{
+    return layer_decode(D, w, x, lens, B, k_cache, v_cache, cap, y, 3);
+}
+
+int orc_attention_block_decode(const orc_layer_desc *D, const orc_layer_weights *w, const float *x,
+                               const int32_t *lens, int B, float *k_cache, float *v_cache, int cap,
+                               float *y)
+{
+    return layer_decode(D, w, x, lens, B, k_cache, v_cache, cap, y, 1);
 }
 
 /* ---- single projection module: y = x W^T (Section 3.1 "Migration": projections are

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libcocoserve_mi.so"
 
 CCS_OK, CCS_EINVAL, CCS_ESTATE, CCS_ENOMEM, CCS_EUNSUPPORTED, CCS_EHIP = 0, -1, -2, -3, -4, -5
-CCS_DECODER_LAYER, CCS_LINEAR = 0, 1
+CCS_DECODER_LAYER, CCS_LINEAR, CCS_ATTN_BLOCK, CCS_FFN_BLOCK = 0, 1, 2, 3
 CCS_F32, CCS_BF16 = 0, 1
 CCS_PREFILL, CCS_DECODE, CCS_ROWS = 0, 1, 2
 CCS_MAX_REPLICAS = 16

@@ -41,6 +41,12 @@ struct Dims {
     size_t esz;
 };
 
+// a decoder layer and its two halves (Section 3.3, Table 1 lists self-attention and FFN as modules of
+// their own) share shapes, kernels and plans
+inline bool is_layerlike(int kind) { return kind == CCS_DECODER_LAYER || kind == CCS_ATTN_BLOCK || kind == CCS_FFN_BLOCK; }
+inline bool has_attn(int kind) { return kind == CCS_DECODER_LAYER || kind == CCS_ATTN_BLOCK; }
+inline bool has_ffn(int kind) { return kind == CCS_DECODER_LAYER || kind == CCS_FFN_BLOCK; }
+
 struct ArenaPlan {
     size_t qkv, o, gu, dn, g1, g2, rope, w;  // offsets inside one layer
     size_t layer;                            // bytes of one layer (256-byte multiple)
@@ -59,7 +65,8 @@ int check_desc(const ccs_module_desc *D, Dims *out)
     d.esz = D->dtype == CCS_BF16 ? 2 : 4;
     d.L = 1;
     if (D->n_layers < 0 || D->n_layers > CCS_MAX_LAYERS) return fail(CCS_EINVAL, "n_layers must be in [0, %d]", (int)CCS_MAX_LAYERS);
-    if (D->kind == CCS_DECODER_LAYER) {
+    if (is_layerlike(D->kind)) {
+        if (D->kind != CCS_DECODER_LAYER && D->n_layers > 1) return fail(CCS_EINVAL, "n_layers applies to whole decoder layers only");
         d.L = D->n_layers > 1 ? D->n_layers : 1;
         if (D->hidden <= 0 || D->n_q_heads <= 0 || D->n_kv_heads <= 0 || D->head_dim <= 0 || D->intermediate <= 0)
             return fail(CCS_EINVAL, "decoder-layer dimensions must be positive");
@@ -99,13 +106,17 @@ ArenaPlan arena_plan(const ccs_module_desc *D, const Dims &d)
     if (D->kind == CCS_LINEAR) {
         p.w = take(wbytes(d.out_f, d.in_f));
     } else {
-        p.qkv = take(wbytes(d.W3, d.H));
-        p.o = take(wbytes(d.H, d.QD));
-        p.gu = take(wbytes(2 * d.I, d.H));
-        p.dn = take(wbytes(d.H, d.I));
-        p.g1 = take((size_t)d.H * d.esz);
-        p.g2 = take((size_t)d.H * d.esz);
-        p.rope = take((size_t)(d.d / 2) * 2 * sizeof(float));  // inverse-frequency table (fp32 head + tail)
+        if (has_attn(D->kind)) {
+            p.qkv = take(wbytes(d.W3, d.H));
+            p.o = take(wbytes(d.H, d.QD));
+            p.g1 = take((size_t)d.H * d.esz);
+            p.rope = take((size_t)(d.d / 2) * 2 * sizeof(float));  // inverse-frequency table (fp32 head + tail)
+        }
+        if (has_ffn(D->kind)) {
+            p.gu = take(wbytes(2 * d.I, d.H));
+            p.dn = take(wbytes(d.H, d.I));
+            p.g2 = take((size_t)d.H * d.esz);
+        }
     }
     p.layer = off;
     p.total = off * (size_t)d.L;
@@ -268,13 +279,13 @@ int check_batch(const ccs_module *m, const ccs_batch *b)
     if (!b) return fail(CCS_EINVAL, "batch is null");
     if (b->n_seqs < 0) return fail(CCS_EINVAL, "n_seqs < 0");
     const Dims &d = m->dims;
-    if (m->desc.kind == CCS_LINEAR) {
-        if (b->mode != CCS_ROWS) return fail(CCS_EINVAL, "a linear module takes mode CCS_ROWS");
+    if (m->desc.kind == CCS_LINEAR || m->desc.kind == CCS_FFN_BLOCK) {
+        if (b->mode != CCS_ROWS) return fail(CCS_EINVAL, "a projection or FFN block takes mode CCS_ROWS");
         if (b->n_seqs > 0 && (!b->x || !b->y)) return fail(CCS_EINVAL, "x / y is null");
         return CCS_OK;
     }
     if (b->mode != CCS_PREFILL && b->mode != CCS_DECODE)
-        return fail(CCS_EINVAL, "a decoder layer takes mode CCS_PREFILL or CCS_DECODE");
+        return fail(CCS_EINVAL, "a decoder layer or attention block takes mode CCS_PREFILL or CCS_DECODE");
     if (b->n_seqs == 0) return CCS_OK;
     if (!b->x || !b->y) return fail(CCS_EINVAL, "x / y is null");
     if (!b->lens_host || !b->lens_dev) return fail(CCS_EINVAL, "lens_host / lens_dev is null");
@@ -341,10 +352,12 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         return CCS_OK;
     }
 
+    const bool attn = has_attn(D.kind), ffn = has_ffn(D.kind);
     const bool decode = b->mode == CCS_DECODE;
-    const int seq_pad = decode ? 1 : b->seq_pad;
+    const bool rows_mode = b->mode == CCS_ROWS;   // FFN block: independent token rows
+    const int seq_pad = (decode || rows_mode) ? 1 : b->seq_pad;
     const int T = b->n_seqs * seq_pad;
-    WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, decode ? 0 : seq_pad, (long)variant_rows);
+    WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, (decode || rows_mode) ? 0 : seq_pad, (long)variant_rows);
     if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
     const bool row_norm = skinny && d.H <= 8192 && d.H % 4 == 0;  // few rows: one workgroup per row
@@ -361,12 +374,18 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         void *vc = b->v_cache ? (char *)b->v_cache + (size_t)l * (size_t)b->cache_layer_stride : nullptr;
         const bool last = l == d.L - 1;
 
+        // h = RMSNorm(x_in) with the gains of the block that comes first
+        const size_t g_first = attn ? m->ap.g1 : m->ap.g2;
         if (!h_ready) {
             if (row_norm)
-                CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm_rows(x_in, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+                CCS_STAGE(attn ? CCS_ST_RMSNORM1 : CCS_ST_RMSNORM2, launch_rmsnorm_rows(x_in, A + g_first, ws + p.h, T, d.H, D.rms_eps, st));
             else
-                CCS_STAGE(CCS_ST_RMSNORM1, launch_rmsnorm(dt, x_in, A + m->ap.g1, ws + p.h, T, d.H, D.rms_eps, st));
+                CCS_STAGE(attn ? CCS_ST_RMSNORM1 : CCS_ST_RMSNORM2, launch_rmsnorm(dt, x_in, A + g_first, ws + p.h, T, d.H, D.rms_eps, st));
         }
+        // x1: the residual stream between the two blocks (the block's input when attention is absent,
+        // the module's output when the FFN is absent)
+        const void *x1_in = attn ? (ffn ? (const void *)(ws + p.x1) : (const void *)x_out) : x_in;
+        void *x1_out = ffn ? (void *)(ws + p.x1) : x_out;
         h_ready = false;
         const void *tab = A + m->ap.rope;
         if (bf) {
@@ -382,6 +401,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st)); \
         }                                                                                                     \
     } while (0)
+            if (attn) {
             if (skinny && decode) {
                 // weight-streaming Q/K/V projection; its reduction also rotates and appends to the cache
                 CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_skinny_main(A + m->ap.qkv, ws + p.h, scratch, T, d.W3, d.H, st));
@@ -399,14 +419,16 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             } else {
                 CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, b->lens_dev, st));
             }
-            if (row_norm) {
+            if (row_norm && ffn) {
                 // weight-streaming O projection; its reduction adds the residual and applies the second norm
                 CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_skinny_main(A + m->ap.o, ws + p.a, scratch, T, d.H, d.QD, st));
                 CCS_STAGE(CCS_ST_GEMM_O_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.QD), T, d.H, x_in, A + m->ap.g2, D.rms_eps, ws + p.x1, ws + p.h, st));
             } else {
-                CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, x_in, ws + p.x1, d.H, d.QD);
-                CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+                CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, x_in, x1_out, d.H, d.QD);
+                if (ffn) CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
             }
+            }
+            if (ffn) {
             CCS_GEMM(CCS_ST_GEMM_GU, m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H);
             if (row_norm && !last) {
                 // inside a run: the down projection's reduction adds the residual and already applies
@@ -415,19 +437,24 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
                 CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.I), T, d.H, ws + p.x1, A + m->ap.layer + m->ap.g1, D.rms_eps, x_out, ws + p.h, st));
                 h_ready = true;
             } else {
-                CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, ws + p.x1, x_out, d.H, d.I);
+                CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, x1_in, x_out, d.H, d.I);
+            }
             }
 #undef CCS_GEMM
         } else {
             auto W = [&](size_t off) { return (const float *)(A + off); };
-            CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
-            CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
-            CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
-            CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)x_in, (float *)(ws + p.x1), T, d.H, d.QD, st));
-            CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
-            CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.gu), nullptr, (float *)(ws + p.gu), T, 2 * d.I, d.H, st));
-            CCS_STAGE(CCS_ST_GEMM_GU_REDUCE, launch_swiglu_f32((const float *)(ws + p.gu), (float *)(ws + p.u), T, d.I, st));
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)(ws + p.u), W(m->ap.dn), (const float *)(ws + p.x1), (float *)x_out, T, d.H, d.I, st));
+            if (attn) {
+                CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
+                CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
+                CCS_STAGE(CCS_ST_ATTN, launch_attn_generic(dt, ws + p.qkv, ws + p.a, T, d.nq, d.nkv, d.d, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
+                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_f32((const float *)(ws + p.a), W(m->ap.o), (const float *)x_in, (float *)x1_out, T, d.H, d.QD, st));
+                if (ffn) CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
+            }
+            if (ffn) {
+                CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.gu), nullptr, (float *)(ws + p.gu), T, 2 * d.I, d.H, st));
+                CCS_STAGE(CCS_ST_GEMM_GU_REDUCE, launch_swiglu_f32((const float *)(ws + p.gu), (float *)(ws + p.u), T, d.I, st));
+                CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)(ws + p.u), W(m->ap.dn), (const float *)x1_in, (float *)x_out, T, d.H, d.I, st));
+            }
         }
     }
     return CCS_OK;
@@ -458,7 +485,7 @@ size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
     }
     const size_t rows = (size_t)max_seqs * max_seq_pad;
     const bool skinny = rows <= (size_t)ccs::kSkinnyMaxRows;
-    const bool layer = desc->kind == CCS_DECODER_LAYER;
+    const bool layer = has_attn(desc->kind);
     // cover every plan a batch within these limits can take: prefill (max_seq_pad rows per
     // sequence), decode (one row per sequence, when a cache size is given), either GEMM variant
     size_t need = ws_plan(desc, d, rows, max_seqs, max_cache_cap, skinny, false, layer ? max_seq_pad : 0).total;
@@ -493,9 +520,12 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
     if (desc->kind == CCS_LINEAR) {
         if (!w->w) return fail(CCS_EINVAL, "weights.w is null");
     } else {
-        for (int l = 0; l < d.L; ++l)
-            if (!w[l].wq || !w[l].wk || !w[l].wv || !w[l].wo || !w[l].wgate || !w[l].wup || !w[l].wdown || !w[l].g1 || !w[l].g2)
-                return fail(CCS_EINVAL, "a weight pointer of layer %d is null", l);
+        for (int l = 0; l < d.L; ++l) {
+            if (has_attn(desc->kind) && (!w[l].wq || !w[l].wk || !w[l].wv || !w[l].wo || !w[l].g1))
+                return fail(CCS_EINVAL, "an attention weight pointer of layer %d is null", l);
+            if (has_ffn(desc->kind) && (!w[l].wgate || !w[l].wup || !w[l].wdown || !w[l].g2))
+                return fail(CCS_EINVAL, "an FFN weight pointer of layer %d is null", l);
+        }
     }
     int ndev = 0;
     CCS_HIP(hipGetDeviceCount(&ndev));
@@ -526,32 +556,40 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
             if (bf) pack(m->ap.w, wl->w, d.out_f, d.in_f, 1, 0);
             else rm_copy(m->ap.w, wl->w, (size_t)d.out_f * d.in_f * 4);
         } else if (bf) {
-            zero_if_padded(m->ap.qkv, d.W3, d.H);
-            zero_if_padded(m->ap.o, d.H, d.QD);
-            zero_if_padded(m->ap.gu, 2 * d.I, d.H);
-            zero_if_padded(m->ap.dn, d.H, d.I);
-            pack(m->ap.qkv, wl->wq, d.QD, d.H, 1, 0);
-            pack(m->ap.qkv, wl->wk, d.KD, d.H, 1, d.QD / 16);
-            pack(m->ap.qkv, wl->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16);
-            pack(m->ap.o, wl->wo, d.H, d.QD, 1, 0);
-            pack(m->ap.gu, wl->wgate, d.I, d.H, 2, 0);  // gate blocks even, up blocks odd
-            pack(m->ap.gu, wl->wup, d.I, d.H, 2, 1);
-            pack(m->ap.dn, wl->wdown, d.H, d.I, 1, 0);
-            rm_copy(m->ap.g1, wl->g1, (size_t)d.H * 2);
-            rm_copy(m->ap.g2, wl->g2, (size_t)d.H * 2);
+            if (has_attn(desc->kind)) {
+                zero_if_padded(m->ap.qkv, d.W3, d.H);
+                zero_if_padded(m->ap.o, d.H, d.QD);
+                pack(m->ap.qkv, wl->wq, d.QD, d.H, 1, 0);
+                pack(m->ap.qkv, wl->wk, d.KD, d.H, 1, d.QD / 16);
+                pack(m->ap.qkv, wl->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16);
+                pack(m->ap.o, wl->wo, d.H, d.QD, 1, 0);
+                rm_copy(m->ap.g1, wl->g1, (size_t)d.H * 2);
+            }
+            if (has_ffn(desc->kind)) {
+                zero_if_padded(m->ap.gu, 2 * d.I, d.H);
+                zero_if_padded(m->ap.dn, d.H, d.I);
+                pack(m->ap.gu, wl->wgate, d.I, d.H, 2, 0);  // gate blocks even, up blocks odd
+                pack(m->ap.gu, wl->wup, d.I, d.H, 2, 1);
+                pack(m->ap.dn, wl->wdown, d.H, d.I, 1, 0);
+                rm_copy(m->ap.g2, wl->g2, (size_t)d.H * 2);
+            }
         } else {
             const size_t rowb = (size_t)d.H * 4;
-            rm_copy(m->ap.qkv, wl->wq, d.QD * rowb);
-            rm_copy(m->ap.qkv + d.QD * rowb, wl->wk, d.KD * rowb);
-            rm_copy(m->ap.qkv + (d.QD + d.KD) * rowb, wl->wv, d.KD * rowb);
-            rm_copy(m->ap.o, wl->wo, (size_t)d.H * d.QD * 4);
-            rm_copy(m->ap.gu, wl->wgate, d.I * rowb);
-            rm_copy(m->ap.gu + d.I * rowb, wl->wup, d.I * rowb);
-            rm_copy(m->ap.dn, wl->wdown, (size_t)d.H * d.I * 4);
-            rm_copy(m->ap.g1, wl->g1, rowb);
-            rm_copy(m->ap.g2, wl->g2, rowb);
+            if (has_attn(desc->kind)) {
+                rm_copy(m->ap.qkv, wl->wq, d.QD * rowb);
+                rm_copy(m->ap.qkv + d.QD * rowb, wl->wk, d.KD * rowb);
+                rm_copy(m->ap.qkv + (d.QD + d.KD) * rowb, wl->wv, d.KD * rowb);
+                rm_copy(m->ap.o, wl->wo, (size_t)d.H * d.QD * 4);
+                rm_copy(m->ap.g1, wl->g1, rowb);
+            }
+            if (has_ffn(desc->kind)) {
+                rm_copy(m->ap.gu, wl->wgate, d.I * rowb);
+                rm_copy(m->ap.gu + d.I * rowb, wl->wup, d.I * rowb);
+                rm_copy(m->ap.dn, wl->wdown, (size_t)d.H * d.I * 4);
+                rm_copy(m->ap.g2, wl->g2, rowb);
+            }
         }
-        if (e == hipSuccess && desc->kind == CCS_DECODER_LAYER) e = launch_rope_table(A + m->ap.rope, d.d, desc->rope_base, st);
+        if (e == hipSuccess && has_attn(desc->kind)) e = launch_rope_table(A + m->ap.rope, d.d, desc->rope_base, st);
     }
     if (e != hipSuccess) {
         delete m;

@@ -433,3 +433,61 @@ def test_stack_split_equals_unsplit():
         parts.append(oracle.decoder_stack_decode(d, ws, inp.x[lo:hi], inp.lens[lo:hi], k2, v2))
         assert np.array_equal(k2, kc[:, lo:hi])
     assert np.array_equal(np.concatenate(parts), y)
+
+
+# ---------------------------------------------------------------- the layer's two halves
+def test_attention_block_then_ffn_block_is_the_layer():
+    """Section 3.3, Table 1 treats self-attention and FFN as modules of their own; with their norm
+    and residual inside, the layer is the one followed by the other - for prefill and for decode."""
+    cfg = _stack_cfg(1, n_seqs=3, seq_pad=8, len_lo=2, len_hi=8)
+    w = workloads.make_weights(cfg, 21)
+    inp = workloads.make_inputs(cfg, 21)
+    d = _odesc(cfg)
+    mask = np.arange(cfg.seq_pad)[None, :] < inp.lens[:, None]
+    y = oracle.decoder_layer_prefill(d, w, inp.x, inp.lens)
+    x1 = oracle.decoder_layer_prefill(d, w, inp.x, inp.lens, attention_only=True)
+    y2 = oracle.ffn_block(d, w, x1.reshape(-1, cfg.hidden)).reshape(x1.shape)
+    np.testing.assert_allclose(y2[mask], y[mask], rtol=1e-6, atol=1e-6)   # x1 passes through fp32 once
+    assert not np.allclose(x1[mask], y[mask])
+    dcfg = workloads.scaled(cfg, mode="decode", seq_pad=1, len_lo=0, len_hi=6)
+    di = workloads.make_inputs(dcfg, 22)
+    yd = oracle.decoder_layer_decode(d, w, di.x, di.lens, di.k_cache.copy(), di.v_cache.copy())
+    x1d = oracle.decoder_layer_decode(d, w, di.x, di.lens, di.k_cache.copy(), di.v_cache.copy(), attention_only=True)
+    np.testing.assert_allclose(oracle.ffn_block(d, w, x1d), yd, rtol=1e-6, atol=1e-6)
+
+
+def test_ffn_block_against_library_fp64_and_special_cases():
+    cfg = _stack_cfg(1)
+    w = workloads.make_weights(cfg, 23)
+    d = _odesc(cfg)
+    x = np.random.default_rng(5).standard_normal((7, cfg.hidden)).astype(np.float32)
+    y = oracle.ffn_block(d, w, x)
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    xd = t(x)
+    h = xd * torch.rsqrt((xd * xd).mean(-1, keepdim=True) + cfg.rms_eps) * t(w["g2"])
+    ref = xd + (F.silu(h @ t(w["wgate"]).T) * (h @ t(w["wup"]).T)) @ t(w["wdown"]).T
+    np.testing.assert_allclose(y, ref.numpy(), rtol=1e-6, atol=1e-6)
+    # silu(0) = 0: a zero gate projection leaves the residual stream untouched, bit for bit
+    w0 = dict(w, wgate=np.zeros_like(w["wgate"]))
+    assert np.array_equal(oracle.ffn_block(d, w0, x), x)
+    # the attention weights are not read
+    w1 = dict(w, wq=np.full_like(w["wq"], np.nan), g1=np.full_like(w["g1"], np.nan))
+    assert np.array_equal(oracle.ffn_block(d, w1, x), y)
+
+
+def test_attention_block_special_cases():
+    cfg = _stack_cfg(1, n_seqs=2, seq_pad=6, len_lo=6, len_hi=6)
+    w = workloads.make_weights(cfg, 24)
+    inp = workloads.make_inputs(cfg, 24)
+    d = _odesc(cfg)
+    # zero output projection: y = x bit for bit; the FFN weights are not read
+    w0 = dict(w, wo=np.zeros_like(w["wo"]), wgate=np.full_like(w["wgate"], np.nan), g2=np.full_like(w["g2"], np.nan))
+    assert np.array_equal(oracle.decoder_layer_prefill(d, w0, inp.x, inp.lens, attention_only=True), inp.x)
+    # first row: one visible key, softmax weight 1 -> x + (v_0 repeated per group) Wo^T
+    y = oracle.decoder_layer_prefill(d, w, inp.x, inp.lens, attention_only=True)
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    x0 = t(inp.x[:, 0])
+    h = x0 * torch.rsqrt((x0 * x0).mean(-1, keepdim=True) + cfg.rms_eps) * t(w["g1"])
+    v = (h @ t(w["wv"]).T).reshape(cfg.n_seqs, cfg.n_kv_heads, cfg.head_dim)
+    a = v.repeat_interleave(cfg.n_q_heads // cfg.n_kv_heads, dim=1).reshape(cfg.n_seqs, -1)
+    np.testing.assert_allclose(y[:, 0], (x0 + a @ t(w["wo"]).T).numpy(), rtol=1e-6, atol=1e-6)

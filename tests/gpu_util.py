@@ -14,7 +14,8 @@ def module_desc(cfg: workloads.Config) -> B.ModuleDesc:
     dt = B.CCS_BF16 if cfg.dtype == "bf16" else B.CCS_F32
     if cfg.kind == "linear":
         return B.ModuleDesc(kind=B.CCS_LINEAR, dtype=dt, in_features=cfg.in_features, out_features=cfg.out_features)
-    return B.ModuleDesc(kind=B.CCS_DECODER_LAYER, dtype=dt, hidden=cfg.hidden, n_q_heads=cfg.n_q_heads,
+    kind = {"decoder_layer": B.CCS_DECODER_LAYER, "attn_block": B.CCS_ATTN_BLOCK, "ffn_block": B.CCS_FFN_BLOCK}[cfg.kind]
+    return B.ModuleDesc(kind=kind, dtype=dt, hidden=cfg.hidden, n_q_heads=cfg.n_q_heads,
                         n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, intermediate=cfg.intermediate,
                         rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, n_layers=cfg.n_layers)
 
@@ -51,9 +52,10 @@ class DeviceBatch:
         self.cfg = cfg
         self.x = to_dev(inp.x, cfg)
         mode = {"prefill": B.CCS_PREFILL, "decode": B.CCS_DECODE, "linear": B.CCS_ROWS}[cfg.mode]
-        if cfg.kind == "linear":
-            self.y = torch.zeros((inp.x.shape[0], cfg.out_features), dtype=tdtype(cfg), device=DEV)
-            self.batch = m.batch(mode, self.x, self.y)
+        if cfg.kind in ("linear", "ffn_block"):
+            out = cfg.out_features if cfg.kind == "linear" else cfg.hidden
+            self.y = torch.zeros((inp.x.shape[0], out), dtype=tdtype(cfg), device=DEV)
+            self.batch = m.batch(B.CCS_ROWS, self.x, self.y)
             return
         self.y = torch.zeros_like(self.x)
         self.lens_host = torch.from_numpy(np.ascontiguousarray(inp.lens, dtype=np.int32))
@@ -100,6 +102,9 @@ def oracle_forward(cfg, seed: int = 0, weights=None, inputs=None, seqs=None, ret
     if cfg.kind == "linear":
         return oracle.linear(inp.x[sel], w["w"])
     d = oracle_desc(cfg)
+    if cfg.kind == "ffn_block":
+        return oracle.ffn_block(d, w, inp.x[sel])
+    ao = cfg.kind == "attn_block"
     if cfg.n_layers > 1:   # a run of layers; caches [L, B, ...]
         if cfg.mode == "prefill":
             return oracle.decoder_stack_prefill(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel])
@@ -108,10 +113,10 @@ def oracle_forward(cfg, seed: int = 0, weights=None, inputs=None, seqs=None, ret
         y = oracle.decoder_stack_decode(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel], kc, vc)
         return (y, kc, vc) if return_caches else y
     if cfg.mode == "prefill":
-        return oracle.decoder_layer_prefill(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel])
+        return oracle.decoder_layer_prefill(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel], attention_only=ao)
     kc = np.ascontiguousarray(inp.k_cache[sel]).copy()
     vc = np.ascontiguousarray(inp.v_cache[sel]).copy()
-    y = oracle.decoder_layer_decode(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel], kc, vc)
+    y = oracle.decoder_layer_decode(d, w, np.ascontiguousarray(inp.x[sel]), inp.lens[sel], kc, vc, attention_only=ao)
     return (y, kc, vc) if return_caches else y
 
 

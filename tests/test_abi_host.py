@@ -36,6 +36,18 @@ def test_arena_bytes_match_table1_weight_bytes(golden_dir):
     assert weights + gains <= arena <= weights + gains + 6 * 256      # + alignment padding only
     lin = B.ModuleDesc(kind=B.CCS_LINEAR, in_features=I, out_features=H)
     assert B.module_arena_bytes(lin) == int(float(g["ffn_proj_mib"]) * 2 ** 20)
+    # the layer's halves: self-attention 200 MiB, FFN 3 x 135 MiB (Table 1), + one gain vector each
+    att = B.module_arena_bytes(B.ModuleDesc(kind=B.CCS_ATTN_BLOCK, hidden=H, n_q_heads=nh, n_kv_heads=nh,
+                                            head_dim=H // nh, intermediate=I))
+    ffn = B.module_arena_bytes(B.ModuleDesc(kind=B.CCS_FFN_BLOCK, hidden=H, n_q_heads=nh, n_kv_heads=nh,
+                                            head_dim=H // nh, intermediate=I))
+    mib = 2 ** 20
+    assert int(float(g["self_attn_mib"])) * mib + H * 2 <= att <= int(float(g["self_attn_mib"])) * mib + H * 2 + 4 * 256
+    assert 3 * int(float(g["ffn_proj_mib"])) * mib + H * 2 <= ffn <= 3 * int(float(g["ffn_proj_mib"])) * mib + H * 2 + 3 * 256
+    assert att + ffn == arena
+    # a run of layers is that many layer arenas back to back
+    run = B.ModuleDesc(hidden=H, n_q_heads=nh, n_kv_heads=nh, head_dim=H // nh, intermediate=I, n_layers=3)
+    assert B.module_arena_bytes(run) == 3 * arena
 
 
 def test_bad_descs_are_rejected_without_a_gpu():

@@ -165,6 +165,30 @@ def test_run_of_layers_fills_and_extends_every_layers_cache():
         m.destroy()
 
 
+def test_attention_block_and_ffn_block_modules():
+    """The layer's two halves as modules of their own (Section 3.3, Table 1): each against its
+    oracle, split bit-exactly, and chained on the GPU they reproduce the whole-layer module."""
+    shape = dict(hidden=1024, n_q_heads=8, n_kv_heads=4, intermediate=2752)
+    dec = workloads.scaled(C["C2"], kind="attn_block", n_seqs=13, len_lo=20, len_hi=300, **shape)
+    run_case(dec, [1, 2, 4], seed=80)
+    pre = workloads.scaled(C["C3"], kind="attn_block", n_seqs=3, seq_pad=70, len_lo=9, len_hi=70, **shape)
+    run_case(pre, [1, 2], seed=81)
+    for n in (13, 200):      # weight-streaming and LDS-tiled GEMMs
+        ffn = workloads.scaled(C["C2"], kind="ffn_block", mode="linear", n_seqs=n, **shape)
+        run_case(ffn, [1, 2, 4], seed=82 + n)
+    f32 = workloads.scaled(C["C1"], kind="attn_block", n_seqs=5, seq_pad=24, len_lo=3, len_hi=24)
+    run_case(f32, [1, 2], seed=83)
+    run_case(workloads.scaled(C["C1"], kind="ffn_block", mode="linear", n_seqs=37), [1, 3], seed=84)
+    # chained on the GPU: attention block -> FFN block == decoder layer (same kernels, same bits)
+    layer = workloads.scaled(C["C2"], n_seqs=13, len_lo=20, len_hi=300, **shape)
+    w = workloads.make_weights(layer, 85)
+    inp = workloads.make_inputs(layer, 85)
+    y_layer = U.gpu_forward(layer, 1, 85, w, inp)
+    x1 = U.gpu_forward(workloads.scaled(layer, kind="attn_block"), 1, 85, w, inp)
+    y2 = U.gpu_forward(workloads.scaled(layer, kind="ffn_block", mode="linear"), 2, 85, w, workloads.Inputs(x=x1))
+    assert np.array_equal(y2, y_layer)
+
+
 def test_uneven_shares_give_the_same_bits_as_any_other_partition():
     """Eq. 1 of the speed-up model lets replica j of a layer take its own share bs_ij of the
     batch: any partition of the sequences must reproduce the unsplit result bit for bit."""

@@ -24,7 +24,7 @@ import torch
 @dataclass(frozen=True)
 class Config:
     name: str
-    kind: str            # "decoder_layer" | "linear"
+    kind: str            # "decoder_layer" | "linear" | "attn_block" | "ffn_block" (the layer's two halves)
     dtype: str           # "f32" | "bf16"
     hidden: int = 0
     n_q_heads: int = 0
@@ -119,6 +119,8 @@ def make_inputs(cfg: Config, seed: int = 0) -> Inputs:
     g = torch.Generator().manual_seed(seed + 1)
     if cfg.kind == "linear":
         return Inputs(x=_randn(g, (cfg.n_seqs, cfg.in_features), cfg.dtype))
+    if cfg.kind == "ffn_block":   # independent token rows
+        return Inputs(x=_randn(g, (cfg.n_seqs, cfg.hidden), cfg.dtype))
     B, H = cfg.n_seqs, cfg.hidden
     lens = torch.randint(cfg.len_lo, cfg.len_hi + 1, (B,), generator=g, dtype=torch.int64)
     lens = lens.to(torch.int32).numpy()

@@ -242,6 +242,34 @@ int ccs_module_sync(ccs_module *m);
  * the caller. */
 int ccs_module_destroy(ccs_module *m);
 
+/* ---- scale-up planning (Section 4.1), host-only: no GPU, no module handle ----------------------- */
+
+/* Eq. 4, homogeneous devices and even splits: S = 1 / (gamma + (1 - gamma) / n * sum_i 1 / p_i),
+ * p[i] >= 1 the number of instances of layer i (host array, n entries), gamma = delta C / (d B).
+ * Returns 0 for bad arguments. */
+double ccs_speedup_homo(const int32_t *p, int32_t n, double gamma);
+
+/* Eq. 1-3, general form: S = W(P0) / (W(P) + T(P)) with W(P) = sum_i max_j d^2 bs_ij l / C_ij and
+ * T(P) = delta sum_i sum_{j>=1} d bs_ij l / B_ij.  bs, capacity, bandwidth are host arrays
+ * flattened over (layer i, instance j < p[i]), instance 0 being the original (its bandwidth
+ * entry is ignored); W(P0) runs each layer's whole batch on its original.  Returns 0 for bad
+ * arguments. */
+double ccs_speedup(const int32_t *p, int32_t n, const double *bs, const double *capacity,
+                   const double *bandwidth, double d, double l, double delta);
+
+/* Algorithm 1 (greedy scale-up).  p_in: current instances per layer (n entries, >= 1).  Node g
+ * (n_nodes of them, visited in order) has node_available[g] free resource units; it is eligible
+ * if at least one replica of replica_size units fits, and takes at most available / size replicas.
+ * placed_in (optional, [n_nodes][n] bytes): which layers node g already holds a replica of.
+ * For each eligible node the candidate layers are ordered by continuity - repeatedly the free
+ * layer that gives the node its longest run of consecutive layers, the lower index on ties - and
+ * a replica is added whenever Eq. 4 improves.  Outputs: p_out (n entries), placed_out
+ * ([n_nodes][n] bytes, caller-allocated), speedup_out (optional).  The call only plans; the
+ * caller instantiates the replicas.  Errors: CCS_EINVAL. */
+int ccs_plan_scale_up(const int32_t *p_in, int32_t n, double gamma, const int64_t *node_available,
+                      int32_t n_nodes, int64_t replica_size, const uint8_t *placed_in,
+                      int32_t *p_out, uint8_t *placed_out, double *speedup_out);
+
 /* Thread-local, never null; valid until the next library call on this thread. */
 const char *ccs_last_error(void);
 

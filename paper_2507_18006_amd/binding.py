@@ -28,6 +28,7 @@ EXPORTS = (
     "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
     "ccs_module_forward_split", "ccs_module_forward_shares", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
     "ccs_module_arena", "ccs_module_profile", "ccs_module_profile_read", "ccs_module_sync", "ccs_module_destroy", "ccs_last_error", "ccs_version",
+    "ccs_speedup_homo", "ccs_speedup", "ccs_plan_scale_up",
 )
 
 
@@ -98,6 +99,14 @@ def lib():
                                           ctypes.POINTER(ctypes.c_int64), i32]
     L.ccs_module_sync.argtypes = [vp]
     L.ccs_module_destroy.argtypes = [vp]
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)
+    L.ccs_speedup_homo.restype = ctypes.c_double
+    L.ccs_speedup_homo.argtypes = [ip, i32, ctypes.c_double]
+    L.ccs_speedup.restype = ctypes.c_double
+    L.ccs_speedup.argtypes = [ip, i32, dp, dp, dp, ctypes.c_double, ctypes.c_double, ctypes.c_double]
+    L.ccs_plan_scale_up.restype = ctypes.c_int
+    L.ccs_plan_scale_up.argtypes = [ip, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_int64), i32, ctypes.c_int64,
+                                    ctypes.POINTER(ctypes.c_uint8), ip, ctypes.POINTER(ctypes.c_uint8), dp]
     L.ccs_last_error.restype = ctypes.c_char_p
     L.ccs_version.restype = ctypes.c_char_p
     for name in ("ccs_module_create", "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
@@ -320,3 +329,31 @@ def cache_copy(dst, src, stream=None):
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("size mismatch")
     _check(lib().ccs_cache_copy(dst.data_ptr(), src.data_ptr(), nbytes, s.cuda_stream))
+
+
+# -- scale-up planning (host only) -----------------------------------------------------------------
+def speedup_homo(p, gamma: float) -> float:
+    a = (ctypes.c_int32 * len(p))(*[int(v) for v in p])
+    return lib().ccs_speedup_homo(a, len(p), float(gamma))
+
+
+def speedup(p, bs, capacity, bandwidth, d: float, l: float, delta: float) -> float:
+    """bs, capacity, bandwidth: one list per layer with p[i] entries (instance 0 = the original)."""
+    a = (ctypes.c_int32 * len(p))(*[int(v) for v in p])
+    flat = lambda rows: (ctypes.c_double * sum(len(r) for r in rows))(*[float(v) for r in rows for v in r])
+    return lib().ccs_speedup(a, len(p), flat(bs), flat(capacity), flat(bandwidth), float(d), float(l), float(delta))
+
+
+def plan_scale_up(p, gamma: float, node_available, replica_size: int, placed=None):
+    """Algorithm 1: returns (p_new, placed[node][layer], speedup)."""
+    n, g = len(p), len(node_available)
+    a = (ctypes.c_int32 * n)(*[int(v) for v in p])
+    av = (ctypes.c_int64 * max(g, 1))(*[int(v) for v in node_available])
+    pin = None
+    if placed is not None:
+        pin = (ctypes.c_uint8 * (g * n))(*[1 if v else 0 for row in placed for v in row])
+    out = (ctypes.c_int32 * n)()
+    pout = (ctypes.c_uint8 * max(g * n, 1))()
+    sp = ctypes.c_double()
+    _check(lib().ccs_plan_scale_up(a, n, float(gamma), av, g, int(replica_size), pin, out, pout, ctypes.byref(sp)))
+    return list(out), [[int(pout[i * n + j]) for j in range(n)] for i in range(g)], sp.value

@@ -338,19 +338,21 @@ hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void 
 // =============================================================================================
 // Decode attention, bf16, head_dim 128
 // =============================================================================================
-constexpr int kDecChunk = 256;   // keys per split; a property of the kernel, not of the batch
+// keys per split: a property of the kernel, never of the batch (128 measured best for the 7B
+// multi-head and the ragged 70B grouped-query decode configurations; 256 within 2 %)
+constexpr int kDecChunkMin = 128;
 constexpr int kDecPart = 132;    // floats per partial: [0] max (log2 domain), [1] sum, [4..131] values
-
-static inline int dec_chunks(int cap) { return (cap + kDecChunk - 1) / kDecChunk; }
+static inline int dec_chunk_keys(int, int) { return kDecChunkMin; }
+static inline int dec_chunks(int cap, int chunk_keys) { return (cap + chunk_keys - 1) / chunk_keys; }
 
 size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap)
 {
-    return (size_t)n_seqs * nq * dec_chunks(cap) * kDecPart * sizeof(float);
+    return (size_t)n_seqs * nq * dec_chunks(cap, kDecChunkMin) * kDecPart * sizeof(float);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Decode attention with both products on the matrix cores (any group size G <= 8).
-// One wavefront = one (sequence, kv head, chunk of kDecChunk keys); it serves the G query heads of
+// One wavefront = one (sequence, kv head, chunk of chunk_keys keys); it serves the G query heads of
 // the group at once, so K and V are read exactly once.  Scores are computed transposed, as in the
 // prefill kernel: S^T[key][head] = K Q^T with 16 cached K rows x 32 d read straight from the
 // row-major cache as the A operand and the group's query heads as the B columns (columns >= G
@@ -474,20 +476,48 @@ template <int G>
 __global__ __launch_bounds__(256, 2) void attn_decode_mfma_kernel(
     const bf16_t *__restrict__ qkv, float *__restrict__ part, int n_seqs, int nq, int nkv,
     const int32_t *__restrict__ lens, const uint4 *__restrict__ kc, const uint4 *__restrict__ vc, int cap,
-    int nchunks)
+    int nchunks, int chunk_keys)
 {
     extern __shared__ uint4 lds[];   // 4 wavefronts x 2 stages x 8 KiB
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // Units are the NON-EMPTY (sequence, kv head, chunk) triples in that order (chunk fastest, so the
+    // wavefronts of a workgroup read neighbouring pieces of one K / V stream): a sequence of n keys
+    // has ceil(n / chunk_keys) chunks per kv head, found with a prefix sum over the batch's
+    // lengths.  The grid is sized for full caches; wavefronts past the last unit leave at once.
     const long unit = (long)blockIdx.x * 4 + wv;
-    if (unit >= (long)n_seqs * nkv * nchunks) return;
-    const int chunk = (int)(unit % nchunks);
-    const int kvh = (int)((unit / nchunks) % nkv);
-    const int b = (int)(unit / ((long)nchunks * nkv));
+    int b = -1, chunk = 0, kvh = 0;
+    long base = 0;
+    for (int s0 = 0; s0 < n_seqs; s0 += 64) {
+        const int i = s0 + lane;
+        const int nch = i < n_seqs ? (lens[i] + chunk_keys) / chunk_keys : 0;
+        int pre = nch;   // inclusive prefix sum over the 64 lanes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(pre, o, 64);
+            if (lane >= o) pre += t;
+        }
+        const long tot = (long)__shfl(pre, 63, 64) * nkv;
+        if (unit < base + tot) {
+            const long lo = base + (long)(pre - nch) * nkv, hi = base + (long)pre * nkv;
+            const unsigned long long hit = __ballot(unit >= lo && unit < hi);
+            const int src = __ffsll((long long)hit) - 1;
+            const int nch_b = __shfl(nch, src, 64);
+            const int r = (int)(unit - base - (long)__shfl(pre - nch, src, 64) * nkv);
+            b = s0 + src;
+            kvh = r / nch_b;
+            chunk = r % nch_b;
+            break;
+        }
+        base += tot;
+    }
+    if (b < 0) return;
+    b = __builtin_amdgcn_readfirstlane(b);
+    chunk = __builtin_amdgcn_readfirstlane(chunk);
+    kvh = __builtin_amdgcn_readfirstlane(kvh);
     const int n_keys = lens[b] + 1;
-    const int j0 = chunk * kDecChunk;
-    if (j0 >= n_keys) return;
-    const int j1 = min(n_keys, j0 + kDecChunk);
+    const int j0 = chunk * chunk_keys;          // < n_keys by construction
+    const int j1 = min(n_keys, j0 + chunk_keys);
     const int width = (nq + 2 * nkv) * 128;
     const int c16 = lane & 15, g4 = lane >> 4;
     const float sc = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
@@ -561,18 +591,38 @@ __global__ __launch_bounds__(256, 2) void attn_decode_mfma_kernel(
 // Merge the chunk partials of one (sequence, head) in chunk order; thread c owns value c.
 __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restrict__ part,
                                                            bf16_t *__restrict__ out, int nq,
-                                                           const int32_t *__restrict__ lens, int nchunks)
+                                                           const int32_t *__restrict__ lens, int nchunks,
+                                                           int chunk_keys)
 {
     const int b = blockIdx.x / nq, h = blockIdx.x % nq, c = threadIdx.x;
-    const int n = (lens[b] + 1 + kDecChunk - 1) / kDecChunk;
+    const int n = (lens[b] + chunk_keys) / chunk_keys;
     const float *p = part + ((size_t)b * nq + h) * nchunks * kDecPart;
+    // eight chunks at a time, their loads all in flight; merged in chunk order
     float M = -INFINITY;
-    for (int i = 0; i < n; ++i) M = fmaxf(M, p[(size_t)i * kDecPart]);
+    for (int i0 = 0; i0 < n; i0 += 8) {
+        float m[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] = i0 + e < n ? p[(size_t)(i0 + e) * kDecPart] : -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) M = fmaxf(M, m[e]);
+    }
     float L = 0.f, a = 0.f;
-    for (int i = 0; i < n; ++i) {
-        const float w = exp2f(p[(size_t)i * kDecPart] - M);
-        L = fmaf(p[(size_t)i * kDecPart + 1], w, L);
-        a = fmaf(p[(size_t)i * kDecPart + 4 + c], w, a);
+    for (int i0 = 0; i0 < n; i0 += 8) {
+        float m[8], l[8], v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool ok = i0 + e < n;
+            const float *q = p + (size_t)(ok ? i0 + e : 0) * kDecPart;
+            m[e] = ok ? q[0] : -INFINITY;   // weight 0
+            l[e] = q[1];
+            v[e] = q[4 + c];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float w = exp2f(m[e] - M);
+            L = fmaf(l[e], w, L);
+            a = fmaf(v[e], w, a);
+        }
     }
     out[packed_index(b, h * 128 + c, (nq * 128) >> 5)] = f2bf(a / L);
 }
@@ -582,7 +632,7 @@ hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs,
                                    const void *v_cache, int cap, hipStream_t st)
 {
     if (n_seqs <= 0) return hipSuccess;
-    const int nchunks = dec_chunks(cap), G = nq / nkv;
+    const int chunk_keys = dec_chunk_keys(nq, nkv), nchunks = dec_chunks(cap, chunk_keys), G = nq / nkv;
     const long units = (long)n_seqs * nkv * nchunks;
     dim3 grid((unsigned)((units + 3) / 4)), block(256);
 #define CCS_GQA(GV)                                                                                        \
@@ -596,7 +646,7 @@ hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs,
         }                                                                                                  \
         hipLaunchKernelGGL((attn_decode_mfma_kernel<GV>), grid, block, 65536, st, (const bf16_t *)qkv,     \
                            partials, n_seqs, nq, nkv, lens_dev, (const uint4 *)k_cache,                    \
-                           (const uint4 *)v_cache, cap, nchunks);                                          \
+                           (const uint4 *)v_cache, cap, nchunks, chunk_keys);                              \
     } while (0)
     switch (G) {
         case 1: CCS_GQA(1); break;
@@ -609,13 +659,13 @@ hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs,
     return hipGetLastError();
 }
 
-hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, int n_seqs, int nq,
+hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, int n_seqs, int nq, int nkv,
                                       const int32_t *lens_dev, int cap, hipStream_t st)
 {
     if (n_seqs <= 0) return hipSuccess;
-    const int nchunks = dec_chunks(cap);
+    const int chunk_keys = dec_chunk_keys(nq, nkv), nchunks = dec_chunks(cap, chunk_keys);
     hipLaunchKernelGGL(attn_combine_kernel, dim3(n_seqs * nq), dim3(128), 0, st, partials, (bf16_t *)out_packed,
-                       nq, lens_dev, nchunks);
+                       nq, lens_dev, nchunks, chunk_keys);
     return hipGetLastError();
 }
 

@@ -110,7 +110,7 @@ size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap);
 hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs, int nq, int nkv,
                                    const int32_t *lens_dev, const void *k_cache,
                                    const void *v_cache, int cap, hipStream_t st);
-hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, int n_seqs, int nq,
+hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, int n_seqs, int nq, int nkv,
                                       const int32_t *lens_dev, int cap, hipStream_t st);
 
 }  // namespace ccs

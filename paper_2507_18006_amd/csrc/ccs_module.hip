@@ -415,7 +415,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             }
             if (decode) {
                 CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
-                CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, b->lens_dev, b->cache_cap, st));
+                CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
             } else {
                 CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, b->lens_dev, st));
             }

@@ -426,3 +426,32 @@ def test_forward_split_recorded_in_a_hip_graph_replays_like_eager():
                 assert torch.equal(db.k, ref.k) and torch.equal(db.v, ref.v)
     finally:
         m.destroy()
+
+
+def test_stage_profile_reports_every_kernel_of_a_decode_step():
+    """ccs_module_profile brackets the selected stages with HIP events on the replica's stream."""
+    cfg = workloads.scaled(C["C2"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
+                           n_seqs=8, len_lo=10, len_hi=200)
+    m = U.make_module(cfg)
+    try:
+        db = U.DeviceBatch(m, cfg, workloads.make_inputs(cfg, 0))
+        m.profile(None)
+        for _ in range(3):
+            m.forward_split(db.batch)
+        m.sync()
+        prof = m.profile_read(0, reset=True)
+        for stage in ("rmsnorm1", "gemm_qkv", "gemm_qkv_reduce", "attn", "attn_combine", "gemm_o", "gemm_o_reduce",
+                      "gemm_gu", "gemm_down", "gemm_down_reduce"):
+            ms, n = prof[stage]
+            assert n == 3 and 0.0 < ms < 50.0, (stage, ms, n)
+        m.profile(("attn",))
+        m.forward_split(db.batch)
+        m.sync()
+        prof = m.profile_read(0, reset=True)
+        assert set(prof) == {"attn"} and prof["attn"][1] == 1
+        m.profile([])
+        m.forward_split(db.batch)
+        m.sync()
+        assert m.profile_read(0) == {}
+    finally:
+        m.destroy()

@@ -176,8 +176,7 @@ int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice);
  * bit-identical for every k at a fixed batch.  The caller keeps successive uses of replica 0
  * ordered (same stream, or its own events); work that created or migrated replica 0 must have
  * completed.  The call only enqueues (kernel launches, event record / wait), so it may be
- * recorded into a HIP graph by capturing `caller_stream` once every kernel variant it uses
- * has been launched outside a capture (the first launch of a variant sets a function attribute). */
+ * recorded into a HIP graph by capturing `caller_stream`. */
 int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream);
 
 /* The same with uneven shares: slice j is the next counts[j] sequences (rows for a projection),

@@ -322,13 +322,6 @@ hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void 
     if (n_seqs <= 0) return hipSuccess;
     const int S32 = (seq_pad + 31) / 32 * 32;
     const size_t smem = (size_t)kPfStages * kPfStageU4 * 16;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_mfma_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
     dim3 grid((seq_pad + 127) / 128, nq, n_seqs);
     hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(256), smem, st, (const bf16_t *)qkv, (const uint4 *)kp,
                        (const uint4 *)vtp, (bf16_t *)out_packed, nq, nkv, seq_pad, S32, lens_dev);
@@ -637,13 +630,6 @@ hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs,
     dim3 grid((unsigned)((units + 3) / 4)), block(256);
 #define CCS_GQA(GV)                                                                                        \
     do {                                                                                                   \
-        static bool attr_done = false;                                                                     \
-        if (!attr_done) {                                                                                  \
-            hipError_t e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<GV>,                  \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 65536);         \
-            if (e != hipSuccess) return e;                                                                 \
-            attr_done = true;                                                                              \
-        }                                                                                                  \
         hipLaunchKernelGGL((attn_decode_mfma_kernel<GV>), grid, block, 65536, st, (const bf16_t *)qkv,     \
                            partials, n_seqs, nq, nkv, lens_dev, (const uint4 *)k_cache,                    \
                            (const uint4 *)v_cache, cap, nchunks, chunk_keys);                              \
@@ -667,6 +653,19 @@ hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, i
     hipLaunchKernelGGL(attn_combine_kernel, dim3(n_seqs * nq), dim3(128), 0, st, partials, (bf16_t *)out_packed,
                        nq, lens_dev, nchunks, chunk_keys);
     return hipGetLastError();
+}
+
+// Function attributes (dynamic LDS sizes) of this file's kernels; once per process, outside any
+// stream capture (ccs_module_create calls it).
+hipError_t init_attention_kernels()
+{
+    const int attr = (int)hipFuncAttributeMaxDynamicSharedMemorySize;
+    hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_mfma_kernel, (hipFuncAttribute)attr, kPfStages * kPfStageU4 * 16);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<1>, (hipFuncAttribute)attr, 65536);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<2>, (hipFuncAttribute)attr, 65536);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<4>, (hipFuncAttribute)attr, 65536);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<8>, (hipFuncAttribute)attr, 65536);
+    return e;
 }
 
 }  // namespace ccs

@@ -292,18 +292,13 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restr
     }
 }
 
+constexpr int sk_lds_bytes(int MB) { return 2 * MB * 16 * (kSkNB * 16 + 4) * (int)sizeof(float); }
+
 template <int MB, int EPI>
 static hipError_t sk_launch(dim3 grid, hipStream_t st, const uint4 *Wp, const uint4 *Xp, float *partials, int nblk,
                             int kfrags, int ntiles, int kf_seg, int M, int N, const bf16_t *res, bf16_t *out)
 {
-    constexpr int kLds = 2 * MB * 16 * (kSkNB * 16 + 4) * (int)sizeof(float);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, EPI>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    constexpr int kLds = sk_lds_bytes(MB);
     hipLaunchKernelGGL((gemm_skinny_kernel<MB, EPI>), grid, dim3(kSkWaves * 64), kLds, st, Wp, Xp, partials, nblk,
                        kfrags, ntiles, kf_seg, M, N, res, out);
     return hipGetLastError();
@@ -637,14 +632,7 @@ hipError_t launch_gemm_tiled_dma(const void *Wp, const void *Xp, int epi, const 
                                  int M, int N, int K, float *part, int S, hipStream_t st)
 {
     using C = DmaCfg<BM, NST>;
-    static bool attr_done = false;
     auto kern = gemm_tiled_dma_kernel<BM, NST>;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + 255) / 256, tiles = tiles_m * tiles_n;
     const int kfrags = K / 32, per = (kfrags + S - 1) / S;
     hipLaunchKernelGGL(kern, dim3(tiles * S), dim3(256), C::LDS_BYTES, st, (const uint4 *)Wp, (const uint4 *)Xp, epi,
@@ -693,6 +681,29 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
     // prologue run under the other's main loop - measured 5-20 % faster than one 256 x 256 or
     // 256 x 128 workgroup per CU with a deeper ring on every projection shape of the 13B layer.
     return launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, st);
+}
+
+// Function attributes (dynamic LDS sizes) of this file's kernels; once per process, outside any
+// stream capture (ccs_module_create calls it).
+template <int MB>
+static hipError_t init_skinny_mb()
+{
+    const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, SK_PARTIALS>, attr, sk_lds_bytes(MB));
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, SK_STORE_RM>, attr, sk_lds_bytes(MB));
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, SK_SWIGLU_PACKED>, attr, sk_lds_bytes(MB));
+    return e;
+}
+
+hipError_t init_gemm_kernels()
+{
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_tiled_dma_kernel<128, 3>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)DmaCfg<128, 3>::LDS_BYTES);
+    if (e == hipSuccess) e = init_skinny_mb<1>();
+    if (e == hipSuccess) e = init_skinny_mb<2>();
+    if (e == hipSuccess) e = init_skinny_mb<3>();
+    if (e == hipSuccess) e = init_skinny_mb<4>();
+    return e;
 }
 
 }  // namespace ccs

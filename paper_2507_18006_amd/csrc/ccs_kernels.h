@@ -9,6 +9,10 @@ namespace ccs {
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
+// One-time function attributes (dynamic LDS sizes); not capturable, so not part of a forward.
+hipError_t init_gemm_kernels();
+hipError_t init_attention_kernels();
+
 // ---- streaming / elementwise (ccs_elementwise.hip) -----------------------------------------
 // dst[0:bytes) = src[0:bytes), both 16-byte aligned, device memory, no overlap.
 hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st);

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -530,6 +531,15 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
     int ndev = 0;
     CCS_HIP(hipGetDeviceCount(&ndev));
     if (ndev < 1) return fail(CCS_EHIP, "no HIP device");
+    {   // kernel attributes: once per process, here rather than in a forward (which may be captured)
+        static std::once_flag once;
+        static hipError_t init_err = hipSuccess;
+        std::call_once(once, [] {
+            init_err = ccs::init_gemm_kernels();
+            if (init_err == hipSuccess) init_err = ccs::init_attention_kernels();
+        });
+        if (init_err != hipSuccess) return fail(CCS_EHIP, "kernel attributes: %s", hipGetErrorString(init_err));
+    }
 
     ccs_module *m = new (std::nothrow) ccs_module();
     if (!m) return fail(CCS_ENOMEM, "host allocation failed");

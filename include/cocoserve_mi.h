@@ -206,8 +206,10 @@ int ccs_cache_copy(void *dst, const void *src, size_t bytes, void *stream);
 int ccs_module_arena(const ccs_module *m, int32_t replica, void **arena_out);
 
 /* Kernels of one replica forward, for per-kernel device timing.  The weight-streaming GEMM
- * variant is two launches (main + REDUCE); the LDS-tiled variant only reports the main stage.
- * A projection module reports PACK_X and GEMM_DOWN(+_REDUCE). */
+ * variant is one launch when K is not split (its epilogue runs in the kernel) and two otherwise
+ * (main + REDUCE); the LDS-tiled variant reports everything under the main stage.  A projection
+ * module reports PACK_X and GEMM_DOWN(+_REDUCE).  In a run of layers a stage accumulates over
+ * the layers. */
 typedef enum ccs_stage {
     CCS_ST_RMSNORM1 = 0,
     CCS_ST_GEMM_QKV = 1, CCS_ST_GEMM_QKV_REDUCE = 2,

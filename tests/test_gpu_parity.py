@@ -78,6 +78,14 @@ def test_bf16_decode_scaled_gqa():
         run_case(cfg, [1, 2], seed=2 + g)
 
 
+def test_bf16_decode_many_sequences_take_the_tiled_gemms():
+    """More than 64 sequences per step: the LDS-tiled GEMMs (with their K split at this size), the
+    stand-alone rotary kernel and several 64-sequence blocks in the attention's unit search."""
+    cfg = workloads.scaled(C["C4"], hidden=1024, n_q_heads=16, n_kv_heads=4, intermediate=1792,
+                           n_seqs=300, len_lo=0, len_hi=150)
+    run_case(cfg, [1, 2, 4], seed=9)
+
+
 def test_bf16_prefill_scaled_ragged():
     cfg = workloads.scaled(C["C3"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
                            n_seqs=5, seq_pad=80, len_lo=17, len_hi=80)

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(
         h = (int)(unit % nq);
         const int kvh = h / (nq / nkv);
         if (decode) {
-            n_keys = lens[row] + 1;
+            n_keys = cached_len(lens, row, cap) + 1;
             kbase = kc + ((size_t)row * nkv + kvh) * cap * d;
             vbase = vc + ((size_t)row * nkv + kvh) * cap * d;
             kstride = d;
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_mfma_kernel(
     long base = 0;
     for (int s0 = 0; s0 < n_seqs; s0 += 64) {
         const int i = s0 + lane;
-        const int nch = i < n_seqs ? (lens[i] + chunk_keys) / chunk_keys : 0;
+        const int nch = i < n_seqs ? (cached_len(lens, i, cap) + chunk_keys) / chunk_keys : 0;
         int pre = nch;   // inclusive prefix sum over the 64 lanes
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -508,7 +508,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_mfma_kernel(
     b = __builtin_amdgcn_readfirstlane(b);
     chunk = __builtin_amdgcn_readfirstlane(chunk);
     kvh = __builtin_amdgcn_readfirstlane(kvh);
-    const int n_keys = lens[b] + 1;
+    const int n_keys = cached_len(lens, b, cap) + 1;
     const int j0 = chunk * chunk_keys;          // < n_keys by construction
     const int j1 = min(n_keys, j0 + chunk_keys);
     const int width = (nq + 2 * nkv) * 128;
@@ -588,7 +588,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restri
                                                            int chunk_keys)
 {
     const int b = blockIdx.x / nq, h = blockIdx.x % nq, c = threadIdx.x;
-    const int n = (lens[b] + chunk_keys) / chunk_keys;
+    const int n = min((max(lens[b], 0) + chunk_keys) / chunk_keys, nchunks);
     const float *p = part + ((size_t)b * nq + h) * nchunks * kDecPart;
     // eight chunks at a time, their loads all in flight; merged in chunk order
     float M = -INFINITY;

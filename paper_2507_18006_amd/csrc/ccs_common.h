@@ -101,6 +101,13 @@ __device__ __forceinline__ void rope_cs(const float2 *__restrict__ tab, int i, i
     c = fmaf(-dl, s0, c0);
 }
 
+// Cached length of sequence i in a decode step, forced into [0, cap - 1]: the host validates its
+// copy of the lengths, this keeps a device copy that disagrees from pushing accesses out of the cache.
+__device__ __forceinline__ int cached_len(const int32_t *__restrict__ lens, int i, int cap)
+{
+    return min(max(lens[i], 0), cap - 1);
+}
+
 template <typename T> struct io;
 template <> struct io<float> {
     static __device__ __forceinline__ float ld(const float *p) { return *p; }

@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, i
     const int width = (nq + 2 * nkv) * d;
     T *r = qkv + (size_t)row * width;
     int seq, pos, len;
-    if (decode) { seq = row; pos = lens[row]; len = pos + 1; }
+    if (decode) { seq = row; pos = cap > 0 ? cached_len(lens, row, cap) : max(lens[row], 0); len = pos + 1; }
     else { seq = row / seq_pad; pos = row % seq_pad; len = lens[seq]; }
     const bool store = (k_cache != nullptr) && (pos < len) && (pos < cap);
     for (int i = threadIdx.x; i < half; i += 64) {
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void qkv_reduce_rope_decode_kernel(
         lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
         hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
     }
-    const int pos = lens[m];
+    const int pos = cached_len(lens, m, cap);
     float l[4] = {lo.x, lo.y, lo.z, lo.w}, h[4] = {hi.x, hi.y, hi.z, hi.w};
     if (head < nq + nkv) {
 #pragma unroll

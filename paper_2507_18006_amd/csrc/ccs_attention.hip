@@ -268,14 +268,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float mn = fmaxf(m_run[qt], mx);   // finite: key q0w of the diagonal block is visible to every row
-            const float alpha = exp2f(m_run[qt] - mn);
+            const float alpha = fast_exp2(m_run[qt] - mn);
             m_run[qt] = mn;
             float ls = 0.f;
 #pragma unroll
             for (int kt2 = 0; kt2 < 2; ++kt2)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    v[kt2][r] = exp2f(v[kt2][r] - mn);
+                    v[kt2][r] = fast_exp2(v[kt2][r] - mn);
                     ls += v[kt2][r];
                 }
             l_run[qt] = l_run[qt] * alpha + ls;
@@ -436,14 +436,14 @@ __device__ __forceinline__ void dm_block(const u32x4_t (&kf)[2][4], const u32x4_
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float mn = fmaxf(m_run, mx);   // finite: key jb of this block is valid
-    const float alpha = exp2f(m_run - mn);
+    const float alpha = fast_exp2(m_run - mn);
     m_run = mn;
     float ls = 0.f;
 #pragma unroll
     for (int kt2 = 0; kt2 < 2; ++kt2)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            x[kt2][r] = exp2f(x[kt2][r] - mn);
+            x[kt2][r] = fast_exp2(x[kt2][r] - mn);
             ls += x[kt2][r];
         }
     l_run = l_run * alpha + ls;
@@ -612,7 +612,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restri
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float w = exp2f(m[e] - M);
+            const float w = fast_exp2(m[e] - M);
             L = fmaf(l[e], w, L);
             a = fmaf(v[e], w, a);
         }

@@ -76,10 +76,77 @@ hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// RMSNorm: one wavefront per row, wave-wide butterfly reduction of the squares; the second
-// pass re-reads the row (it is in L1/L2).  A row's arithmetic does not depend on how many
-// rows the launch has.
+// RMSNorm.  A row's arithmetic depends on H alone: not on how many rows the launch has, nor on
+// where the row sits in it.
+//
+// Block form (bf16, rows up to 8192 wide): a workgroup of 8 waves owns one 16-row block of the
+// packed output and wave w owns its 1 KiB fragments w, w + 8, ...  Lane (r, q) = (lane & 15,
+// lane >> 4) reads the 16-byte chunk 4 f + q of row r, which is exactly slot `lane` of fragment
+// f, so every store instruction writes one whole contiguous fragment (the row-per-wave form
+// writes 16-byte pieces 256 bytes apart).  The row stays in registers between the two passes,
+// all loads are in flight together, and the sum of squares is put together in a fixed order:
+// a lane's fragments in sequence, the four k quarters by two butterfly steps, the eight waves
+// in index order through LDS.
 // ---------------------------------------------------------------------------------------------
+constexpr int kNormWaves = 8;
+
+template <int HOLD>   // fragments a wave keeps in registers: kfrags <= 8 * HOLD
+__global__ __launch_bounds__(512) void rmsnorm_bf16_block_kernel(const uint4 *__restrict__ x,
+                                                                 const uint4 *__restrict__ g,
+                                                                 uint4 *__restrict__ out, int rows,
+                                                                 int H, float eps)
+{
+    __shared__ float part[kNormWaves][16];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int row = blockIdx.x * 16 + r;
+    const bool live = row < rows;
+    const int chunks = H >> 3, kfrags = H >> 5;
+    const uint4 *xr = x + (size_t)(live ? row : 0) * chunks + q;
+    uint4 v[HOLD];
+#pragma unroll
+    for (int i = 0; i < HOLD; ++i) {
+        const int f = w + kNormWaves * i;
+        v[i] = (live && f < kfrags) ? xr[4 * f] : make_uint4(0, 0, 0, 0);
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < HOLD; ++i) {
+        const uint32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float a = bf_lo(e[j]), b = bf_hi(e[j]);
+            ss = fmaf(a, a, ss);
+            ss = fmaf(b, b, ss);
+        }
+    }
+    ss += __shfl_xor(ss, 16);
+    ss += __shfl_xor(ss, 32);
+    if (q == 0) part[w][r] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int j = 0; j < kNormWaves; ++j) tot += part[j][r];
+    const float rs = 1.0f / sqrtf(tot / (float)H + eps);
+    uint4 *oblk = out + (size_t)blockIdx.x * kfrags * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < HOLD; ++i) {
+        const int f = w + kNormWaves * i;
+        if (f < kfrags) {
+            const uint4 gv = g[4 * f + q];
+            const uint32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+            const uint32_t ge[4] = {gv.x, gv.y, gv.z, gv.w};
+            uint4 o;
+            o.x = pack2bf(bf_lo(e[0]) * rs * bf_lo(ge[0]), bf_hi(e[0]) * rs * bf_hi(ge[0]));
+            o.y = pack2bf(bf_lo(e[1]) * rs * bf_lo(ge[1]), bf_hi(e[1]) * rs * bf_hi(ge[1]));
+            o.z = pack2bf(bf_lo(e[2]) * rs * bf_lo(ge[2]), bf_hi(e[2]) * rs * bf_hi(ge[2]));
+            o.w = pack2bf(bf_lo(e[3]) * rs * bf_lo(ge[3]), bf_hi(e[3]) * rs * bf_hi(ge[3]));
+            oblk[(size_t)f * 64] = o;
+        }
+    }
+}
+
+// Row-per-wave form for wider rows: two passes, the second re-reads the row from L1/L2.
 __global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint4 *__restrict__ x,
                                                            const uint4 *__restrict__ g,
                                                            uint4 *__restrict__ out, int rows, int H,
@@ -90,6 +157,8 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint4 *__restri
     if (row >= rows) return;
     const int chunks = H >> 3;
     const uint4 *xr = x + (size_t)row * chunks;
+    const int kfrags = H >> 5;
+    uint4 *orow = out + (size_t)(row >> 4) * kfrags * 64 + (row & 15);   // + (c >> 2) * 64 + 16 * (c & 3)
     float ss = 0.f;
     for (int c = lane; c < chunks; c += 64) {
         uint4 v = xr[c];
@@ -103,7 +172,6 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint4 *__restri
     }
     ss = wave_sum(ss);
     const float r = 1.0f / sqrtf(ss / (float)H + eps);
-    const int kfrags = H >> 5;
     for (int c = lane; c < chunks; c += 64) {
         uint4 v = xr[c], gv = g[c];
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -112,8 +180,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint4 *__restri
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             o[j] = pack2bf(bf_lo(w[j]) * r * bf_lo(gw[j]), bf_hi(w[j]) * r * bf_hi(gw[j]));
-        size_t dst = (((size_t)(row >> 4) * kfrags + (c >> 2)) * 64) + (row & 15) + 16 * (c & 3);
-        out[dst] = make_uint4(o[0], o[1], o[2], o[3]);
+        orow[(size_t)(c >> 2) * 64 + 16 * (c & 3)] = make_uint4(o[0], o[1], o[2], o[3]);
     }
 }
 
@@ -138,7 +205,19 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, in
 {
     if (rows <= 0) return hipSuccess;
     dim3 grid((rows + 3) / 4), block(256);
-    if (dtype == DT_BF16)
+    if (dtype == DT_BF16 && H <= 8192) {
+        const dim3 g16((rows + 15) / 16), b512(512);
+        const int per_wave = ((H >> 5) + kNormWaves - 1) / kNormWaves;
+#define CCS_NORM_BLOCK(HOLD)                                                                              \
+    hipLaunchKernelGGL(rmsnorm_bf16_block_kernel<HOLD>, g16, b512, 0, st, (const uint4 *)x, (const uint4 *)g, \
+                       (uint4 *)out, rows, H, eps)
+        if (per_wave <= 8) CCS_NORM_BLOCK(8);
+        else if (per_wave <= 16) CCS_NORM_BLOCK(16);
+        else if (per_wave <= 24) CCS_NORM_BLOCK(24);
+        else CCS_NORM_BLOCK(32);
+#undef CCS_NORM_BLOCK
+    }
+    else if (dtype == DT_BF16)
         hipLaunchKernelGGL(rmsnorm_bf16_kernel, grid, block, 0, st, (const uint4 *)x, (const uint4 *)g,
                            (uint4 *)out, rows, H, eps);
     else

@@ -69,7 +69,7 @@ def bench_layer(args, name):
     H, d, nq, nkv, I = cfg.hidden, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads, cfg.intermediate
     lens = inp.lens.astype(np.int64)
     n_tok = int(cfg.n_seqs if decode else lens.sum())          # tokens the step produces / processes
-    rows = cfg.n_seqs * (1 if decode else cfg.seq_pad)          # rows the kernels execute
+    rows = cfg.n_seqs if decode else n_tok                      # rows the kernels execute (a bf16 prefill drops the padding)
     arena = m.arena_bytes
     shapes = {"gemm_qkv": ((nq + 2 * nkv) * d, H), "gemm_o": (H, nq * d), "gemm_gu": (2 * I, H), "gemm_down": (H, I)}
     if decode:
@@ -196,7 +196,7 @@ def bench_layer(args, name):
         roof = {"kernel": "gemm_tiled_dma_kernel<128,3> (gate/up + SwiGLU)", "bound": "mfma",
                 "achieved": round(fl / dom_s / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(fl / dom_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(name),
-                "algorithmic_flops_per_launch": fl, "rows_executed": rows, "rows_valid": n_tok}
+                "algorithmic_flops_per_launch": fl, "rows_executed": rows, "rows_padded_batch": cfg.n_seqs * cfg.seq_pad}
     roof["avg_launch_us"] = round(dom_s * 1e6, 2)
     roof["launches_timed"] = dom_n
 

@@ -101,8 +101,10 @@ typedef struct ccs_weights {
 
 /* One batch (or one contiguous slice of it).
  *   PREFILL: x, y are [n_seqs, seq_pad, hidden]; lens[b] in [1, seq_pad] is the prompt length,
- *            rows t >= lens[b] are padding: never read as keys, their y rows are unspecified
- *            (finite).  If k_cache/v_cache are non-null the rotated keys and the values of
+ *            rows t >= lens[b] are padding: never read (bf16 modules gather the valid rows
+ *            into a dense matrix and compute those alone); their y rows are written as zeros
+ *            by bf16 modules and hold unspecified finite values for fp32 modules.
+ *            If k_cache/v_cache are non-null the rotated keys and the values of
  *            positions < lens[b] are stored there (cache_cap >= lens[b]).
  *   DECODE:  x, y are [n_seqs, hidden]; lens[b] >= 0 is the number of cached positions; the
  *            new token is position lens[b]: its key/value are stored at slot lens[b] and the
@@ -221,7 +223,9 @@ typedef enum ccs_stage {
     CCS_ST_GEMM_DOWN = 11, CCS_ST_GEMM_DOWN_REDUCE = 12,
     CCS_ST_PACK_X = 13,
     CCS_ST_CLONE = 14,
-    CCS_N_STAGES = 15
+    CCS_ST_COMPACT = 15,   /* bf16 prefill: valid rows of the padded batch gathered into dense rows */
+    CCS_ST_EXPAND = 16,    /* ... and the output rows put back, padded rows zeroed */
+    CCS_N_STAGES = 17
 } ccs_stage;
 
 /* Per-kernel timing (the paper's Monitor gathers latencies with event timers, Section 5

@@ -18,7 +18,7 @@ CCS_PREFILL, CCS_DECODE, CCS_ROWS = 0, 1, 2
 CCS_MAX_REPLICAS = 16
 STAGES = ("rmsnorm1", "gemm_qkv", "gemm_qkv_reduce", "rope", "attn", "attn_combine", "gemm_o",
           "gemm_o_reduce", "rmsnorm2", "gemm_gu", "gemm_gu_reduce", "gemm_down", "gemm_down_reduce",
-          "pack_x", "clone")
+          "pack_x", "clone", "compact", "expand")
 CCS_N_STAGES = len(STAGES)
 _STATUS = {0: "CCS_OK", -1: "CCS_EINVAL", -2: "CCS_ESTATE", -3: "CCS_ENOMEM",
            -4: "CCS_EUNSUPPORTED", -5: "CCS_EHIP"}

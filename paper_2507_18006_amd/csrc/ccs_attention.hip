@@ -154,7 +154,7 @@ __device__ __forceinline__ f32x4_t pf_mfma(const u32x4_t &a, const u32x4_t &b, f
 
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
     const bf16_t *__restrict__ qkv, const uint4 *__restrict__ Kp, const uint4 *__restrict__ VTp,
-    bf16_t *__restrict__ out, int nq, int nkv, int seq_pad, int S32, const int32_t *__restrict__ lens)
+    bf16_t *__restrict__ out, int nq, int nkv, int S32, const int32_t *__restrict__ offs)
 {
     extern __shared__ uint4 lds[];
     const int b = blockIdx.z, h = blockIdx.y, qb = gridDim.x - 1 - blockIdx.x;  // long blocks first
@@ -163,19 +163,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
     const int g = lane >> 4, c16 = lane & 15;
     const int q_start = qb * 128;
     const int ofrags = (nq * 128) >> 5;
-    const size_t row0 = (size_t)b * seq_pad;
-    if (q_start >= lens[b]) {
-        // nothing but padding in this block: defined (zero) output, no work
-        for (int idx = tid; idx < 128 * 32; idx += 256) {
-            const int t = q_start + (idx >> 5);
-            if (t < seq_pad) *(uint2 *)(out + packed_index((int)(row0 + t), h * 128 + (idx & 31) * 4, ofrags)) = make_uint2(0, 0);
-        }
-        return;
-    }
+    const size_t row0 = (size_t)offs[b];                                 // rows are dense: sequence b starts at offs[b]
+    const int len = offs[b + 1] - offs[b];
+    if (q_start >= len) return;                                          // no query of this sequence here
     const int q0w = q_start + wave * 32;                                // first query row of this wavefront
-    const int last_q = min(q_start + 127, seq_pad - 1);
+    const int last_q = min(q_start + 127, len - 1);
     const int nkb = (last_q >> 5) + 1;                                   // key blocks the workgroup walks
-    const int my_blocks = (q0w < seq_pad) ? (q0w >> 5) + 1 : 0;          // key blocks this wavefront multiplies
+    const int my_blocks = (q0w < len) ? (q0w >> 5) + 1 : 0;              // key blocks this wavefront multiplies
     const int kvh = h / (nq / nkv);
     const uint4 *kbase = Kp + ((size_t)b * nkv + kvh) * S32 * 16 + lane;   // 16 uint4 per key
     const uint4 *vbase = VTp + ((size_t)b * nkv + kvh) * S32 * 16 + lane;
@@ -196,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
     u32x4_t qf[2][4];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
-        const int t = min(q0w + qt * 16 + c16, seq_pad - 1);
+        const int t = min(q0w + qt * 16 + c16, len - 1);
         const bf16_t *qrow = qkv + (row0 + t) * width + (size_t)h * 128 + g * 8;
 #pragma unroll
         for (int dblk = 0; dblk < 4; ++dblk) {
@@ -305,7 +299,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
         l += __shfl_xor(l, 32, 64);
         const float inv = 1.0f / l;
         const int t = q0w + qt * 16 + c16;
-        if (t >= seq_pad) continue;
+        if (t >= len) continue;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
             const f32x4_t a = o[qt][dt];
@@ -316,15 +310,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
 }
 
 hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void *vtp, void *out_packed,
-                                    int n_seqs, int seq_pad, int nq, int nkv, const int32_t *lens_dev,
-                                    hipStream_t st)
+                                    int n_seqs, int seq_pad, int nq, int nkv, const int32_t *offs, hipStream_t st)
 {
     if (n_seqs <= 0) return hipSuccess;
     const int S32 = (seq_pad + 31) / 32 * 32;
     const size_t smem = (size_t)kPfStages * kPfStageU4 * 16;
     dim3 grid((seq_pad + 127) / 128, nq, n_seqs);
     hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(256), smem, st, (const bf16_t *)qkv, (const uint4 *)kp,
-                       (const uint4 *)vtp, (bf16_t *)out_packed, nq, nkv, seq_pad, S32, lens_dev);
+                       (const uint4 *)vtp, (bf16_t *)out_packed, nq, nkv, S32, offs);
     return hipGetLastError();
 }
 

@@ -227,6 +227,73 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, in
 }
 
 // ---------------------------------------------------------------------------------------------
+// Prefill without the padding (bf16): the valid rows of a right-padded batch [n_seqs, seq_pad, H]
+// are moved into one dense [sum len, H] matrix, sequence after sequence, before the first layer,
+// and moved back (padded rows written as zeros) after the last; every kernel in between works on
+// valid rows only.  offs[b] = number of valid rows before sequence b, from the device copy of the
+// lengths clamped into [0, seq_pad], and capped at `total`, the row count the host sized the dense
+// buffers for from its own copy of the lengths.  Every later kernel takes a sequence's length as
+// offs[b + 1] - offs[b], so no dense row index can reach `total` even if the two copies disagree.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prefill_offsets_kernel(const int32_t *__restrict__ lens, int n_seqs,
+                                                              int seq_pad, int total, int32_t *__restrict__ offs)
+{
+    __shared__ int part[256];
+    const int per = (n_seqs + 255) / 256;
+    const int lo = min(n_seqs, (int)threadIdx.x * per), hi = min(n_seqs, lo + per);
+    int s = 0;
+    for (int i = lo; i < hi; ++i) s += min(max(lens[i], 0), seq_pad);
+    part[threadIdx.x] = s;
+    __syncthreads();
+    int before = 0;
+    for (int t = 0; t < (int)threadIdx.x; ++t) before += part[t];
+    for (int i = lo; i < hi; ++i) {
+        offs[i] = min(before, total);
+        before += min(max(lens[i], 0), seq_pad);
+    }
+    if (hi == n_seqs && lo < n_seqs) offs[n_seqs] = min(before, total);
+}
+
+// n_seqs x ceil(seq_pad / 4) workgroups, one wavefront per row.  expand = 0: dense[offs[b] + s] = padded[b, s]
+// for s < len_b; expand = 1: padded[b, s] = dense[offs[b] + s] for s < len_b, zero otherwise.
+__global__ __launch_bounds__(256) void prefill_rows_kernel(uint4 *__restrict__ padded, uint4 *__restrict__ dense,
+                                                           const int32_t *__restrict__ offs, int seq_pad,
+                                                           int chunks, int expand)
+{
+    const int per_seq = (seq_pad + 3) >> 2;
+    const int b = blockIdx.x / per_seq, s = (blockIdx.x % per_seq) * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (s >= seq_pad) return;
+    const int len = offs[b + 1] - offs[b];
+    uint4 *prow = padded + ((size_t)b * seq_pad + s) * chunks;
+    uint4 *drow = dense + (size_t)(offs[b] + min(s, max(len - 1, 0))) * chunks;
+    if (!expand) {
+        if (s < len)
+            for (int c = lane; c < chunks; c += 64) drow[c] = ld_stream(prow + c);
+    } else if (s < len) {
+        for (int c = lane; c < chunks; c += 64) st_stream(prow + c, drow[c]);
+    } else {
+        for (int c = lane; c < chunks; c += 64) st_stream(prow + c, make_uint4(0, 0, 0, 0));
+    }
+}
+
+hipError_t launch_prefill_offsets(const int32_t *lens_dev, int n_seqs, int seq_pad, int total, int32_t *offs,
+                                  hipStream_t st)
+{
+    if (n_seqs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(prefill_offsets_kernel, dim3(1), dim3(256), 0, st, lens_dev, n_seqs, seq_pad, total, offs);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_rows(void *padded, void *dense, const int32_t *offs, int n_seqs, int seq_pad, int H,
+                               bool expand, hipStream_t st)
+{
+    if (n_seqs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(prefill_rows_kernel, dim3((unsigned)n_seqs * ((seq_pad + 3) / 4)), dim3(256), 0, st, (uint4 *)padded,
+                       (uint4 *)dense, offs, seq_pad, H / 8, expand ? 1 : 0);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // Rotary embedding + KV-cache append.  One workgroup per row, thread i owns the pair
 // (i, i + d/2) of every head; the angle pos * base^(-2i/d) and its sine/cosine are evaluated
 // in fp64 once per thread and applied in fp32.
@@ -282,13 +349,15 @@ __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, i
 // One workgroup = (sequence, block of 32 positions, group of 8 head slots); thread = (position,
 // 8 consecutive d of the first half + their partners 64 up), so every global access is 16 bytes:
 // q in place, K straight into packed chunks, V through a 32 x 128 LDS tile that is read back
-// transposed.  Positions >= seq_pad (S32 = seq_pad rounded up to 32) write zeros, so that
-// masked products stay finite.  Optionally fills the row-major caches.
+// transposed.  The rows are dense (sequence b = rows offs[b] .. offs[b + 1] - 1 of qkv); only
+// blocks that hold a valid position are written, and positions past the sequence's length inside
+// the last block write zeros, so that masked products stay finite.  Optionally fills the
+// row-major caches.
 constexpr int kRopeHeadsPerGroup = 8;
 
 __global__ __launch_bounds__(256) void rope_pack_prefill_kernel(
     bf16_t *__restrict__ qkv, bf16_t *__restrict__ kp, bf16_t *__restrict__ vtp, int nq, int nkv,
-    const float2 *__restrict__ tab, int seq_pad, int S32, int groups, const int32_t *__restrict__ lens,
+    const float2 *__restrict__ tab, int S32, int groups, const int32_t *__restrict__ offs,
     bf16_t *__restrict__ k_cache, bf16_t *__restrict__ v_cache, int cap)
 {
     __shared__ bf16_t vt[32][128 + 2];
@@ -297,12 +366,14 @@ __global__ __launch_bounds__(256) void rope_pack_prefill_kernel(
     const int kb = rem / groups, hg = rem % groups;
     const int tid = threadIdx.x, pl = tid >> 3, c = tid & 7;
     const int pos = kb * 32 + pl;
-    const bool valid = pos < seq_pad;
-    const bool store = valid && (k_cache != nullptr) && (pos < lens[seq]) && (pos < cap);
+    const int len = offs[seq + 1] - offs[seq];
+    if (kb * 32 >= len) return;   // the attention kernel reads key blocks up to the one holding key len - 1
+    const bool valid = pos < len;
+    const bool store = valid && (k_cache != nullptr) && (pos < cap);
     const int slots = nq + 2 * nkv, width = slots * 128;
     const int h_lo = hg * kRopeHeadsPerGroup, h_hi = min(slots, h_lo + kRopeHeadsPerGroup);
     const size_t head_elems = (size_t)S32 * 128;
-    bf16_t *row = qkv + ((size_t)seq * seq_pad + (valid ? pos : 0)) * width;
+    bf16_t *row = qkv + ((size_t)offs[seq] + (valid ? pos : 0)) * width;
 
     float cs[8], sn[8];
     if (h_lo < nq + nkv) {
@@ -368,15 +439,15 @@ __global__ __launch_bounds__(256) void rope_pack_prefill_kernel(
 }
 
 hipError_t launch_rope_pack_prefill(void *qkv, void *kp, void *vtp, int n_seqs, int seq_pad, int nq, int nkv,
-                                    const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
+                                    const void *tab, const int32_t *offs, void *k_cache, void *v_cache, int cap,
                                     hipStream_t st)
 {
     if (n_seqs <= 0) return hipSuccess;
     const int S32 = (seq_pad + 31) / 32 * 32;
     const int groups = (nq + 2 * nkv + kRopeHeadsPerGroup - 1) / kRopeHeadsPerGroup;
     hipLaunchKernelGGL(rope_pack_prefill_kernel, dim3(n_seqs * (S32 / 32) * groups), dim3(256), 0, st, (bf16_t *)qkv,
-                       (bf16_t *)kp, (bf16_t *)vtp, nq, nkv, (const float2 *)tab, seq_pad, S32, groups, lens_dev,
-                       (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
+                       (bf16_t *)kp, (bf16_t *)vtp, nq, nkv, (const float2 *)tab, S32, groups, offs, (bf16_t *)k_cache,
+                       (bf16_t *)v_cache, cap);
     return hipGetLastError();
 }
 

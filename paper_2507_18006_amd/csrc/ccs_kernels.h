@@ -45,11 +45,22 @@ hipError_t launch_rmsnorm_rows(const void *x, const void *g, void *out, int rows
 hipError_t launch_rope(int dtype, void *qkv, int rows, int nq, int nkv, int d, const void *tab,
                        int decode, int seq_pad, const int32_t *lens_dev, void *k_cache,
                        void *v_cache, int cap, hipStream_t st);
-// bf16 prefill with head_dim 128: rotate q in place and emit K (fragment-packed per kv head) and
-// V (transposed, in the key order of the MFMA prefill-attention kernel) into kp / vtp, each
-// n_seqs * nkv * S32 * 128 elements, S32 = seq_pad rounded up to 32; optional row-major caches.
+// bf16 prefill without padding: offs[b] = valid rows before sequence b (n_seqs + 1 entries), from
+// the device copy of the lengths clamped into [0, seq_pad] and capped at `total` (the dense row
+// count the host planned for); the kernels below take len_b = offs[b + 1] - offs[b].
+// launch_prefill_rows moves the valid rows of a padded [n_seqs, seq_pad, H] batch into a dense
+// [offs[n_seqs], H] matrix (expand = false) or back, writing the padded rows as zeros (expand = true).
+hipError_t launch_prefill_offsets(const int32_t *lens_dev, int n_seqs, int seq_pad, int total, int32_t *offs,
+                                  hipStream_t st);
+hipError_t launch_prefill_rows(void *padded, void *dense, const int32_t *offs, int n_seqs, int seq_pad, int H,
+                               bool expand, hipStream_t st);
+// bf16 prefill with head_dim 128 on dense rows (sequence b = rows offs[b] .. offs[b] + len_b - 1 of
+// qkv): rotate q in place and emit K (fragment-packed per kv head) and V (transposed, in the key
+// order of the MFMA prefill-attention kernel) into kp / vtp, each n_seqs * nkv * S32 * 128
+// elements, S32 = seq_pad rounded up to 32, for the 32-key blocks that hold a valid key (keys
+// past len_b inside the last block are written as zeros); optional row-major caches.
 hipError_t launch_rope_pack_prefill(void *qkv, void *kp, void *vtp, int n_seqs, int seq_pad, int nq, int nkv,
-                                    const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache, int cap,
+                                    const void *tab, const int32_t *offs, void *k_cache, void *v_cache, int cap,
                                     hipStream_t st);
 // f32 path: u[t,j] = silu(gu[t,j]) * gu[t, I + j], gu row-major [rows, 2I].
 hipError_t launch_swiglu_f32(const float *gu, float *u, int rows, int I, hipStream_t st);
@@ -102,13 +113,11 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
 hipError_t launch_attn_generic(int dtype, const void *qkv, void *out, int rows, int nq, int nkv,
                                int d, int decode, int seq_pad, const int32_t *lens_dev,
                                const void *k_cache, const void *v_cache, int cap, hipStream_t st);
-// bf16, head_dim 128 causal prefill attention on the matrix cores: q rows from qkv (rotated, row
-// major), keys/values from the kp / vtp buffers of launch_rope_pack_prefill; output fragment
-// packed [rows16, nq*128].  Rows of 128-row query blocks that start at or after lens[b] are
-// written as zero; other padded rows hold finite don't-care values.
+// bf16, head_dim 128 causal prefill attention on the matrix cores over dense rows: q rows from
+// qkv (rotated, row major, sequence b at rows offs[b]..), keys/values from the kp / vtp buffers of
+// launch_rope_pack_prefill; output fragment packed [rows16, nq*128] at the same dense rows.
 hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void *vtp, void *out_packed,
-                                    int n_seqs, int seq_pad, int nq, int nkv, const int32_t *lens_dev,
-                                    hipStream_t st);
+                                    int n_seqs, int seq_pad, int nq, int nkv, const int32_t *offs, hipStream_t st);
 // bf16, head_dim 128 decode attention with split-KV partials (fp32) and an ordered combine.
 size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap);
 hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs, int nq, int nkv,

@@ -55,7 +55,7 @@ struct ArenaPlan {
 };
 
 struct WsPlan {
-    size_t h, qkv, a, x1, gu, u, xp, kp, vtp, xa, xb, scratch, scratch_bytes, total;  // xa, xb: activations between layers of a run
+    size_t h, qkv, a, x1, gu, u, xp, kp, vtp, xa, xb, xc, yc, offs, scratch, scratch_bytes, total;  // xa, xb: activations between layers of a run; xc, yc, offs: dense prefill rows in / out and their per-sequence offsets
 };
 
 int check_desc(const ccs_module_desc *D, Dims *out)
@@ -154,6 +154,9 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
             const size_t s32 = align_up((size_t)prefill_seq_pad, 32);
             p.kp = take((size_t)n_seqs * d.nkv * s32 * d.d * 2);
             p.vtp = take((size_t)n_seqs * d.nkv * s32 * d.d * 2);
+            p.xc = take(rows * d.H * 2);   // the batch's valid rows without the padding, and the output before it is padded again
+            p.yc = take(rows * d.H * 2);
+            p.offs = take(((size_t)n_seqs + 1) * 4);
         }
         if (d.L > 1) {
             p.xa = take(rows * d.H * 2);
@@ -317,6 +320,20 @@ int check_batch(const ccs_module *m, const ccs_batch *b)
     return CCS_OK;
 }
 
+// Rows the kernels work on: for a bf16 prefill the sum of the (validated) lengths, otherwise
+// every row of the batch.
+long long valid_rows(const ccs_batch *b)
+{
+    long long t = 0;
+    for (int i = 0; i < b->n_seqs; ++i) t += b->lens_host[i] < b->seq_pad ? b->lens_host[i] : b->seq_pad;
+    return t;
+}
+long long batch_rows(const ccs_module *m, const ccs_batch *b)
+{
+    if (b->mode != CCS_PREFILL) return b->n_seqs;
+    return m->desc.dtype == CCS_BF16 ? valid_rows(b) : (long long)b->n_seqs * b->seq_pad;
+}
+
 // One replica, one slice.  variant_rows: row count that selects the GEMM variant (the full
 // batch's for a replicated forward, so that every replica count produces the same bits).
 int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows, bool on_caller_stream = false,
@@ -357,7 +374,9 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     const bool decode = b->mode == CCS_DECODE;
     const bool rows_mode = b->mode == CCS_ROWS;   // FFN block: independent token rows
     const int seq_pad = (decode || rows_mode) ? 1 : b->seq_pad;
-    const int T = b->n_seqs * seq_pad;
+    // bf16 prefill drops the padding: the kernels see the sum of the lengths as one dense row range
+    const bool dense = bf && !decode && !rows_mode;
+    const int T = dense ? (int)valid_rows(b) : b->n_seqs * seq_pad;
     WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, (decode || rows_mode) ? 0 : seq_pad, (long)variant_rows);
     if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
@@ -366,11 +385,18 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     // A run of layers: layer l reads x_in and writes x_out, ping-ponging between two workspace
     // buffers; the first layer reads the batch's x, the last writes its y (Section 3.1: inside a
     // run of consecutive layers nothing is scattered or gathered).
+    const int32_t *offs = (const int32_t *)(ws + p.offs);
+    if (dense) {
+        CCS_STAGE(CCS_ST_COMPACT, launch_prefill_offsets(b->lens_dev, b->n_seqs, seq_pad, T, (int32_t *)(ws + p.offs), st));
+        CCS_STAGE(CCS_ST_COMPACT, launch_prefill_rows(const_cast<void *>(b->x), ws + p.xc, offs, b->n_seqs, seq_pad, d.H, false, st));
+    }
     bool h_ready = false;   // h already holds RMSNorm_1 of x_in (fused into the previous layer's last reduction)
     for (int l = 0; l < d.L; ++l) {
         const char *A = A0 + (size_t)l * m->ap.layer;
-        const void *x_in = l == 0 ? b->x : (const void *)(ws + ((l & 1) ? p.xa : p.xb));
-        void *x_out = l == d.L - 1 ? b->y : (void *)(ws + ((l & 1) ? p.xb : p.xa));
+        const void *x_first = dense ? (const void *)(ws + p.xc) : b->x;
+        void *y_last = dense ? (void *)(ws + p.yc) : b->y;
+        const void *x_in = l == 0 ? x_first : (const void *)(ws + ((l & 1) ? p.xa : p.xb));
+        void *x_out = l == d.L - 1 ? y_last : (void *)(ws + ((l & 1) ? p.xb : p.xa));
         void *kc = b->k_cache ? (char *)b->k_cache + (size_t)l * (size_t)b->cache_layer_stride : nullptr;
         void *vc = b->v_cache ? (char *)b->v_cache + (size_t)l * (size_t)b->cache_layer_stride : nullptr;
         const bool last = l == d.L - 1;
@@ -412,13 +438,13 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
                 if (decode)
                     CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
                 else
-                    CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, b->lens_dev, kc, vc, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, offs, kc, vc, b->cache_cap, st));
             }
             if (decode) {
                 CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
                 CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
             } else {
-                CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, b->lens_dev, st));
+                CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, offs, st));
             }
             if (row_norm && ffn) {
                 // weight-streaming O projection; its reduction adds the residual and applies the second norm
@@ -458,6 +484,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             }
         }
     }
+    if (dense) CCS_STAGE(CCS_ST_EXPAND, launch_prefill_rows(b->y, ws + p.yc, offs, b->n_seqs, seq_pad, d.H, true, st));
     return CCS_OK;
 }
 
@@ -492,12 +519,11 @@ size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
     size_t need = ws_plan(desc, d, rows, max_seqs, max_cache_cap, skinny, false, layer ? max_seq_pad : 0).total;
     // smaller batches may split K in the tiled GEMM: the partial buffer grows with the split
     for (size_t v = 128; v < rows && v <= 4096; v += 128) {
-        const int seqs_v = (int)((v + max_seq_pad - 1) / max_seq_pad);
-        need = max_sz(need, ws_plan(desc, d, v, seqs_v, max_cache_cap, false, false, layer ? max_seq_pad : 0).total);
+        // (a bf16 prefill works on the valid rows only, so few rows can come with many sequences)
+        need = max_sz(need, ws_plan(desc, d, v, max_seqs, max_cache_cap, false, false, layer ? max_seq_pad : 0).total);
     }
     if (!skinny) {
-        const int small_seqs = max_seqs < ccs::kSkinnyMaxRows ? max_seqs : ccs::kSkinnyMaxRows;
-        need = max_sz(need, ws_plan(desc, d, ccs::kSkinnyMaxRows, small_seqs, max_cache_cap, true, false, layer ? 64 : 0).total);
+        need = max_sz(need, ws_plan(desc, d, ccs::kSkinnyMaxRows, max_seqs, max_cache_cap, true, false, layer ? max_seq_pad : 0).total);
     }
     if (layer && max_cache_cap > 0) {
         const bool dsk = max_seqs <= ccs::kSkinnyMaxRows;
@@ -677,8 +703,7 @@ int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice)
     if (replica >= m->k) return fail(CCS_ESTATE, "replica %d is not instantiated (module has %d)", replica, m->k);
     int rc = check_batch(m, slice);
     if (rc != CCS_OK) return rc;
-    const long long rows = (long long)slice->n_seqs * (slice->mode == CCS_PREFILL ? slice->seq_pad : 1);
-    return forward_one(m, replica, slice, rows);
+    return forward_one(m, replica, slice, batch_rows(m, slice));
 }
 
 // Slice j = sequences [bounds[j], bounds[j + 1]) on replica j; slice 0 on the caller's stream.
@@ -689,7 +714,7 @@ static int forward_bounds(ccs_module *m, const ccs_batch *full, const long long 
     if (n == 0) return CCS_OK;
     const bool prefill = full->mode == CCS_PREFILL;
     const long long rows_per_seq = prefill ? full->seq_pad : 1;
-    const long long full_rows = n * rows_per_seq;
+    const long long full_rows = batch_rows(m, full);   // selects the kernel variants of every slice
     const Dims &d = m->dims;
     const size_t esz = d.esz;
     const size_t x_row = (m->desc.kind == CCS_LINEAR ? (size_t)d.in_f : (size_t)d.H) * esz;

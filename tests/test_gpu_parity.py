@@ -94,6 +94,57 @@ def test_bf16_prefill_scaled_ragged():
     run_case(gqa, [1, 3], seed=6)
 
 
+def test_bf16_prefill_drops_the_padding_and_writes_it_back_as_zeros():
+    """The bf16 prefill gathers the valid rows into a dense matrix (here 222 of 525 rows, neither a
+    multiple of 16) and works on those alone.  Lengths sit on the edges of the attention's 32-key
+    blocks and 128-query blocks; the output's padded rows must come back as zeros (the oracle's
+    convention), also where the caller's buffer held NaNs."""
+    cfg = workloads.scaled(C["C3"], hidden=1024, n_q_heads=8, n_kv_heads=4, intermediate=2752,
+                           n_seqs=7, seq_pad=75, len_lo=1, len_hi=75)
+    w = workloads.make_weights(cfg, 11)
+    inp = workloads.make_inputs(cfg, 11)
+    inp.lens[:] = [1, 75, 33, 2, 64, 31, 16]
+    ref = U.oracle_forward(cfg, 11, w, inp)
+    mask = U.valid_mask(cfg, inp.lens)
+    assert not ref[~mask].any()
+    base = None
+    for k in (1, 2, 3):
+        say(f"[case] dense prefill lens={list(inp.lens)} k={k}")
+        m = U.make_module(cfg, w)
+        try:
+            m.replicate(k)
+            db = U.DeviceBatch(m, cfg, inp)
+            db.y.fill_(float("nan"))
+            m.forward_split(db.batch)
+            y = db.out()
+        finally:
+            m.destroy()
+        assert U.rel_err(y, ref, mask) <= TOL["bf16"]
+        assert not y[~mask].any(), "padded rows must be written as zeros"
+        base = y if base is None else base
+        assert np.array_equal(y, base), f"k={k} differs from k=1"
+
+
+def test_bf16_prefill_device_lengths_that_disagree_with_the_host_stay_in_bounds():
+    """The dense buffers are sized from the host copy of the lengths; a device copy that claims
+    more rows is cut off at that size (the result is then unspecified, but every access stays
+    inside the buffers and the call completes)."""
+    cfg = workloads.scaled(C["C3"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752,
+                           n_seqs=3, seq_pad=40, len_lo=3, len_hi=9)
+    w = workloads.make_weights(cfg, 12)
+    inp = workloads.make_inputs(cfg, 12)
+    m = U.make_module(cfg, w)
+    try:
+        db = U.DeviceBatch(m, cfg, inp)
+        db.lens_dev.fill_(cfg.seq_pad)          # device says 40 valid rows per sequence, the host 3..9
+        say("[case] prefill with device lengths larger than the host's")
+        m.forward_split(db.batch)
+        y = db.out()
+    finally:
+        m.destroy()
+    assert np.isfinite(y).all()
+
+
 def test_bf16_linear_rows_across_variants():
     base = workloads.scaled(C["C5"], in_features=2752, out_features=1024)
     for n in (1, 15, 64, 65, 130, 300):       # weight-streaming up to 64 rows, tiled above

@@ -145,6 +145,36 @@ def test_bf16_prefill_device_lengths_that_disagree_with_the_host_stay_in_bounds(
     assert np.isfinite(y).all()
 
 
+def test_bf16_long_sequences_prefill_and_decode():
+    """Long streams through the attention kernels: a 2048-token prompt walks 64 key blocks of the
+    prefill ring next to a 5-token one; a decode step with 20000 cached keys spreads one sequence
+    over 157 chunks per kv head next to an empty and a one-chunk cache."""
+    pre = workloads.scaled(C["C3"], hidden=512, n_q_heads=4, n_kv_heads=2, intermediate=1408,
+                           n_seqs=2, seq_pad=2048, len_lo=2048, len_hi=2048)
+    w = workloads.make_weights(pre, 21)
+    inp = workloads.make_inputs(pre, 21)
+    inp.lens[:] = [2048, 5]
+    ref = U.oracle_forward(pre, 21, w, inp)
+    mask = U.valid_mask(pre, inp.lens)
+    say("[case] prefill lens=[2048, 5]")
+    y1 = U.gpu_forward(pre, 1, 21, w, inp)
+    y2 = U.gpu_forward(pre, 2, 21, w, inp)
+    assert U.rel_err(y1, ref, mask) <= TOL["bf16"]
+    assert np.array_equal(y1, y2)
+
+    dec = workloads.scaled(C["C4"], hidden=512, n_q_heads=8, n_kv_heads=2, intermediate=1408,
+                           n_seqs=3, len_lo=20000, len_hi=20000)
+    w = workloads.make_weights(dec, 22)
+    inp = workloads.make_inputs(dec, 22)
+    inp.lens[:] = [20000, 0, 100]
+    ref = U.oracle_forward(dec, 22, w, inp)
+    say("[case] decode lens=[20000, 0, 100]")
+    y1 = U.gpu_forward(dec, 1, 22, w, inp)
+    y3 = U.gpu_forward(dec, 3, 22, w, inp)
+    assert U.rel_err(y1, ref) <= TOL["bf16"]
+    assert np.array_equal(y1, y3)
+
+
 def test_bf16_linear_rows_across_variants():
     base = workloads.scaled(C["C5"], in_features=2752, out_features=1024)
     for n in (1, 15, 64, 65, 130, 300):       # weight-streaming up to 64 rows, tiled above

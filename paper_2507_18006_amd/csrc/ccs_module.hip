@@ -236,6 +236,13 @@ int make_event(hipEvent_t *ev)
     return CCS_OK;
 }
 
+void drop_events(Replica &R)
+{
+    if (R.ready) (void)hipEventDestroy(R.ready);
+    if (R.done) (void)hipEventDestroy(R.done);
+    R.ready = R.done = nullptr;
+}
+
 constexpr size_t kProfMaxPending = 1u << 16;
 
 ProfPair *prof_begin(ccs_module *m, Replica &R, int stage, hipStream_t st)
@@ -249,9 +256,13 @@ ProfPair *prof_begin(ccs_module *m, Replica &R, int stage, hipStream_t st)
         p.stage = stage;
         R.prof->pool.pop_back();
     } else if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) {
+        if (p.a) (void)hipEventDestroy(p.a);
         return nullptr;
     }
-    if (hipEventRecord(p.a, st) != hipSuccess) return nullptr;
+    if (hipEventRecord(p.a, st) != hipSuccess) {
+        R.prof->pool.push_back(p);   // keep the pair for a later launch
+        return nullptr;
+    }
     R.prof->pending.push_back(p);
     return &R.prof->pending.back();
 }
@@ -633,12 +644,18 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
     }
     Replica &R = m->rep[0];
     R.arena = arena0; R.ws = workspace0; R.ws_bytes = workspace_bytes; R.stream = st;
-    if (make_event(&R.ready) != CCS_OK || make_event(&R.done) != CCS_OK || make_event(&m->fork) != CCS_OK) {
+    auto drop = [&] {
+        drop_events(R);
+        if (m->fork) (void)hipEventDestroy(m->fork);
+        prof_free(R);
         delete m;
+    };
+    if (make_event(&R.ready) != CCS_OK || make_event(&R.done) != CCS_OK || make_event(&m->fork) != CCS_OK) {
+        drop();
         return CCS_EHIP;
     }
     e = hipEventRecord(R.ready, st);
-    if (e != hipSuccess) { delete m; return fail(CCS_EHIP, "hipEventRecord: %s", hipGetErrorString(e)); }
+    if (e != hipSuccess) { drop(); return fail(CCS_EHIP, "hipEventRecord: %s", hipGetErrorString(e)); }
     m->k = 1;
     *out = m;
     return CCS_OK;
@@ -675,17 +692,27 @@ int ccs_module_replicate(ccs_module *m, int32_t k, void *const *arenas, void *co
         Replica R;
         R.arena = arenas[j]; R.ws = workspaces[j]; R.ws_bytes = workspace_bytes; R.stream = (hipStream_t)streams[j];
         int rc = make_event(&R.ready);
-        if (rc != CCS_OK) return rc;
-        rc = make_event(&R.done);
-        if (rc != CCS_OK) return rc;
-        CCS_HIP(hipStreamWaitEvent(R.stream, m->rep[0].ready, 0));
-        {
-            hipStream_t st = R.stream;
-            CCS_STAGE(CCS_ST_CLONE, ccs::launch_clone(R.arena, m->rep[0].arena, m->ap.total, st));
+        if (rc == CCS_OK) rc = make_event(&R.done);
+        if (rc == CCS_OK) {
+            m->rep[j] = R;
+            m->k = j + 1;
+        } else {
+            drop_events(R);
+            return rc;
         }
-        CCS_HIP(hipEventRecord(R.ready, R.stream));
-        m->rep[j] = R;
-        m->k = j + 1;
+        Replica &N = m->rep[j];
+        auto undo = [&] { prof_free(N); drop_events(N); N = Replica(); m->k = j; };   // earlier new replicas stay
+        hipError_t e = hipStreamWaitEvent(N.stream, m->rep[0].ready, 0);
+        if (e == hipSuccess) {
+            ProfPair *pp = prof_begin(m, N, CCS_ST_CLONE, N.stream);
+            e = ccs::launch_clone(N.arena, m->rep[0].arena, m->ap.total, N.stream);
+            prof_end(pp, N.stream);
+        }
+        if (e == hipSuccess) e = hipEventRecord(N.ready, N.stream);
+        if (e != hipSuccess) {
+            undo();
+            return fail(CCS_EHIP, "cloning replica %d: %s", j, hipGetErrorString(e));
+        }
     }
     return CCS_OK;
 }

@@ -175,6 +175,40 @@ def test_bf16_long_sequences_prefill_and_decode():
     assert np.array_equal(y1, y3)
 
 
+def test_bf16_seeded_random_shapes():
+    """Seventy-two seeded random module shapes and batches inside the documented limits (hidden,
+    heads, GQA group, SwiGLU width, sequence counts, prompt lengths, cache lengths, replica counts,
+    runs of one to three layers, the attention and FFN halves), each against the oracle and across
+    replica counts."""
+    rng = np.random.default_rng(20250718)
+    for case in range(72):
+        nkv = int(rng.choice([1, 2, 3]))
+        g = int(rng.choice([1, 2, 4, 8]))
+        hidden = int(rng.choice([128, 256, 384, 512, 1024, 1536]))
+        inter = int(rng.choice([32, 352, 1408, 2752]))
+        layers = int(rng.choice([1, 1, 2, 3]))
+        ks = [1] + sorted(set(int(v) for v in rng.choice([2, 3, 4, 5], size=2)))
+        kind = str(rng.choice(["decoder_layer", "decoder_layer", "decoder_layer", "attn_block", "ffn_block"]))
+        if kind != "decoder_layer":
+            layers = 1
+        if kind == "ffn_block":
+            cfg = workloads.scaled(C["C2"], kind="ffn_block", mode="linear", hidden=hidden, n_q_heads=g * nkv,
+                                   n_kv_heads=nkv, intermediate=inter, n_seqs=int(rng.integers(1, 400)))
+        elif case % 2 == 0:
+            n_seqs, seq_pad = int(rng.integers(1, 7)), int(rng.integers(1, 131))
+            lo = int(rng.integers(1, seq_pad + 1))
+            cfg = workloads.scaled(C["C3"], kind=kind, hidden=hidden, n_q_heads=g * nkv, n_kv_heads=nkv,
+                                   intermediate=inter, n_seqs=n_seqs, seq_pad=seq_pad, len_lo=lo, len_hi=seq_pad,
+                                   n_layers=layers)
+        else:
+            n_seqs = int(rng.choice([1, 2, 7, 16, 33, 64, 65, 80]))
+            hi = int(rng.choice([0, 1, 127, 128, 129, 700]))
+            cfg = workloads.scaled(C["C4"], kind=kind, hidden=hidden, n_q_heads=g * nkv, n_kv_heads=nkv,
+                                   intermediate=inter, n_seqs=n_seqs, len_lo=0, len_hi=hi, n_layers=layers)
+        say(f"[random case {case}] kind={kind} hidden={hidden} heads={g * nkv}/{nkv} inter={inter} layers={layers}")
+        run_case(cfg, ks, seed=100 + case)
+
+
 def test_bf16_linear_rows_across_variants():
     base = workloads.scaled(C["C5"], in_features=2752, out_features=1024)
     for n in (1, 15, 64, 65, 130, 300):       # weight-streaming up to 64 rows, tiled above

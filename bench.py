@@ -95,9 +95,19 @@ def bench_layer(args, name):
         dt = time.perf_counter() - t0
         prof = [m.profile_read(j, reset=True) for j in range(k)]
         m.profile([])
+        # latency of single steps: HIP events on the caller's stream around fork ... join, one at a time
+        lat = []
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        for a, b in ev:
+            a.record()
+            m.forward_split(db.batch)
+            b.record()
+            torch.cuda.synchronize()
+        lat = sorted(a.elapsed_time(b) for a, b in ev)
+        latency[k] = {"p50": round(lat[len(lat) // 2] * 1e3, 1), "min": round(lat[0] * 1e3, 1)}
         return dt / K, prof
 
-    per_k = {}
+    per_k, latency = {}, {}
     # k = 1: the timed region also brackets the dominant kernel with HIP events on its stream
     per_k[1], prof1 = timed(1, (dominant,))
     dom_ms, dom_n = prof1[0][dominant]
@@ -201,7 +211,8 @@ def bench_layer(args, name):
     roof["launches_timed"] = dom_n
 
     def step_entry(k, t):
-        e = {"tokens_per_s": round(n_tok / t, 1), "ms_per_step": round(t * 1e3, 4)}
+        e = {"tokens_per_s": round(n_tok / t, 1), "ms_per_step": round(t * 1e3, 4),
+             "single_step_latency_us": latency[k]}
         if decode:
             b = k * arena + kv_bytes + act_bytes
             e["algorithmic_bytes"] = b

@@ -513,6 +513,19 @@ def test_empty_batches_more_replicas_than_sequences_and_errors():
         m.destroy()
 
 
+def test_maximum_replica_and_layer_counts():
+    """The two compile-time limits of the library: 16 instances of one module (20 sequences over
+    16 replicas: four slices of two, twelve of one) and a run of 128 layers (fp32, so that the
+    comparison stays tight over the depth)."""
+    cfg = workloads.scaled(C["C2"], hidden=512, n_q_heads=4, n_kv_heads=2, intermediate=1024, n_seqs=20,
+                           len_lo=0, len_hi=90)
+    run_case(cfg, [1, B.CCS_MAX_REPLICAS], seed=40)
+    deep = workloads.scaled(C["C1"], n_layers=128, n_seqs=2, seq_pad=8, len_lo=3, len_hi=8)
+    run_case(deep, [1, 2], seed=41)
+    dec = workloads.scaled(deep, mode="decode", seq_pad=1, n_seqs=3, len_lo=0, len_hi=12)
+    run_case(dec, [1, 3], seed=42)
+
+
 def test_forward_split_recorded_in_a_hip_graph_replays_like_eager():
     """forward_split only enqueues kernels and fork/join events, so a caller may capture it.
     Replays (with eager work and synchronisation between them, inputs changed in place) must

@@ -50,6 +50,26 @@ def test_arena_bytes_match_table1_weight_bytes(golden_dir):
     assert B.module_arena_bytes(run) == 3 * arena
 
 
+def test_arena_of_a_run_grows_like_table2_memory(golden_dir):
+    """Table 2: every further replicated LLaMA-13B layer takes 608 of the table's MB (the slope is
+    the same between all printed rows); a layer's weights are 605 MiB (Table 1), so the table's MB
+    are MiB and a layer carries about 3 MiB beside its weights.  The library's replica memory
+    per layer (the arena) must sit between the two figures."""
+    g = read_golden(os.path.join(golden_dir, "table2_scaling_cost.txt"))
+    t1 = read_golden(os.path.join(golden_dir, "table1_llama13b.txt"))
+    n = [int(v) for v in g["layers"].split()]
+    mem = [int(v) for v in g["replication_memory_mb"].split()]
+    slopes = {(mem[i + 1] - mem[i]) // (n[i + 1] - n[i]) for i in range(len(n) - 1)}
+    assert all((mem[i + 1] - mem[i]) % (n[i + 1] - n[i]) == 0 for i in range(len(n) - 1))
+    assert slopes == {608}
+    H, I, nh = int(t1["d_model"]), int(t1["d_ff"]), int(t1["n_heads"])
+    mib = 2 ** 20
+    for layers in n:
+        d = B.ModuleDesc(hidden=H, n_q_heads=nh, n_kv_heads=nh, head_dim=H // nh, intermediate=I, n_layers=layers)
+        per_layer = B.module_arena_bytes(d) / layers / mib
+        assert int(t1["decoder_layer_mib"]) <= per_layer <= 608
+
+
 def test_bad_descs_are_rejected_without_a_gpu():
     bad = B.ModuleDesc(hidden=4096, n_q_heads=32, n_kv_heads=5, head_dim=128, intermediate=11008)
     assert B.module_arena_bytes(bad) == 0 and b"n_kv" in B.lib().ccs_last_error()

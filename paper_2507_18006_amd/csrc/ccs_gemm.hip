@@ -438,7 +438,12 @@ __global__ __launch_bounds__(256, (BM == 128 && NST <= 3) ? 2 : 1) void gemm_til
     const int wn = wave & 1, wm = wave >> 1;
     // K segment of this workgroup (one segment unless the launch is split over K: then the
     // fp32 partial sums of segment `seg` go to part[seg][M][N] and a reduction kernel follows)
-    const int tile_id = blockIdx.x % tiles, seg = blockIdx.x / tiles;
+    // Workgroups go to the 8 XCDs round-robin by index and every XCD has its own L2: give XCD x a
+    // contiguous range of the (tile, K segment) list, so that the row tiles that share a weight
+    // panel run on one XCD at about the same time and the panel is fetched into one L2 once.
+    const int nwg = gridDim.x, xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3;
+    const int logical = xcd * (nwg >> 3) + min(xcd, nwg & 7) + in_xcd;
+    const int tile_id = logical % tiles, seg = logical / tiles;
     const int tm = tile_id % tiles_m, tn = tile_id / tiles_m;
     const int nb0 = tn * C::TN, mb0 = tm * C::TM;
     const int nblk = N >> 4, mblk = (M + 15) >> 4;

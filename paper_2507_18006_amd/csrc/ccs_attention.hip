@@ -154,10 +154,25 @@ __device__ __forceinline__ f32x4_t pf_mfma(const u32x4_t &a, const u32x4_t &b, f
 
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(
     const bf16_t *__restrict__ qkv, const uint4 *__restrict__ Kp, const uint4 *__restrict__ VTp,
-    bf16_t *__restrict__ out, int nq, int nkv, int S32, const int32_t *__restrict__ offs)
+    bf16_t *__restrict__ out, int nq, int nkv, int S32, int nqb, const int32_t *__restrict__ offs)
 {
     extern __shared__ uint4 lds[];
-    const int b = blockIdx.z, h = blockIdx.y, qb = gridDim.x - 1 - blockIdx.x;  // long blocks first
+    // Workgroups go to the 8 XCDs round-robin by index and every XCD has its own L2.  The (sequence,
+    // kv head) groups are dealt to the XCDs in turn and all workgroups of a group - its query
+    // blocks and the query heads that share the kv head - run on that XCD, so the group's keys and
+    // values are fetched into one L2 (when the number of groups is no multiple of 8 the list is
+    // walked in plain order).
+    const int G = nq / nkv, per_group = G * nqb, groups = (int)gridDim.x / per_group;
+    int grp, within;
+    if ((groups & 7) == 0) {
+        const int i = blockIdx.x >> 3;
+        grp = (blockIdx.x & 7) + 8 * (i / per_group);
+        within = i % per_group;
+    } else {
+        grp = blockIdx.x / per_group;
+        within = blockIdx.x % per_group;
+    }
+    const int b = grp / nkv, h = (grp % nkv) * G + within / nqb, qb = nqb - 1 - within % nqb;  // long blocks first
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c16 = lane & 15;
@@ -315,9 +330,10 @@ hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void 
     if (n_seqs <= 0) return hipSuccess;
     const int S32 = (seq_pad + 31) / 32 * 32;
     const size_t smem = (size_t)kPfStages * kPfStageU4 * 16;
-    dim3 grid((seq_pad + 127) / 128, nq, n_seqs);
+    const int nqb = (seq_pad + 127) / 128;   // 128-row query blocks per sequence
+    dim3 grid((unsigned)nqb * nq * n_seqs);
     hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(256), smem, st, (const bf16_t *)qkv, (const uint4 *)kp,
-                       (const uint4 *)vtp, (bf16_t *)out_packed, nq, nkv, S32, offs);
+                       (const uint4 *)vtp, (bf16_t *)out_packed, nq, nkv, S32, nqb, offs);
     return hipGetLastError();
 }
 

@@ -31,8 +31,9 @@ METRIC = "decoder-layer tokens/s (7B shape, k=1/2/4 replicas); module replicate 
 
 # HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` runs (FETCH_SIZE,
 # WRITE_SIZE) scaled by the same counters on the clone kernel of known size; see
-# profiles/decoder_layer_decode_C2_k1_pmc_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"C2": 547593038}
+# profiles/decoder_layer_decode_C2_k1_pmc_hbm_traffic.md and ..._prefill_C3_k1_pmc_hbm_traffic.md (C3: fabric
+# traffic into the L2s of the gate/up GEMM; most of it is served by the Infinity Cache).
+MEASURED_TRAFFIC_BYTES = {"C2": 547593038, "C3": 2839000000}
 
 
 def time_events(torch, fn, reps):

@@ -54,7 +54,7 @@ def bench_layer(args, name):
     import torch
     import workloads
     from paper_2507_18006_amd import binding as B
-    from tests import gpu_util as U
+    import harness as U
 
     cfg = workloads.CONFIGS[name]
     K, W = args.steps, args.warmup
@@ -257,7 +257,7 @@ def bench_bursty(args):
     import numpy as np
     import torch
     import workloads
-    from tests import gpu_util as U
+    import harness as U
 
     cfg = workloads.CONFIGS["C5"]
     counts = workloads.bursty_token_counts(0)

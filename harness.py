@@ -1,9 +1,12 @@
-"""Helpers shared by the GPU parity tests, smoke() and bench.py: run a workloads.Config through
-the HIP library (via the C ABI binding) and through the CPU oracle."""
+"""Glue shared by the GPU parity tests, smoke() and bench.py: run a workloads.Config through the
+HIP library (via the C ABI binding) and, for the comparison legs only, through the CPU oracle.
+
+The oracle is test infrastructure: it is imported inside the two functions that call it
+(`oracle_forward`, `oracle_desc`), never at module load, so a process that only runs the GPU
+path does not load it."""
 import numpy as np
 import torch
 
-import oracle
 import workloads
 from paper_2507_18006_amd import binding as B
 
@@ -20,7 +23,8 @@ def module_desc(cfg: workloads.Config) -> B.ModuleDesc:
                         rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, n_layers=cfg.n_layers)
 
 
-def oracle_desc(cfg: workloads.Config) -> oracle.LayerDesc:
+def oracle_desc(cfg: workloads.Config):
+    import oracle
     return oracle.LayerDesc(cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.intermediate,
                             cfg.rms_eps, cfg.rope_base)
 
@@ -96,6 +100,7 @@ def gpu_forward(cfg, k: int, seed: int = 0, weights=None, inputs=None, return_ca
 
 def oracle_forward(cfg, seed: int = 0, weights=None, inputs=None, seqs=None, return_caches=False):
     """The oracle on the same seeded inputs; `seqs` restricts it to some sequences / rows."""
+    import oracle
     w = workloads.make_weights(cfg, seed) if weights is None else weights
     inp = workloads.make_inputs(cfg, seed) if inputs is None else inputs
     sel = slice(None) if seqs is None else seqs
@@ -124,6 +129,41 @@ def valid_mask(cfg, lens, n_seqs=None):
     """Boolean [B, S] of rows that are part of the result (prefill: t < len)."""
     B_ = len(lens)
     return np.arange(cfg.seq_pad)[None, :] < np.asarray(lens)[:, None]
+
+
+def l2_err(y, ref, mask=None) -> float:
+    """||y - ref||_2 / ||ref||_2 over the rows that count (reported beside the max-error bar)."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if mask is not None:
+        y, ref = y[mask], ref[mask]
+    if ref.size == 0:
+        return 0.0
+    if not np.isfinite(y).all():
+        return float("inf")
+    n = np.linalg.norm(ref.ravel())
+    return float(np.linalg.norm((y - ref).ravel()) / n) if n > 0 else 0.0
+
+
+def row_rel_err(y, ref, mask=None) -> float:
+    """max over rows of max_c |y - ref| / max_c |ref|: every token row (decode: every sequence) is
+    held to the bar by its own magnitude, so a row whose result is small is not hidden behind a
+    large one elsewhere in the batch."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if mask is not None:
+        y, ref = y[mask], ref[mask]
+    y, ref = y.reshape(-1, y.shape[-1]), ref.reshape(-1, ref.shape[-1])
+    if ref.size == 0:
+        return 0.0
+    if not np.isfinite(y).all():
+        return float("inf")
+    den = np.abs(ref).max(axis=1)
+    num = np.abs(y - ref).max(axis=1)
+    ok = den > 0
+    if (num[~ok] > 0).any():
+        return float("inf")
+    return float((num[ok] / den[ok]).max()) if ok.any() else 0.0
 
 
 def rel_err(y, ref, mask=None) -> float:

@@ -115,22 +115,31 @@ class Inputs:
     v_cache: Optional[np.ndarray] = None
 
 
-def make_inputs(cfg: Config, seed: int = 0) -> Inputs:
+def make_inputs(cfg: Config, seed: int = 0, lens=None, x_std: float = 1.0, k_std: float = 1.0) -> Inputs:
+    """lens: fixed lengths instead of drawn ones (each within [0 or 1, len_hi]); x_std / k_std:
+    standard deviation of the activations / of the cached keys (1 in the benchmark configurations;
+    parity cases use a small x_std so that the module's output is dominated by what its kernels
+    add to the residual stream, and a larger k_std for sharply peaked attention weights)."""
     g = torch.Generator().manual_seed(seed + 1)
     if cfg.kind == "linear":
-        return Inputs(x=_randn(g, (cfg.n_seqs, cfg.in_features), cfg.dtype))
+        return Inputs(x=_randn(g, (cfg.n_seqs, cfg.in_features), cfg.dtype, x_std))
     if cfg.kind == "ffn_block":   # independent token rows
-        return Inputs(x=_randn(g, (cfg.n_seqs, cfg.hidden), cfg.dtype))
+        return Inputs(x=_randn(g, (cfg.n_seqs, cfg.hidden), cfg.dtype, x_std))
     B, H = cfg.n_seqs, cfg.hidden
-    lens = torch.randint(cfg.len_lo, cfg.len_hi + 1, (B,), generator=g, dtype=torch.int64)
-    lens = lens.to(torch.int32).numpy()
+    drawn = torch.randint(cfg.len_lo, cfg.len_hi + 1, (B,), generator=g, dtype=torch.int64)
+    if lens is None:
+        lens = drawn.to(torch.int32).numpy()
+    else:
+        lens = np.asarray(lens, dtype=np.int32).copy()
+        if lens.shape != (B,) or lens.min() < 0 or lens.max() > cfg.len_hi:
+            raise ValueError("lens: one value in [0, len_hi] per sequence")
     if cfg.mode == "prefill":
-        return Inputs(x=_randn(g, (B, cfg.seq_pad, H), cfg.dtype), lens=lens)
-    x = _randn(g, (B, H), cfg.dtype)
+        return Inputs(x=_randn(g, (B, cfg.seq_pad, H), cfg.dtype, x_std), lens=lens)
+    x = _randn(g, (B, H), cfg.dtype, x_std)
     shape = (B, cfg.n_kv_heads, cfg.cache_cap, cfg.head_dim)
     if cfg.n_layers > 1:
         shape = (cfg.n_layers,) + shape    # one cache per layer of the run
-    k = _randn(g, shape, cfg.dtype)
+    k = _randn(g, shape, cfg.dtype, k_std)
     v = _randn(g, shape, cfg.dtype)
     # slots at and beyond the cached length are not part of the input: zero them so that a
     # reader of a wrong slot is caught

@@ -103,18 +103,10 @@ hipError_t launch_attn_generic(int dtype, const void *qkv, void *out, int rows, 
     dim3 grid((unsigned)((units + 3) / 4)), block(256);
     if (dtype == DT_BF16) {
         auto kern = attn_generic_kernel<bf16_t>;
-        if (smem > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e != hipSuccess) return e;
-        }
         hipLaunchKernelGGL(kern, grid, block, smem, st, (const bf16_t *)qkv, (bf16_t *)out, rows, nq, nkv, d,
                            decode, seq_pad, lens_dev, (const bf16_t *)k_cache, (const bf16_t *)v_cache, cap, max_keys);
     } else {
         auto kern = attn_generic_kernel<float>;
-        if (smem > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e != hipSuccess) return e;
-        }
         hipLaunchKernelGGL(kern, grid, block, smem, st, (const float *)qkv, (float *)out, rows, nq, nkv, d,
                            decode, seq_pad, lens_dev, (const float *)k_cache, (const float *)v_cache, cap, max_keys);
     }
@@ -674,6 +666,10 @@ hipError_t init_attention_kernels()
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<2>, (hipFuncAttribute)attr, 65536);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<4>, (hipFuncAttribute)attr, 65536);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<8>, (hipFuncAttribute)attr, 65536);
+    // the generic kernel keeps one score per key in LDS: allow it the whole 160 KiB here, so that no
+    // forward (which a caller may be capturing into a graph) has to change a kernel attribute
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_generic_kernel<float>, (hipFuncAttribute)attr, 160 * 1024);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_generic_kernel<bf16_t>, (hipFuncAttribute)attr, 160 * 1024);
     return e;
 }
 

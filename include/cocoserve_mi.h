@@ -169,6 +169,27 @@ int ccs_module_replicas(const ccs_module *m);
  * (workspace too small for this batch), CCS_EHIP. */
 int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice);
 
+/* For callers that cannot allocate or bring a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): ccs_module_forward with everything the
+ * kernels keep between launches - normalised rows, q/k/v, attention output, SwiGLU output, the
+ * fp32 partial sums of the split-K projections and of the split-KV attention - in an array of
+ * CCS_STATIC_WORKSPACE_BYTES that is part of the library's code object (every GPU the library
+ * runs on holds one copy until the process ends) instead of the replica's workspace.  The call
+ * makes no allocation of any kind and records no per-kernel timing.  Same kernels, same
+ * arithmetic, same bits as ccs_module_forward.  A batch whose plan does not fit the array is
+ * rejected with CCS_ENOMEM and a message that gives both sizes (64 MiB hold every decode step of
+ * the 7B / 13B / 70B shapes up to 64 sequences x 2048 cached positions and projections of a few
+ * hundred rows; a 13B prefill of thousands of rows does not fit).  Nothing in the array has to
+ * start at zero: every partial sum a kernel reads was written by the launch before it.  ALL
+ * calls on one GPU share that GPU's array - of every module and replica: two calls whose kernels
+ * may overlap in time (different streams without an ordering between them) race; keep them on
+ * one stream or order them with events.  Other errors as ccs_module_forward. */
+enum { CCS_STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024 };
+int ccs_module_forward_static(ccs_module *m, int32_t replica, const ccs_batch *slice);
+
+/* CCS_STATIC_WORKSPACE_BYTES as the built library has it. */
+size_t ccs_static_workspace_bytes(void);
+
 /* The replicated forward of Section 3.1: cut the batch into k = ccs_module_replicas(m)
  * contiguous slices [floor(j n / k), floor((j+1) n / k)) - over sequences for a decoder layer,
  * over token rows for a projection.  Slice 0 runs on `caller_stream` itself with replica 0's

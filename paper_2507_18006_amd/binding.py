@@ -25,8 +25,8 @@ _STATUS = {0: "CCS_OK", -1: "CCS_EINVAL", -2: "CCS_ESTATE", -3: "CCS_ENOMEM",
 
 EXPORTS = (
     "ccs_module_arena_bytes", "ccs_module_workspace_bytes", "ccs_module_create",
-    "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
-    "ccs_module_forward_split", "ccs_module_forward_shares", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
+    "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward", "ccs_module_forward_static",
+    "ccs_static_workspace_bytes", "ccs_module_forward_split", "ccs_module_forward_shares", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
     "ccs_module_arena", "ccs_module_profile", "ccs_module_profile_read", "ccs_module_sync", "ccs_module_destroy", "ccs_last_error", "ccs_version",
     "ccs_speedup_homo", "ccs_speedup", "ccs_plan_scale_up",
 )
@@ -88,6 +88,10 @@ def lib():
     L.ccs_module_replicate.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), sz, ctypes.POINTER(vp)]
     L.ccs_module_replicas.argtypes = [vp]
     L.ccs_module_forward.argtypes = [vp, i32, ctypes.POINTER(ccs_batch)]
+    L.ccs_module_forward_static.argtypes = [vp, i32, ctypes.POINTER(ccs_batch)]
+    L.ccs_module_forward_static.restype = ctypes.c_int
+    L.ccs_static_workspace_bytes.restype = sz
+    L.ccs_static_workspace_bytes.argtypes = []
     L.ccs_module_forward_split.argtypes = [vp, ctypes.POINTER(ccs_batch), vp]
     L.ccs_module_forward_shares.argtypes = [vp, ctypes.POINTER(ccs_batch), ctypes.POINTER(i32), vp]
     L.ccs_module_copy.argtypes = [vp, i32, vp, vp]
@@ -248,6 +252,10 @@ class Module:
 
     def forward(self, replica: int, batch: ccs_batch):
         _check(self.L.ccs_module_forward(self.handle, replica, ctypes.byref(batch)))
+
+    def forward_static(self, replica: int, batch: ccs_batch):
+        """forward() in the library's built-in workspace: no allocation, no caller workspace."""
+        _check(self.L.ccs_module_forward_static(self.handle, replica, ctypes.byref(batch)))
 
     def forward_split(self, batch: ccs_batch, stream=None):
         s = self._torch.cuda.current_stream(self.device) if stream is None else stream

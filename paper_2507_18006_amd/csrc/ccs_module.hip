@@ -14,6 +14,12 @@
 #include "ccs_common.h"
 #include "ccs_kernels.h"
 
+// Workspace of ccs_module_forward_static: one array per GPU, inside the code object, so that the
+// entry point needs no caller workspace and no allocation.  Host code never uses this name as an
+// address (on the host it is only a stand-in for the symbol): static_workspace() asks the runtime
+// for the device address once per device and everything else goes through that pointer.
+static __device__ __align__(256) unsigned char g_static_ws[CCS_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -34,6 +40,28 @@ int fail(int code, const char *fmt, ...)
     } while (0)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Device address of g_static_ws on the current device (every GPU holds its own copy of the array at
+// its own address); resolved on first use per device, then cached.
+constexpr int kMaxDevices = 64;
+std::mutex g_static_ws_mutex;
+void *g_static_ws_ptr[kMaxDevices] = {nullptr};
+
+int static_workspace(void **out)
+{
+    int dev = -1;
+    CCS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CCS_EUNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_static_ws_mutex);
+    if (!g_static_ws_ptr[dev]) {
+        void *p = nullptr;
+        CCS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_ws)));
+        if (!p || ((uintptr_t)p & 255)) return fail(CCS_EHIP, "static workspace symbol resolved to %p", p);
+        g_static_ws_ptr[dev] = p;
+    }
+    *out = g_static_ws_ptr[dev];
+    return CCS_OK;
+}
 
 struct Dims {
     int H, nq, nkv, d, I, QD, KD, W3;  // W3 = QD + 2 KD
@@ -283,7 +311,7 @@ void prof_free(Replica &R)
 
 #define CCS_STAGE(sid, expr)                              \
     do {                                                  \
-        ProfPair *pp__ = prof_begin(m, R, (sid), st);     \
+        ProfPair *pp__ = prof_on ? prof_begin(m, R, (sid), st) : nullptr; \
         hipError_t se__ = (expr);                         \
         prof_end(pp__, st);                               \
         if (se__ != hipSuccess) return fail(CCS_EHIP, "%s: %s", #expr, hipGetErrorString(se__)); \
@@ -347,8 +375,10 @@ long long batch_rows(const ccs_module *m, const ccs_batch *b)
 
 // One replica, one slice.  variant_rows: row count that selects the GEMM variant (the full
 // batch's for a replicated forward, so that every replica count produces the same bits).
+// ws_static: run in this workspace of ws_static_bytes bytes instead of the replica's own, and
+// record no per-kernel timing (that path creates events); used by ccs_module_forward_static.
 int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows, bool on_caller_stream = false,
-                hipStream_t caller_stream = nullptr)
+                hipStream_t caller_stream = nullptr, void *ws_static = nullptr, size_t ws_static_bytes = 0)
 {
     using namespace ccs;
     Replica &R = m->rep[r];
@@ -358,7 +388,9 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     if (b->n_seqs == 0) return CCS_OK;
     const bool bf = D.dtype == CCS_BF16;
     const bool skinny = bf && variant_rows <= kSkinnyMaxRows;
-    char *ws = (char *)R.ws;
+    const bool prof_on = ws_static == nullptr;
+    char *ws = ws_static ? (char *)ws_static : (char *)R.ws;
+    const size_t ws_bytes = ws_static ? ws_static_bytes : R.ws_bytes;
     const char *A0 = (const char *)R.arena;
 
     if (D.kind == CCS_LINEAR) {
@@ -369,7 +401,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             return CCS_OK;
         }
         WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false, 0, (long)variant_rows);
-        if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
+        if (p.total > ws_bytes) return fail(CCS_ENOMEM, "%s workspace has %zu bytes, batch needs %zu", ws_static ? "the static" : "the replica's", ws_bytes, p.total);
         CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, st));
         if (skinny) {
             bool fused = false;
@@ -389,7 +421,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     const bool dense = bf && !decode && !rows_mode;
     const int T = dense ? (int)valid_rows(b) : b->n_seqs * seq_pad;
     WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, (decode || rows_mode) ? 0 : seq_pad, (long)variant_rows);
-    if (p.total > R.ws_bytes) return fail(CCS_ENOMEM, "workspace of replica %d has %zu bytes, batch needs %zu", r, R.ws_bytes, p.total);
+    if (p.total > ws_bytes) return fail(CCS_ENOMEM, "%s workspace has %zu bytes, batch needs %zu", ws_static ? "the static" : "the replica's", ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
     const bool row_norm = skinny && d.H <= 8192 && d.H % 4 == 0;  // few rows: one workgroup per row
 
@@ -578,6 +610,11 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
         if (init_err != hipSuccess) return fail(CCS_EHIP, "kernel attributes: %s", hipGetErrorString(init_err));
     }
 
+    {   // the static workspace's address on this device, resolved at set-up rather than in a forward
+        void *sws = nullptr;
+        rc = static_workspace(&sws);
+        if (rc != CCS_OK) return rc;
+    }
     ccs_module *m = new (std::nothrow) ccs_module();
     if (!m) return fail(CCS_ENOMEM, "host allocation failed");
     m->desc = *desc;
@@ -733,6 +770,21 @@ int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice)
     return forward_one(m, replica, slice, batch_rows(m, slice));
 }
 
+int ccs_module_forward_static(ccs_module *m, int32_t replica, const ccs_batch *slice)
+{
+    if (!m) return fail(CCS_EINVAL, "module is null");
+    if (replica < 0 || replica >= CCS_MAX_REPLICAS) return fail(CCS_EINVAL, "replica index %d out of range", replica);
+    if (replica >= m->k) return fail(CCS_ESTATE, "replica %d is not instantiated (module has %d)", replica, m->k);
+    int rc = check_batch(m, slice);
+    if (rc != CCS_OK) return rc;
+    void *ws = nullptr;
+    rc = static_workspace(&ws);
+    if (rc != CCS_OK) return rc;
+    return forward_one(m, replica, slice, batch_rows(m, slice), false, nullptr, ws, (size_t)CCS_STATIC_WORKSPACE_BYTES);
+}
+
+size_t ccs_static_workspace_bytes(void) { return (size_t)CCS_STATIC_WORKSPACE_BYTES; }
+
 // Slice j = sequences [bounds[j], bounds[j + 1]) on replica j; slice 0 on the caller's stream.
 static int forward_bounds(ccs_module *m, const ccs_batch *full, const long long *bounds, hipStream_t cs)
 {
@@ -818,6 +870,7 @@ int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *strea
         CCS_HIP(hipEventRecord(R.done, R.stream));
         CCS_HIP(hipStreamWaitEvent(st, R.done, 0));
     }
+    const bool prof_on = true;
     CCS_STAGE(CCS_ST_CLONE, ccs::launch_clone(dst_arena, R.arena, m->ap.total, st));
     return CCS_OK;
 }

@@ -10,8 +10,11 @@ object prices the dominant kernel against its roofline (decode attention vs HBM;
 workload the gate/up projection vs the bf16 MFMA peak); `cpu_baseline` is the CPU oracle timed
 on this machine's host cores.
 
-`--workload C3|C4|C5` runs the other benchmark configurations the same way (13B prefill, 70B GQA
-decode, bursty down-projection).
+The default run also measures the other benchmark configurations - 13B prefill (C3), 70B GQA decode
+(C4), bursty down-projection (C5) - and reports them as sub-objects under `workloads`, each with its
+tokens/s per replica count, its own `roofline` and its parity against the oracle on the WHOLE batch.
+`--workload C3|C4|C5` runs one of them alone (with its own CPU baseline); `--only-headline` skips
+the sub-objects.
 
 Prints ONE JSON line.
 """
@@ -29,11 +32,28 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 METRIC = "decoder-layer tokens/s (7B shape, k=1/2/4 replicas); module replicate GB/s"
 
-# HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` runs (FETCH_SIZE,
-# WRITE_SIZE) scaled by the same counters on the clone kernel of known size; see
-# profiles/decoder_layer_decode_C2_k1_pmc_hbm_traffic.md and ..._prefill_C3_k1_pmc_hbm_traffic.md (C3: fabric
-# traffic into the L2s of the gate/up GEMM; most of it is served by the Infinity Cache).
-MEASURED_TRAFFIC_BYTES = {"C2": 547593038, "C3": 2839000000}
+# HBM bytes per launch of the dominant kernel come from two `rocprofv3 --pmc` runs (FETCH_SIZE,
+# WRITE_SIZE) scaled by the same counters on the clone kernel of known size.  The summaries of those
+# runs are tracked under profiles/; each carries one line `traffic_bytes_per_launch = <int>` that
+# this script reads (null when the file or the line is missing - nothing is hard-coded here).
+TRAFFIC_PROFILE = {"C2": "profiles/decoder_layer_decode_C2_k1_pmc_hbm_traffic.md",
+                   "C3": "profiles/decoder_layer_prefill_C3_k1_pmc_hbm_traffic.md",
+                   "C4": "profiles/decoder_layer_decode_C4_k1_pmc_hbm_traffic.md"}
+
+
+def measured_traffic(name):
+    """(bytes per launch of the dominant kernel, file it was read from) or (None, None)."""
+    rel = TRAFFIC_PROFILE.get(name)
+    if not rel:
+        return None, None
+    try:
+        with open(os.path.join(ROOT, rel)) as f:
+            for line in f:
+                if line.strip().startswith("traffic_bytes_per_launch"):
+                    return int(float(line.split("=", 1)[1].split()[0])), rel
+    except (OSError, ValueError, IndexError):
+        pass
+    return None, None
 
 
 def time_events(torch, fn, reps):
@@ -49,7 +69,9 @@ def time_events(torch, fn, reps):
     return ev0.elapsed_time(ev1) / reps * 1e-3
 
 
-def bench_layer(args, name):
+def bench_layer(args, name, sub=False):
+    """sub: this workload is a sub-object of the default run - fewer steps for the prefill, no run of
+    layers, no clone timing, no CPU baseline (the headline workload carries those)."""
     import numpy as np
     import torch
     import workloads
@@ -58,6 +80,8 @@ def bench_layer(args, name):
 
     cfg = workloads.CONFIGS[name]
     K, W = args.steps, args.warmup
+    if sub and cfg.mode == "prefill":
+        K, W = max(10, K // 4), max(3, W // 4)
     ks = [int(v) for v in args.replicas.split(",") if int(v) in cfg.replicas or int(v) == 1]
     decode = cfg.mode == "decode"
 
@@ -135,27 +159,32 @@ def bench_layer(args, name):
     m.replicate(1)
     spare = torch.empty(arena, dtype=torch.uint8, device=U.DEV)
     t_clone = time_events(torch, lambda: m.copy_into(0, spare), 20)
-    big_bytes = 2 * (2 * 8192 * 8192 + 2 * 8192 * 1024 + 3 * 8192 * 28672)
-    src_big = torch.empty(big_bytes, dtype=torch.uint8, device=U.DEV).random_(0, 255)
-    dst_big = torch.empty_like(src_big)
-    t_clone_big = time_events(torch, lambda: B.cache_copy(dst_big, src_big), 20)
-    assert torch.equal(dst_big[:: 4097], src_big[:: 4097])
-    del src_big, dst_big, spare
+    del spare
+    clone = {"payload_GBps": round(arena / t_clone / 1e9, 1), "bytes": arena,
+             "hbm_frac": round(2 * arena / t_clone / 1e9 / HBM_PEAK_GBPS, 4),
+             "note": "payload = bytes cloned / time; HBM traffic is 2 x payload (read + write)"}
+    if not sub:
+        big_bytes = 2 * (2 * 8192 * 8192 + 2 * 8192 * 1024 + 3 * 8192 * 28672)
+        src_big = torch.empty(big_bytes, dtype=torch.uint8, device=U.DEV).random_(0, 255)
+        dst_big = torch.empty_like(src_big)
+        t_clone_big = time_events(torch, lambda: B.cache_copy(dst_big, src_big), 20)
+        assert torch.equal(dst_big[:: 4097], src_big[:: 4097])
+        del src_big, dst_big
+        clone.update({"layer70b_payload_GBps": round(big_bytes / t_clone_big / 1e9, 1), "layer70b_bytes": big_bytes,
+                      "layer70b_hbm_frac": round(2 * big_bytes / t_clone_big / 1e9 / HBM_PEAK_GBPS, 4)})
 
-    # check the timed configuration once against the oracle (sampled sequences keep it short)
+    # the timed configuration against the oracle: the WHOLE batch, every valid row
+    m.forward_split(db.batch)
     y = db.out()
-    if decode:
-        sel = slice(0, 4)
-        parity = U.rel_err(y[sel], U.oracle_forward(cfg, 0, w, inp, seqs=sel))
-    else:
-        b0 = int(np.argmin(lens))
-        sel = slice(b0, b0 + 1)
-        parity = U.rel_err(y[sel], U.oracle_forward(cfg, 0, w, inp, seqs=sel), U.valid_mask(cfg, inp.lens[sel]))
+    ref = U.oracle_forward(cfg, 0, w, inp)
+    mask = None if decode else U.valid_mask(cfg, inp.lens)
+    parity, parity_l2 = U.rel_err(y, ref, mask), U.l2_err(y, ref, mask)
+    del ref
 
     # the same layer inside a run of consecutive layers (one module, scatter / gather only at the
     # ends of the run): per-layer time with the layer boundaries fused
     run = None
-    if args.layers > 1:
+    if args.layers > 1 and not sub:
         m.destroy()
         m = None
         rc = workloads.scaled(cfg, n_layers=args.layers)
@@ -178,12 +207,14 @@ def bench_layer(args, name):
                "layer_tokens_per_s": round(n_tok / (t_run / args.layers), 1)}
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not sub:
         import oracle
         if decode:
             csel, ctok, what = slice(None), n_tok, f"full step ({cfg.n_seqs} sequences)"
         else:
-            csel, ctok, what = sel, int(lens[sel].sum()), f"the shortest sequence ({int(lens[sel].sum())} tokens)"
+            b0 = int(np.argmin(lens))
+            csel = slice(b0, b0 + 1)
+            ctok, what = int(lens[csel].sum()), f"the shortest sequence ({int(lens[csel].sum())} tokens)"
         reps, t_cpu = 0, 0.0
         while reps < 200 and t_cpu < 10.0:   # about ten seconds of host work
             t0 = time.perf_counter()
@@ -195,18 +226,19 @@ def bench_layer(args, name):
     if m is not None:
         m.destroy()
 
+    traffic, traffic_file = measured_traffic(name)
     if decode:
         roof = {"kernel": "attn_decode_mfma_kernel", "bound": "hbm",
                 "achieved": round(kv_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(kv_bytes / dom_s / 1e9 / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "traffic": traffic, "traffic_source": traffic_file,
                 "algorithmic_bytes_per_launch": kv_bytes}
     else:
         N, Kd = shapes[dominant]
         fl = 2.0 * rows * N * Kd
         roof = {"kernel": "gemm_tiled_dma_kernel<128,3> (gate/up + SwiGLU)", "bound": "mfma",
                 "achieved": round(fl / dom_s / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(fl / dom_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "frac": round(fl / dom_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic, "traffic_source": traffic_file,
                 "algorithmic_flops_per_launch": fl, "rows_executed": rows, "rows_padded_batch": cfg.n_seqs * cfg.seq_pad}
     roof["avg_launch_us"] = round(dom_s * 1e6, 2)
     roof["launches_timed"] = dom_n
@@ -224,7 +256,7 @@ def bench_layer(args, name):
             e["mfma_frac_valid_rows"] = round(fl / t / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
         return e
 
-    return {
+    out = {
         "metric": METRIC if name == "C2" else f"decoder-layer tokens/s ({cfg.name})",
         "value": round(n_tok / per_k[1], 1),
         "unit": "tokens/s",
@@ -238,20 +270,23 @@ def bench_layer(args, name):
                                + ", k=1 replica (other k in `replicas`)",
                    "hidden": H, "q_heads": nq, "kv_heads": nkv, "head_dim": d, "intermediate": I},
         "replicas": {str(k): step_entry(k, t) for k, t in per_k.items()},
-        "clone": {"payload_GBps": round(arena / t_clone / 1e9, 1), "bytes": arena,
-                  "hbm_frac": round(2 * arena / t_clone / 1e9 / HBM_PEAK_GBPS, 4),
-                  "layer70b_payload_GBps": round(big_bytes / t_clone_big / 1e9, 1), "layer70b_bytes": big_bytes,
-                  "layer70b_hbm_frac": round(2 * big_bytes / t_clone_big / 1e9 / HBM_PEAK_GBPS, 4),
-                  "note": "payload = bytes cloned / time; HBM traffic is 2 x payload (read + write)"},
+        "clone": clone,
         "kernels_k1": breakdown,
-        "run_of_layers_k1": run,
         "parity_rel_err_vs_oracle": float(f"{parity:.3e}"),
+        "parity_l2_rel_err_vs_oracle": float(f"{parity_l2:.3e}"),
+        "parity_rows_compared": f"all {n_tok} valid rows of the batch" if not decode else f"all {n_tok} sequences",
         "roofline": roof,
-        "cpu_baseline": cpu,
     }
+    if not sub:
+        out["run_of_layers_k1"] = run
+        out["cpu_baseline"] = cpu
+    else:
+        for key in ("n_gpus", "higher_is_better", "scaling", "vs_baseline", "data"):
+            out.pop(key)
+    return out
 
 
-def bench_bursty(args):
+def bench_bursty(args, sub=False):
     """configs[4]: down_proj 11008 -> 4096 under the seeded bursty token stream; replica count per
     batch by token count, and every batch at fixed k for comparison."""
     import numpy as np
@@ -305,10 +340,20 @@ def bench_bursty(args):
             "achieved": round(fl / (g_ms * 1e-3) / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(fl / (g_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
             "algorithmic_flops_per_launch": fl / g_n, "avg_launch_us": round(g_ms / g_n * 1e3, 2), "launches_timed": g_n}
+    # parity on whole batches of the stream (every row): the smallest, a mid-sized and the largest one
+    import oracle
+    xs_all = x_all.float().cpu().numpy()
+    par, par_l2, par_rows = 0.0, 0.0, 0
+    for n in sorted({min(counts), sorted(counts)[len(counts) // 2], max(counts)}):
+        m.replicate(workloads.replicas_for_tokens(n))
+        m.forward_split(m.batch(B.CCS_ROWS, x_all[:n], y_all[:n]))
+        torch.cuda.synchronize()
+        ref = oracle.linear(xs_all[:n], w["w"])
+        got = y_all[:n].float().cpu().numpy()
+        par, par_l2, par_rows = max(par, U.row_rel_err(got, ref)), max(par_l2, U.l2_err(got, ref)), par_rows + n
     cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        xs = x_all.float().cpu().numpy()
+    if not args.no_cpu_baseline and not sub:
+        xs = xs_all
         done, t_cpu = 0, 0.0
         for n in counts:
             t0 = time.perf_counter()
@@ -320,13 +365,22 @@ def bench_bursty(args):
         cpu = {"value": round(done / t_cpu, 1), "unit": "tokens/s", "cores": oracle.omp_threads(), "kind": "oracle",
                "sample": f"the first batches of the stream ({done} tokens), fp64 arithmetic"}
     m.destroy()
-    return {"metric": "aggregate tokens/s (C5 down_proj 11008->4096, 200 bursty batches)",
-            "value": res["by_tokens"]["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
-            "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": "configs[4]: 200 batches, tokens = max(1, Poisson(64)) x {1,4,16}",
-                       "tokens_total": int(sum(counts)), "tokens_min": min(counts), "tokens_max": max(counts),
-                       "note": "the 90 MB weight fits the 256 MB Infinity Cache: figures are cache-assisted"},
-            "policies": res, "roofline": roof, "cpu_baseline": cpu}
+    out = {"metric": "aggregate tokens/s (C5 down_proj 11008->4096, 200 bursty batches)",
+           "value": res["by_tokens"]["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+           "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "configs[4]: 200 batches, tokens = max(1, Poisson(64)) x {1,4,16}",
+                      "tokens_total": int(sum(counts)), "tokens_min": min(counts), "tokens_max": max(counts),
+                      "note": "the 90 MB weight fits the 256 MB Infinity Cache: figures are cache-assisted"},
+           "policies": res,
+           "parity_worst_row_rel_err_vs_oracle": float(f"{par:.3e}"), "parity_l2_rel_err_vs_oracle": float(f"{par_l2:.3e}"),
+           "parity_rows_compared": f"every row of 3 batches of the stream ({par_rows} rows)",
+           "roofline": roof}
+    if not sub:
+        out["cpu_baseline"] = cpu
+    else:
+        for key in ("n_gpus", "higher_is_better", "data"):
+            out.pop(key)
+    return out
 
 
 def main():
@@ -339,6 +393,8 @@ def main():
     ap.add_argument("--workload", type=str, default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--layers", type=int, default=4,
                     help="also time a run of this many consecutive layers as one module (0 or 1: skip)")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="default workload only: skip the C3 / C4 / C5 sub-objects")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (replicas are HIP streams of one MI355X, no "
@@ -352,6 +408,17 @@ def main():
         __graft_entry__.build()
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     out = bench_bursty(args) if args.workload == "C5" else bench_layer(args, args.workload)
+    if args.workload == "C2" and not args.only_headline:
+        import gc
+        t0 = time.perf_counter()
+        subs = {}
+        for name in ("C3", "C4", "C5"):
+            gc.collect()
+            torch.cuda.empty_cache()
+            print(f"bench.py: sub-workload {name} ...", file=sys.stderr, flush=True)
+            subs[name] = bench_bursty(args, sub=True) if name == "C5" else bench_layer(args, name, sub=True)
+        out["workloads"] = subs
+        out["workloads_wall_s"] = round(time.perf_counter() - t0, 1)
     print(json.dumps(out))
 
 

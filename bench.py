@@ -155,6 +155,37 @@ def bench_layer(args, name, sub=False):
             e["GBps"] = round(kv_bytes / us / 1e3, 1)
         breakdown[s] = e
 
+    # uneven shares (Eq. 1 of the speed-up model: an instance's share follows its capacity and the
+    # layer takes as long as its slowest instance): k = 2 with shares for capacity ratios 1:1, 1:3
+    # and 1:7; per instance the summed kernel time on its stream, and the step time
+    uneven = None
+    if not decode and 2 in cfg.replicas:
+        uneven = []
+        m.replicate(2)
+        for ratio in (1.0, 3.0, 7.0):
+            counts = B.shares_from_capacity(cfg.n_seqs, [1.0, ratio])
+            for _ in range(3):
+                m.forward_shares(db.batch, counts)
+            torch.cuda.synchronize()
+            reps = max(5, K // 4)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                m.forward_shares(db.batch, counts)
+            torch.cuda.synchronize()
+            t_step = (time.perf_counter() - t0) / reps
+            m.profile(None)
+            for _ in range(3):
+                m.forward_shares(db.batch, counts)
+            torch.cuda.synchronize()
+            busy = [sum(ms for ms, _ in m.profile_read(j, reset=True).values()) / 3 for j in range(2)]
+            m.profile([])
+            lo = np.cumsum([0] + counts)
+            uneven.append({"capacity_ratio": f"1:{ratio:g}", "shares_sequences": counts,
+                           "shares_tokens": [int(lens[lo[j]:lo[j + 1]].sum()) for j in range(2)],
+                           "ms_per_step": round(t_step * 1e3, 4),
+                           "instance_kernel_ms": [round(b, 4) for b in busy]})
+        m.replicate(1)
+
     # replica clone: this layer's arena, and a 70B-layer-sized buffer (configs[3]: 1,711.3 MB)
     m.replicate(1)
     spare = torch.empty(arena, dtype=torch.uint8, device=U.DEV)
@@ -277,6 +308,9 @@ def bench_layer(args, name, sub=False):
         "parity_rows_compared": f"all {n_tok} valid rows of the batch" if not decode else f"all {n_tok} sequences",
         "roofline": roof,
     }
+    if uneven:
+        out["uneven_shares_k2"] = {"cases": uneven, "note": "one GPU: the two instances share one capacity, so the step takes "
+                                   "about the sum of both instances' work whatever the split; each instance's own kernel time follows its share"}
     if not sub:
         out["run_of_layers_k1"] = run
         out["cpu_baseline"] = cpu

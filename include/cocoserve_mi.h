@@ -140,7 +140,10 @@ size_t ccs_module_arena_bytes(const ccs_module_desc *desc);
 size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
                                   int32_t max_seq_pad, int32_t max_cache_cap);
 
-/* Create a module with ONE instance (replica 0, "the original"): packs `weights` (host array of
+/* Section 1 (footnote on modules) and Section 2.1: a module - decoder layer, attention or FFN
+ * block, projection - is the unit that is replicated and migrated; Section 3.1: the original
+ * instance keeps serving while replicas are added beside it.
+ * Create a module with ONE instance (replica 0, "the original"): packs `weights` (host array of
  * max(1, n_layers) structs holding device pointers) into
  * `arena0` (device, >= ccs_module_arena_bytes, 256-byte aligned) on `stream`, and remembers
  * `workspace0` (device, workspace_bytes long, 256-byte aligned) and `stream` as replica 0's.
@@ -163,7 +166,9 @@ int ccs_module_replicate(ccs_module *m, int32_t k, void *const *arenas, void *co
 /* Number of instances the module currently has (>= 1), or CCS_EINVAL. */
 int ccs_module_replicas(const ccs_module *m);
 
-/* Run the module on ONE replica over one contiguous slice, on that replica's stream.
+/* Section 3.1 "Replication": every instance runs the UNMODIFIED module on its contiguous slice of
+ * the batch; Section 2.1: the module's arithmetic in prefill and decode.
+ * Run the module on ONE replica over one contiguous slice, on that replica's stream.
  * `slice` (host struct; its pointers as documented above) already points at the slice's first
  * row / sequence.  Errors: CCS_EINVAL (bad replica index, bad batch), CCS_ESTATE, CCS_ENOMEM
  * (workspace too small for this batch), CCS_EHIP. */
@@ -196,9 +201,12 @@ size_t ccs_static_workspace_bytes(void);
  * weights and workspace; for j >= 1 the call orders `caller_stream` -> replica j's stream (fork
  * event), runs slice j there, and orders that stream -> `caller_stream` (join event).  Outputs
  * land in `full->y` at their batch positions, so the gather is free.  Output rows are
- * bit-identical for every k at a fixed batch.  The caller keeps successive uses of replica 0
- * ordered (same stream, or its own events); work that created or migrated replica 0 must have
- * completed.  The call only enqueues (kernel launches, event record / wait), so it may be
+ * bit-identical for every k at a fixed batch.  `caller_stream` is ordered after the work that
+ * created or migrated replica 0, and copies / migrations / the next forward of replica 0 on
+ * another stream are ordered after this slice 0; two replicated forwards of one module issued from
+ * DIFFERENT caller streams without an ordering between them still share replica 0's workspace:
+ * keep them on one stream or order them.  If a slice fails after others were forked, the forked
+ * streams are joined before the error is returned.  The call only enqueues (kernel launches, event record / wait), so it may be
  * recorded into a HIP graph by capturing `caller_stream`. */
 int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream);
 
@@ -210,8 +218,11 @@ int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_
 int ccs_module_forward_shares(ccs_module *m, const ccs_batch *full, const int32_t *counts,
                               void *caller_stream);
 
-/* Clone replica `replica`'s packed weights into `dst_arena` (device, arena_bytes) on `stream`
- * (ordered after that replica's pending work); the source stays in use. */
+/* Section 3.1 "Implementation": instantiating a replica duplicates the module with its weights;
+ * Section 6.5, Table 2 prices that step.
+ * Clone replica `replica`'s packed weights into `dst_arena` (device, arena_bytes) on `stream`
+ * (ordered after that replica's pending work, including a slice 0 that a replicated forward
+ * ran on a caller's stream); the source stays in use.  Errors: CCS_EINVAL, CCS_ESTATE, CCS_EHIP. */
 int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *stream);
 
 /* Migrate: clone as ccs_module_copy, then make `dst_arena` the replica's arena; later
@@ -261,11 +272,13 @@ int ccs_module_profile(ccs_module *m, uint32_t stage_mask);
 int ccs_module_profile_read(ccs_module *m, int32_t replica, double *ms_sum, int64_t *count,
                             int32_t reset);
 
-/* Block the host until every stream of the module has drained. */
+/* Section 3.1 (correctness of scaling operations): an instance is only dropped or moved once its
+ * work has finished.  Block the host until every stream of the module has drained, including
+ * caller streams that ran slice 0 of a replicated forward. */
 int ccs_module_sync(ccs_module *m);
 
-/* Wait for the module's work, release events and host metadata.  Device buffers stay with
- * the caller. */
+/* Section 3.1 "Migration": removing an instance hands its memory back.  Wait for the module's
+ * work, release events and host metadata.  Device buffers stay with the caller. */
 int ccs_module_destroy(ccs_module *m);
 
 /* ---- scale-up planning (Section 4.1), host-only: no GPU, no module handle ----------------------- */
@@ -282,6 +295,17 @@ double ccs_speedup_homo(const int32_t *p, int32_t n, double gamma);
  * arguments. */
 double ccs_speedup(const int32_t *p, int32_t n, const double *bs, const double *capacity,
                    const double *bandwidth, double d, double l, double delta);
+
+/* Section 4.1, Eq. 1: a layer takes as long as its slowest instance, max_j d^2 bs_ij l / C_ij, so an
+ * instance's share of the batch should follow its capacity.  Computes the integer shares
+ * counts_out[j] >= 0 (host, k entries, sum n) that MINIMISE max_j counts[j] / capacity[j] for the
+ * k instances' capacities (host, k positive finite doubles; only their ratios matter), ready for
+ * ccs_module_forward_shares.  Among the optimal answers it returns the one reached from the
+ * capacity-weighted contiguous split - boundaries floor(n (C_0 + .. + C_{j-1}) / C_total), which for
+ * equal capacities is the paper's floor(j n / k) rule (15 -> 7 + 8) - by handing single units from
+ * a slowest instance to the instance that stays fastest.  Host-only.
+ * Errors: CCS_EINVAL (null pointers, k outside [1, CCS_MAX_REPLICAS], n < 0, a capacity <= 0). */
+int ccs_shares_from_capacity(int64_t n, int32_t k, const double *capacity, int32_t *counts_out);
 
 /* Algorithm 1 (greedy scale-up).  p_in: current instances per layer (n entries, >= 1).  Node g
  * (n_nodes of them, visited in order) has node_available[g] free resource units; it is eligible

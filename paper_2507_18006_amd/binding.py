@@ -28,7 +28,7 @@ EXPORTS = (
     "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward", "ccs_module_forward_static",
     "ccs_static_workspace_bytes", "ccs_module_forward_split", "ccs_module_forward_shares", "ccs_module_copy", "ccs_module_migrate", "ccs_cache_copy",
     "ccs_module_arena", "ccs_module_profile", "ccs_module_profile_read", "ccs_module_sync", "ccs_module_destroy", "ccs_last_error", "ccs_version",
-    "ccs_speedup_homo", "ccs_speedup", "ccs_plan_scale_up",
+    "ccs_speedup_homo", "ccs_speedup", "ccs_plan_scale_up", "ccs_shares_from_capacity",
 )
 
 
@@ -111,6 +111,8 @@ def lib():
     L.ccs_plan_scale_up.restype = ctypes.c_int
     L.ccs_plan_scale_up.argtypes = [ip, i32, ctypes.c_double, ctypes.POINTER(ctypes.c_int64), i32, ctypes.c_int64,
                                     ctypes.POINTER(ctypes.c_uint8), ip, ctypes.POINTER(ctypes.c_uint8), dp]
+    L.ccs_shares_from_capacity.restype = ctypes.c_int
+    L.ccs_shares_from_capacity.argtypes = [ctypes.c_int64, i32, dp, ip]
     L.ccs_last_error.restype = ctypes.c_char_p
     L.ccs_version.restype = ctypes.c_char_p
     for name in ("ccs_module_create", "ccs_module_replicate", "ccs_module_replicas", "ccs_module_forward",
@@ -350,6 +352,17 @@ def speedup(p, bs, capacity, bandwidth, d: float, l: float, delta: float) -> flo
     a = (ctypes.c_int32 * len(p))(*[int(v) for v in p])
     flat = lambda rows: (ctypes.c_double * sum(len(r) for r in rows))(*[float(v) for r in rows for v in r])
     return lib().ccs_speedup(a, len(p), flat(bs), flat(capacity), flat(bandwidth), float(d), float(l), float(delta))
+
+
+def shares_from_capacity(n: int, capacity):
+    """Integer shares of n sequences / rows over the instances, minimising max_j share_j / capacity_j."""
+    k = len(capacity)
+    c = (ctypes.c_double * max(k, 1))(*[float(v) for v in capacity])
+    out = (ctypes.c_int32 * max(k, 1))()
+    rc = lib().ccs_shares_from_capacity(int(n), k, c, out)
+    if rc < 0:
+        raise CcsError(rc, "ccs_shares_from_capacity: bad arguments")
+    return list(out)[:k]
 
 
 def plan_scale_up(p, gamma: float, node_available, replica_size: int, placed=None):

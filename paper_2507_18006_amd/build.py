@@ -15,7 +15,7 @@ LIB = os.path.join(HERE, "libcocoserve_mi.so")
 SOURCES = ["ccs_elementwise.hip", "ccs_gemm.hip", "ccs_attention.hip", "ccs_module.hip", "ccs_planner.hip"]
 # packed-fp32 VALU forms are switched off on purpose (device pass only; the host pass warns
 # that it does not know the feature, which is harmless)
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -2,11 +2,13 @@
 // prompt, decode one token against the growing KV cache and is memory-bound).
 //
 //  * attn_generic: any head_dim <= 256, fp32 or bf16, prefill or decode; one wavefront per
-//    (query row, head).  Used by the fp32 path and as the first bf16 prefill kernel.
-//  * attn_decode:  bf16, head_dim 128.  One wavefront per (sequence, kv head, 256-key chunk)
-//    streams K then V of its chunk with fully coalesced 1 KiB loads (16 lanes per key row,
-//    4 keys per load) and serves all query heads of the GQA group from the same registers;
-//    chunk results (max, sum, weighted values) are merged in chunk order by attn_combine.
+//    (query row, head), all-VALU.  The fp32 path.
+//  * attn_prefill_mfma: bf16, head_dim 128, both products on the matrix cores, K / V^T blocks
+//    of 32 keys through a direct-to-LDS ring.
+//  * attn_decode_mfma: bf16, head_dim 128.  One wavefront per (sequence, kv head, 128-key
+//    chunk) serves all query heads of the GQA group, so K and V are read once: scores on the
+//    matrix cores with K rows straight from the cache, V through LDS and the transposing LDS
+//    read; chunk results (max, sum, weighted values) are merged in chunk order by attn_combine.
 //    The chunking depends only on the sequence's own length, so a sequence's output bits do
 //    not depend on the batch it is in.
 #include "ccs_common.h"

@@ -295,8 +295,8 @@ hipError_t launch_prefill_rows(void *padded, void *dense, const int32_t *offs, i
 
 // ---------------------------------------------------------------------------------------------
 // Rotary embedding + KV-cache append.  One workgroup per row, thread i owns the pair
-// (i, i + d/2) of every head; the angle pos * base^(-2i/d) and its sine/cosine are evaluated
-// in fp64 once per thread and applied in fp32.
+// (i, i + d/2) of every head; sine and cosine of pos * base^(-2i/d) come from the module's fp32
+// head + tail table of inverse frequencies (rope_cs in ccs_common.h) and are applied in fp32.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(64) void rope_kernel(T *__restrict__ qkv, int nq, int nkv, int d,

@@ -2,15 +2,16 @@
 // projections are linear maps; Table 1 puts ~99 % of a layer's FLOPs in them).
 //
 // y[m, n] = sum_k x[m, k] * W[n, k].  On the bf16 path both operands are fragment-packed
-// (ccs_common.h) and every variant uses v_mfma_f32_16x16x32_bf16 with the weight fragment as
-// the A operand and the activation fragment as the B operand, so one accumulator register
-// quartet holds 4 consecutive n for one row m.
+// (ccs_common.h): 1 KiB fragments of 16 rows x 32 k in the operand register layout of the matrix
+// cores, the weight as the A operand and the activation as the B operand.
 //
-//  * gemm_tiled:  LDS-tiled, double-buffered, for compute-bound row counts (prefill).
-//  * gemm_skinny: weight-streaming for <= 64 rows (decode): no LDS staging of operands, each
-//    wavefront streams 1 KiB weight fragments straight into MFMA operands; K is cut into
-//    segments whose count depends on the weight shape only and partial sums are reduced in a
-//    fixed order, so a row's bits never depend on which other rows share the launch.
+//  * gemm_tiled_dma: LDS-tiled, for compute-bound row counts (prefill): 256 x 128 x 32 workgroup
+//    tiles of v_mfma_f32_32x32x16_bf16, operands brought in by direct-to-LDS loads through a
+//    3-stage ring, optional deterministic K split for launches that cannot fill the GPU.
+//  * gemm_skinny: weight-streaming for <= 64 rows (decode), v_mfma_f32_16x16x32_bf16: no LDS
+//    staging of operands, each wavefront streams 8 KiB weight pieces straight into MFMA operands;
+//    K is cut into segments whose count depends on the weight shape only and partial sums are
+//    reduced in a fixed order, so a row's bits never depend on which other rows share the launch.
 //  * gemm_f32: plain FMA kernel for the fp32 path.
 #include "ccs_common.h"
 #include "ccs_kernels.h"
@@ -90,37 +91,6 @@ int skinny_segments(int N, int K)
 size_t skinny_partial_bytes(int M, int N, int K)
 {
     return (size_t)skinny_segments(N, K) * (size_t)M * (size_t)N * sizeof(float);
-}
-
-// hand-issued 16-byte loads (OFF: immediate byte offset, at most 4095) and the wait that makes
-// a register set usable: nothing may read the registers between the two
-template <int OFF>
-__device__ __forceinline__ void sk_ld_nt(u32x4_t &dst, const uint4 *p)
-{
-    asm volatile("global_load_dwordx4 %0, %1, off offset:%2 nt" : "=v"(dst) : "v"(p), "i"(OFF) : "memory");
-}
-__device__ __forceinline__ void sk_ld(u32x4_t &dst, const uint4 *p)
-{
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
-}
-// all loads but the CNT issued last have landed (loads return in order)
-template <int CNT>
-__device__ __forceinline__ void sk_wait_older(u32x4_t (&r)[CNT])
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CNT) : "memory");
-#pragma unroll
-    for (int i = 0; i < CNT; ++i) asm volatile("" : "+v"(r[i]));
-}
-template <int CNT>
-__device__ __forceinline__ void sk_wait_all(u32x4_t (&r)[CNT])
-{
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int i = 0; i < CNT; ++i) asm volatile("" : "+v"(r[i]));
-}
-__device__ __forceinline__ f32x4_t mfma16x(const u32x4_t &a, const u32x4_t &b, f32x4_t c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
 // (3 or 4 row blocks: 128 accumulator registers plus two 2-step register sets need more than 256

@@ -253,6 +253,8 @@ struct ccs_module {
     int k = 0;
     Replica rep[CCS_MAX_REPLICAS];
     hipEvent_t fork = nullptr;
+    hipEvent_t slice0_done = nullptr;   // end of the last slice 0 that ran on a caller's stream other than replica 0's
+    bool slice0_recorded = false;
     uint32_t prof_mask = 0;
 };
 
@@ -531,6 +533,13 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     return CCS_OK;
 }
 
+// Order `st` after a slice 0 that a replicated forward ran on a caller's stream.
+int wait_slice0(ccs_module *m, int replica, hipStream_t st)
+{
+    if (replica == 0 && m->slice0_recorded) CCS_HIP(hipStreamWaitEvent(st, m->slice0_done, 0));
+    return CCS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -684,10 +693,12 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
     auto drop = [&] {
         drop_events(R);
         if (m->fork) (void)hipEventDestroy(m->fork);
+        if (m->slice0_done) (void)hipEventDestroy(m->slice0_done);
         prof_free(R);
         delete m;
     };
-    if (make_event(&R.ready) != CCS_OK || make_event(&R.done) != CCS_OK || make_event(&m->fork) != CCS_OK) {
+    if (make_event(&R.ready) != CCS_OK || make_event(&R.done) != CCS_OK || make_event(&m->fork) != CCS_OK ||
+        make_event(&m->slice0_done) != CCS_OK) {
         drop();
         return CCS_EHIP;
     }
@@ -767,6 +778,8 @@ int ccs_module_forward(ccs_module *m, int32_t replica, const ccs_batch *slice)
     if (replica >= m->k) return fail(CCS_ESTATE, "replica %d is not instantiated (module has %d)", replica, m->k);
     int rc = check_batch(m, slice);
     if (rc != CCS_OK) return rc;
+    rc = wait_slice0(m, replica, m->rep[replica].stream);
+    if (rc != CCS_OK) return rc;
     return forward_one(m, replica, slice, batch_rows(m, slice));
 }
 
@@ -779,6 +792,8 @@ int ccs_module_forward_static(ccs_module *m, int32_t replica, const ccs_batch *s
     if (rc != CCS_OK) return rc;
     void *ws = nullptr;
     rc = static_workspace(&ws);
+    if (rc != CCS_OK) return rc;
+    rc = wait_slice0(m, replica, m->rep[replica].stream);
     if (rc != CCS_OK) return rc;
     return forward_one(m, replica, slice, batch_rows(m, slice), false, nullptr, ws, (size_t)CCS_STATIC_WORKSPACE_BYTES);
 }
@@ -800,6 +815,23 @@ static int forward_bounds(ccs_module *m, const ccs_batch *full, const long long 
     const size_t y_row = (m->desc.kind == CCS_LINEAR ? (size_t)d.out_f : (size_t)d.H) * esz;
     const size_t cache_seq = (size_t)d.nkv * (size_t)full->cache_cap * d.d * esz;
 
+    // Slice 0 uses replica 0's arena and workspace from the caller's stream.  When that is not
+    // replica 0's own stream, order it after whatever filled or moved the arena, and leave an event
+    // behind that copies, migrations and later forwards of replica 0 wait for.  (Not while the
+    // caller is capturing: events recorded outside a capture cannot be tied into it, and an event
+    // recorded inside one must not leak out; a capturing caller orders these itself.)
+    const bool foreign = cs != m->rep[0].stream;
+    bool capturing = false;
+    if (foreign) {
+        hipStreamCaptureStatus cst = hipStreamCaptureStatusNone;
+        CCS_HIP(hipStreamIsCapturing(cs, &cst));
+        capturing = cst != hipStreamCaptureStatusNone;
+        if (!capturing) {
+            CCS_HIP(hipEventRecord(m->rep[0].done, m->rep[0].stream));   // replica 0's own earlier forwards
+            CCS_HIP(hipStreamWaitEvent(cs, m->rep[0].done, 0));
+            CCS_HIP(hipStreamWaitEvent(cs, m->rep[0].ready, 0));
+        }
+    }
     if (k > 1) CCS_HIP(hipEventRecord(m->fork, cs));
     for (int j = 0; j < k; ++j) {
         const long long lo = bounds[j], hi = bounds[j + 1];
@@ -818,15 +850,23 @@ static int forward_bounds(ccs_module *m, const ccs_batch *full, const long long 
         // slice 0 runs on the caller's stream itself (no events at k = 1); the others fork and join
         const bool inline_ = (j == 0) || R.stream == cs;
         if (!inline_) CCS_HIP(hipStreamWaitEvent(R.stream, m->fork, 0));
-        int rc = forward_one(m, j, &s, full_rows, inline_, cs);
-        if (rc != CCS_OK) return rc;
+        const int rc = forward_one(m, j, &s, full_rows, inline_, cs);
         if (!inline_) {
-            CCS_HIP(hipEventRecord(R.done, R.stream));
-            CCS_HIP(hipStreamWaitEvent(cs, R.done, 0));
+            // join also when the slice failed half-way: the stream was forked, and a caller that
+            // captures must get every forked stream back
+            const hipError_t e1 = hipEventRecord(R.done, R.stream);
+            const hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(cs, R.done, 0) : e1;
+            if (rc == CCS_OK && e2 != hipSuccess) return fail(CCS_EHIP, "joining replica %d: %s", j, hipGetErrorString(e2));
         }
+        if (rc != CCS_OK) return rc;   // earlier slices are already joined
+    }
+    if (foreign && !capturing && bounds[1] > bounds[0]) {
+        CCS_HIP(hipEventRecord(m->slice0_done, cs));
+        m->slice0_recorded = true;
     }
     return CCS_OK;
 }
+
 
 int ccs_module_forward_split(ccs_module *m, const ccs_batch *full, void *caller_stream)
 {
@@ -869,6 +909,10 @@ int ccs_module_copy(ccs_module *m, int32_t replica, void *dst_arena, void *strea
         // order after everything the replica has enqueued so far (its pack/clone included)
         CCS_HIP(hipEventRecord(R.done, R.stream));
         CCS_HIP(hipStreamWaitEvent(st, R.done, 0));
+    }
+    {   // ... and after a slice 0 that ran on some caller's stream
+        const int rc0 = wait_slice0(m, replica, st);
+        if (rc0 != CCS_OK) return rc0;
     }
     const bool prof_on = true;
     CCS_STAGE(CCS_ST_CLONE, ccs::launch_clone(dst_arena, R.arena, m->ap.total, st));
@@ -942,6 +986,7 @@ int ccs_module_sync(ccs_module *m)
 {
     if (!m) return fail(CCS_EINVAL, "module is null");
     for (int j = 0; j < m->k; ++j) CCS_HIP(hipStreamSynchronize(m->rep[j].stream));
+    if (m->slice0_recorded) CCS_HIP(hipEventSynchronize(m->slice0_done));
     return CCS_OK;
 }
 
@@ -955,7 +1000,9 @@ int ccs_module_destroy(ccs_module *m)
         if (R.done) (void)hipEventDestroy(R.done);
         prof_free(R);
     }
+    if (m->slice0_recorded) (void)hipEventSynchronize(m->slice0_done);
     if (m->fork) (void)hipEventDestroy(m->fork);
+    if (m->slice0_done) (void)hipEventDestroy(m->slice0_done);
     delete m;
     return CCS_OK;
 }

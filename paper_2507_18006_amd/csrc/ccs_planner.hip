@@ -60,6 +60,39 @@ double ccs_speedup(const int32_t *p, int32_t n, const double *bs, const double *
     return w0 / (w + delta * t);                                          // Eq. 3
 }
 
+int ccs_shares_from_capacity(int64_t n, int32_t k, const double *capacity, int32_t *counts_out)
+{
+    if (!capacity || !counts_out || k < 1 || k > CCS_MAX_REPLICAS || n < 0 || n > 0x7fffffffLL) return CCS_EINVAL;
+    double total = 0.0;
+    for (int32_t j = 0; j < k; ++j) {
+        if (!(capacity[j] > 0.0) || capacity[j] > 1e300) return CCS_EINVAL;
+        total += capacity[j];
+    }
+    // capacity-weighted contiguous split: boundary j = floor(n * (C_0 + .. + C_{j-1}) / C_total)
+    double before = 0.0;
+    int64_t lo = 0;
+    for (int32_t j = 0; j < k; ++j) {
+        before += capacity[j];
+        int64_t hi = j == k - 1 ? n : (int64_t)__builtin_floor((double)n * before / total);
+        if (hi < lo) hi = lo;
+        if (hi > n) hi = n;
+        counts_out[j] = (int32_t)(hi - lo);
+        lo = hi;
+    }
+    // hand units from a slowest instance to the one that stays fastest, while that helps
+    for (;;) {
+        int32_t worst = 0, taker = 0;
+        for (int32_t j = 1; j < k; ++j) {
+            if (counts_out[j] / capacity[j] > counts_out[worst] / capacity[worst]) worst = j;
+            if ((counts_out[j] + 1) / capacity[j] < (counts_out[taker] + 1) / capacity[taker]) taker = j;
+        }
+        if (counts_out[worst] == 0 || (counts_out[taker] + 1) / capacity[taker] >= counts_out[worst] / capacity[worst]) break;
+        counts_out[worst] -= 1;
+        counts_out[taker] += 1;
+    }
+    return CCS_OK;
+}
+
 int ccs_plan_scale_up(const int32_t *p_in, int32_t n, double gamma, const int64_t *node_available, int32_t n_nodes,
                       int64_t replica_size, const uint8_t *placed_in, int32_t *p_out, uint8_t *placed_out,
                       double *speedup_out)

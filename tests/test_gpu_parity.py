@@ -372,7 +372,9 @@ def test_uneven_shares_give_the_same_bits_as_any_other_partition():
         base = db.out().copy()
         assert U.rel_err(base, ref) <= TOL["bf16"]
         m.replicate(3)
-        for counts in ([10, 4, 1], [0, 15, 0], [1, 1, 13], [5, 5, 5]):
+        by_capacity = B.shares_from_capacity(cfg.n_seqs, [1.0, 3.0, 0.5])     # shares that follow capacities (Eq. 1)
+        assert sum(by_capacity) == cfg.n_seqs
+        for counts in ([10, 4, 1], [0, 15, 0], [1, 1, 13], [5, 5, 5], by_capacity):
             say(f"[case] shares {counts}")
             db2 = U.DeviceBatch(m, cfg, inp)
             m.forward_shares(db2.batch, counts)
@@ -612,6 +614,68 @@ def test_forward_split_recorded_in_a_hip_graph_replays_like_eager():
                 torch.cuda.synchronize()
                 assert torch.equal(db.y, ref.y), f"k={k} replay {rep} differs from eager"
                 assert torch.equal(db.k, ref.k) and torch.equal(db.v, ref.v)
+    finally:
+        m.destroy()
+
+
+def test_slice0_on_a_foreign_stream_is_ordered_with_copies_migrations_and_replica0_forwards():
+    """forward_split from a stream that is not replica 0's: slice 0 runs there, and a migration of
+    replica 0 issued afterwards on a third stream (old arena overwritten once that stream has
+    drained) must neither disturb that forward nor the next one."""
+    cfg = workloads.scaled(C["C2"], hidden=1024, n_q_heads=8, n_kv_heads=8, intermediate=2752, n_seqs=12,
+                           len_lo=10, len_hi=300)
+    w = workloads.make_weights(cfg, 90)
+    inp = workloads.make_inputs(cfg, 90)
+    m = U.make_module(cfg, w)
+    try:
+        base = U.DeviceBatch(m, cfg, inp)
+        m.forward_split(base.batch)
+        y0 = base.out()
+        m.replicate(2)
+        side, third = torch.cuda.Stream(), torch.cuda.Stream()
+        for rep in range(3):
+            say(f"[case] foreign-stream forward_split + migrate, round {rep}")
+            db = U.DeviceBatch(m, cfg, inp)
+            torch.cuda.synchronize()
+            m.forward_split(db.batch, stream=side)
+            old = m.migrate(0, stream=third)          # waits for slice 0 on `side`, then copies; returns after `third` drained
+            old.fill_(0xFF)                           # the old arena is the caller's again
+            db2 = U.DeviceBatch(m, cfg, inp)
+            m.forward(0, db2.batch)                   # replica 0 on its own stream: ordered after the migration
+            m.forward_split(db.batch, stream=side)    # again from the foreign stream: same rows, same bits
+            side.synchronize()
+            m.sync()
+            assert np.array_equal(db.out(), y0)
+            assert np.array_equal(db2.out(), y0)
+    finally:
+        m.destroy()
+
+
+def test_a_slice_that_fails_after_the_fork_leaves_no_unjoined_stream_in_a_capture():
+    """Shares 1 + 40 with workspaces sized for 8 sequences: slice 0 is enqueued, slice 1 is refused
+    (CCS_ENOMEM) after its stream was forked.  The capture must still end cleanly, which it only
+    does when every forked stream was joined back."""
+    cfg = workloads.scaled(C["C2"], hidden=512, n_q_heads=4, n_kv_heads=4, intermediate=1024, n_seqs=41,
+                           len_lo=0, len_hi=60)
+    small = workloads.scaled(cfg, n_seqs=8)
+    m = U.make_module(small, workloads.make_weights(cfg, 91))
+    try:
+        m.replicate(2)
+        db = U.DeviceBatch(m, cfg, workloads.make_inputs(cfg, 91))
+        warm = U.DeviceBatch(m, small, workloads.make_inputs(small, 92))
+        m.forward_split(warm.batch)
+        m.sync()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        say("[case] failing slice inside a capture")
+        with torch.cuda.graph(g, stream=side):
+            with pytest.raises(B.CcsError) as e:
+                m.forward_shares(db.batch, [1, 40])
+            assert e.value.status == B.CCS_ENOMEM
+        torch.cuda.synchronize()
+        m.forward_split(warm.batch)                # the module is still usable
+        m.sync()
     finally:
         m.destroy()
 

@@ -83,6 +83,82 @@ def test_greedy_scale_up_properties():
     assert p == [1] * 6 and sp == 1.0 and sum(placed[0]) == 0
 
 
+def test_greedy_scale_up_is_the_best_subset_of_its_offers():
+    """Eq. 4 grows with every p_i while gamma < 1, so no subset of the offers beats taking them
+    all: the fold's result equals an exhaustive search over the subsets (small cases)."""
+    import itertools
+    rng = random.Random(13)
+    for _ in range(25):
+        n = rng.randint(1, 6)
+        p0 = [rng.randint(1, 3) for _ in range(n)]
+        nodes = [rng.randint(0, 350) for _ in range(rng.randint(1, 3))]
+        gamma = rng.uniform(0.0, 0.6)
+        placed0 = [[0] * n for _ in nodes]
+        offers = P.scale_up_offers(n, nodes, 100, placed0)
+        best = 0.0
+        for r in range(len(offers) + 1):
+            for sub in itertools.combinations(offers, r):
+                p = list(p0)
+                for _, layer in sub:
+                    p[layer] += 1
+                best = max(best, P.speedup_homo(p, gamma))
+        got = P.plan_scale_up(p0, gamma, nodes, 100)
+        assert math.isclose(got[2], best, rel_tol=1e-14)
+        assert sum(got[0]) - sum(p0) == len(offers)
+
+
+# ---------------------------------------------------------------- batch shares from capacities (Eq. 1)
+def compositions(n, k):
+    if k == 1:
+        yield (n,)
+        return
+    for first in range(n + 1):
+        for rest in compositions(n - first, k - 1):
+            yield (first,) + rest
+
+
+def test_shares_from_capacity_minimise_the_slowest_instance():
+    """Against exhaustive search over every way to cut n into k non-negative integers."""
+    rng = random.Random(17)
+    for _ in range(200):
+        k = rng.randint(1, 4)
+        n = rng.randint(0, 14)
+        cap = [rng.choice([1.0, 2.0, 3.0, 0.5, 10.0, 1.7]) for _ in range(k)]
+        got = P.shares_from_capacity(n, cap)
+        assert len(got) == k and sum(got) == n and min(got) >= 0
+        best = min(P.slowest_instance(c, cap) for c in compositions(n, k))
+        assert P.slowest_instance(got, cap) == best, (n, cap, got)
+
+
+def test_shares_from_capacity_special_cases():
+    import oracle
+    # equal capacities: the paper's contiguous split, 15 -> 7 + 8 (Section 3.1)
+    assert P.shares_from_capacity(15, [1.0, 1.0]) == [7, 8]
+    for n in (0, 1, 7, 15, 64, 1000):
+        for k in (1, 2, 3, 4, 7, 16):
+            b = oracle.split_bounds(n, k)
+            assert P.shares_from_capacity(n, [2.5] * k) == [b[j + 1] - b[j] for j in range(k)]
+    # shares proportional to capacity: 1 : 3 on 16 -> 4 + 12, the case the speed-up model prices above
+    assert P.shares_from_capacity(16, [1.0, 3.0]) == [4, 12]
+    assert P.shares_from_capacity(5, [10.0, 1.0]) == [5, 0]     # the weighted floor split alone would say 4 + 1
+    assert P.shares_from_capacity(5, [1.0, 10.0]) == [0, 5]
+    # the model's own arithmetic: proportional shares equalise the instances (Eq. 1)
+    sh = P.shares_from_capacity(64, [1.0, 3.0])
+    assert sh == [16, 48] and P.slowest_instance(sh, [1.0, 3.0]) == 16.0
+
+
+def test_library_shares_match_oracle():
+    rng = random.Random(19)
+    for _ in range(300):
+        k = rng.randint(1, 16)
+        n = rng.choice([0, 1, 2, 15, 64, 100, 4096, rng.randint(0, 100000)])
+        cap = [rng.choice([1.0, 1.0, 2.0, 3.0, 0.25, rng.uniform(0.1, 50.0)]) for _ in range(k)]
+        assert B.shares_from_capacity(n, cap) == P.shares_from_capacity(n, cap), (n, cap)
+    for bad in ((5, []), (5, [1.0, 0.0]), (5, [1.0, -2.0]), (-1, [1.0]), (5, [float("nan")]), (5, [1.0] * 17)):
+        with pytest.raises(B.CcsError):
+            B.shares_from_capacity(*bad)
+
+
 # ---------------------------------------------------------------- library == oracle
 def test_library_speedup_matches_oracle():
     rng = random.Random(5)

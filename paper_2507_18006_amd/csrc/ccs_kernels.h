@@ -104,6 +104,30 @@ size_t tiled_partial_bytes(int M, int N, int K, long variant_rows);
 hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void *res, void *out,
                              int M, int N, int K, long variant_rows, float *partials, hipStream_t st);
 
+// ---- weight-streaming projections, one launch each (ccs_gemm_stream.hip) -----------------------
+// For M <= kSkinnyMaxRows rows.  Weights are fragment-packed in groups of G 16-row blocks
+// (ccs_common.h); x is either fragment-packed or the row-major bf16 rows [M, K] themselves, and
+// with `gain` (row-major x only) the kernel also applies RMSNorm(x; gain, eps) in front of the
+// projection.  A row's result depends on that row alone.
+enum { GS_STORE = 0, GS_SWIGLU = 1, GS_QKV_DECODE = 2 };
+hipError_t init_gemm_stream_kernels();
+// Group size of a store-type weight [N, K] (O, down, a single projection): also its tile width.
+int stream_store_nb(int N);
+// out[m, n] = sum_k x'[m, k] W[n, k] (+ res[m, n]), row-major bf16 [M, N]; the tile is one group.
+hipError_t launch_gemm_stream_store(const void *Wp, int G, int nb, const void *X, bool x_rows, const void *gain, float eps,
+                                    const void *res, void *out, int M, int N, int K, hipStream_t st);
+// u = silu(gate) * up, fragment-packed [M16, N2 / 2]; weight [N2, K] with gate / up interleaved in
+// 16-row blocks, grouped by kWGroup; x row-major with RMSNorm gains.
+hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *x_rows, const void *gain, float eps, void *u_packed,
+                                     int M, int N2, int K, hipStream_t st);
+// Decode Q/K/V projection (head_dim 128, weight [Wq; Wk; Wv] grouped by kWGroup = one head) with
+// RMSNorm in front and, behind it, the rotary embedding at position lens[m], the q store into the
+// row-major qkv buffer [M, (nq + 2 nkv) * 128] and the append of the rotated key and the value at
+// cache slot lens[m] (caches [M, nkv, cap, 128]).
+hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *x_rows, const void *gain, float eps, void *qkv,
+                                         int M, int nq, int nkv, int K, const void *tab, const int32_t *lens_dev,
+                                         void *k_cache, void *v_cache, int cap, hipStream_t st);
+
 // ---- attention (ccs_attention.hip) ---------------------------------------------------------
 // Generic (slow, any head_dim <= 256) softmax attention: one wavefront per query row.
 // Query rows come from qkv row-major [rows, (nq+2nkv)*d].  prefill: keys/values are the k/v

@@ -652,10 +652,10 @@ def test_slice0_on_a_foreign_stream_is_ordered_with_copies_migrations_and_replic
 
 
 def test_a_slice_that_fails_after_the_fork_leaves_no_unjoined_stream_in_a_capture():
-    """Shares 1 + 40 with workspaces sized for 8 sequences: slice 0 is enqueued, slice 1 is refused
+    """Shares 1 + 200 with workspaces sized for 8 sequences: slice 0 is enqueued, slice 1 is refused
     (CCS_ENOMEM) after its stream was forked.  The capture must still end cleanly, which it only
     does when every forked stream was joined back."""
-    cfg = workloads.scaled(C["C2"], hidden=512, n_q_heads=4, n_kv_heads=4, intermediate=1024, n_seqs=41,
+    cfg = workloads.scaled(C["C2"], hidden=512, n_q_heads=4, n_kv_heads=4, intermediate=1024, n_seqs=201,
                            len_lo=0, len_hi=60)
     small = workloads.scaled(cfg, n_seqs=8)
     m = U.make_module(small, workloads.make_weights(cfg, 91))
@@ -671,7 +671,7 @@ def test_a_slice_that_fails_after_the_fork_leaves_no_unjoined_stream_in_a_captur
         say("[case] failing slice inside a capture")
         with torch.cuda.graph(g, stream=side):
             with pytest.raises(B.CcsError) as e:
-                m.forward_shares(db.batch, [1, 40])
+                m.forward_shares(db.batch, [1, 200])
             assert e.value.status == B.CCS_ENOMEM
         torch.cuda.synchronize()
         m.forward_split(warm.batch)                # the module is still usable

@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcocoserve_mi.so")
-SOURCES = ["ccs_elementwise.hip", "ccs_gemm.hip", "ccs_attention.hip", "ccs_module.hip", "ccs_planner.hip"]
+SOURCES = ["ccs_elementwise.hip", "ccs_gemm.hip", "ccs_gemm_stream.hip", "ccs_attention.hip", "ccs_module.hip", "ccs_planner.hip"]
 # packed-fp32 VALU forms are switched off on purpose (device pass only; the host pass warns
 # that it does not know the feature, which is harmless)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -51,7 +51,8 @@ hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4 *__restrict__ src,
                                                         uint4 *__restrict__ dst, int N, int K,
-                                                        int blk_stride, int blk_offset, int grouped)
+                                                        int blk_stride, int blk_offset, int grouped,
+                                                        const uint4 *__restrict__ gain)
 {
     const int kchunks = K >> 3;
     const size_t total = (size_t)N * kchunks;
@@ -60,18 +61,26 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4 *__restrict_
         int n = (int)(i / kchunks), kc = (int)(i % kchunks);
         int nb = (n >> 4) * blk_stride + blk_offset;
         const size_t frag = grouped ? weight_fragment(nb, kc >> 2, kfrags) : (size_t)nb * kfrags + (kc >> 2);
-        dst[frag * 64 + (n & 15) + 16 * (kc & 3)] = src[i];
+        uint4 v = src[i];
+        if (gain) {   // fold the gains of the RMSNorm in front of this projection into the weight
+            const uint4 g = gain[kc];
+            v.x = pack2bf(bf_lo(v.x) * bf_lo(g.x), bf_hi(v.x) * bf_hi(g.x));
+            v.y = pack2bf(bf_lo(v.y) * bf_lo(g.y), bf_hi(v.y) * bf_hi(g.y));
+            v.z = pack2bf(bf_lo(v.z) * bf_lo(g.z), bf_hi(v.z) * bf_hi(g.z));
+            v.w = pack2bf(bf_lo(v.w) * bf_lo(g.w), bf_hi(v.w) * bf_hi(g.w));
+        }
+        dst[frag * 64 + (n & 15) + 16 * (kc & 3)] = v;
     }
 }
 
 hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int blk_stride,
-                            int blk_offset, bool grouped, hipStream_t st)
+                            int blk_offset, bool grouped, const void *gain, hipStream_t st)
 {
     size_t total = (size_t)N * (K / 8);
     if (!total) return hipSuccess;
     int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
     hipLaunchKernelGGL(pack_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src,
-                       (uint4 *)dst_packed, N, K, blk_stride, blk_offset, grouped ? 1 : 0);
+                       (uint4 *)dst_packed, N, K, blk_stride, blk_offset, grouped ? 1 : 0, (const uint4 *)gain);
     return hipGetLastError();
 }
 
@@ -133,7 +142,7 @@ __global__ __launch_bounds__(512) void rmsnorm_bf16_block_kernel(const uint4 *__
     for (int i = 0; i < HOLD; ++i) {
         const int f = w + kNormWaves * i;
         if (f < kfrags) {
-            const uint4 gv = g[4 * f + q];
+            const uint4 gv = g ? g[4 * f + q] : make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);   // bf16 1.0
             const uint32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
             const uint32_t ge[4] = {gv.x, gv.y, gv.z, gv.w};
             uint4 o;
@@ -173,7 +182,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint4 *__restri
     ss = wave_sum(ss);
     const float r = 1.0f / sqrtf(ss / (float)H + eps);
     for (int c = lane; c < chunks; c += 64) {
-        uint4 v = xr[c], gv = g[c];
+        uint4 v = xr[c], gv = g ? g[c] : make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
         const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
         uint32_t o[4];
@@ -479,182 +488,6 @@ __global__ void rope_table_kernel(float2 *tab, int d, float base)
 hipError_t launch_rope_table(void *tab, int d, float base, hipStream_t st)
 {
     hipLaunchKernelGGL(rope_table_kernel, dim3((d / 2 + 63) / 64), dim3(64), 0, st, (float2 *)tab, d, base);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------------
-// Decode, bf16, head_dim 128: epilogue of the weight-streaming Q/K/V projection.  Sums the K
-// segments' partials in segment order, rotates q and k to position lens[row], stores q (bf16)
-// into the row-major qkv buffer and appends the rotated key and the value at cache slot
-// lens[row].  One thread owns 4 columns of the first half of a head and their partners 64 up.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void qkv_reduce_rope_decode_kernel(
-    const float *__restrict__ part, int S, int M, int nq, int nkv, const float2 *__restrict__ tab,
-    const int32_t *__restrict__ lens, bf16_t *__restrict__ qkv, bf16_t *__restrict__ k_cache,
-    bf16_t *__restrict__ v_cache, int cap)
-{
-    const int heads = nq + 2 * nkv, width = heads * 128;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= M * heads * 16) return;
-    const int m = idx / (heads * 16), hu = idx % (heads * 16);
-    const int head = hu >> 4, c = (hu & 15) * 4;
-    const size_t seg = (size_t)M * width;
-    const float *p = part + (size_t)m * width + head * 128 + c;
-    float4 lo = *(const float4 *)p, hi = *(const float4 *)(p + 64);
-    for (int k = 1; k < S; ++k) {
-        const float4 a = *(const float4 *)(p + k * seg), b = *(const float4 *)(p + k * seg + 64);
-        lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
-        hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
-    }
-    const int pos = cached_len(lens, m, cap);
-    float l[4] = {lo.x, lo.y, lo.z, lo.w}, h[4] = {hi.x, hi.y, hi.z, hi.w};
-    if (head < nq + nkv) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float cs, sn;
-            rope_cs(tab, c + e, pos, cs, sn);
-            const float a = l[e], b = h[e];
-            l[e] = a * cs - b * sn;
-            h[e] = b * cs + a * sn;
-        }
-    }
-    const uint2 plo = make_uint2(pack2bf(l[0], l[1]), pack2bf(l[2], l[3]));
-    const uint2 phi = make_uint2(pack2bf(h[0], h[1]), pack2bf(h[2], h[3]));
-    bf16_t *dst;
-    if (head < nq) dst = qkv + (size_t)m * width + head * 128 + c;
-    else if (head < nq + nkv) dst = k_cache + (((size_t)m * nkv + (head - nq)) * cap + pos) * 128 + c;
-    else dst = v_cache + (((size_t)m * nkv + (head - nq - nkv)) * cap + pos) * 128 + c;
-    *(uint2 *)dst = plo;
-    *(uint2 *)(dst + 64) = phi;
-}
-
-hipError_t launch_qkv_reduce_rope_decode(const float *partials, int S, int M, int nq, int nkv, const void *tab,
-                                         const int32_t *lens_dev, void *qkv, void *k_cache, void *v_cache,
-                                         int cap, hipStream_t st)
-{
-    if (M <= 0) return hipSuccess;
-    const int total = M * (nq + 2 * nkv) * 16;
-    hipLaunchKernelGGL(qkv_reduce_rope_decode_kernel, dim3((total + 255) / 256), dim3(256), 0, st, partials, S, M, nq,
-                       nkv, (const float2 *)tab, lens_dev, (bf16_t *)qkv, (bf16_t *)k_cache, (bf16_t *)v_cache, cap);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------------
-// Decode, bf16: epilogue of the weight-streaming O projection fused with the second RMSNorm.
-// One workgroup per row: x1 = bf16(sum of partials in segment order + x), stored row-major;
-// h2 = RMSNorm(x1; g2) stored fragment-packed.  The sum of squares is reduced in a fixed order
-// (thread partials, wavefront butterfly, wavefronts 0..15), so a row's bits do not depend on the
-// batch.  H <= 8192.  1024 threads per row: one or two 16-byte columns each, segment loads batched.
-// ---------------------------------------------------------------------------------------------
-constexpr int kRowNormMaxH = 8192;
-
-__global__ __launch_bounds__(1024) void reduce_residual_rmsnorm_kernel(
-    const float *__restrict__ part, int S, int M, int H, const bf16_t *__restrict__ res,
-    const bf16_t *__restrict__ g, float eps, bf16_t *__restrict__ x1, bf16_t *__restrict__ h2)
-{
-    __shared__ float wsum[16];
-    const int m = blockIdx.x, tid = threadIdx.x;
-    const size_t seg = (size_t)M * H;
-    float v[kRowNormMaxH / 4096][4];
-    float ss = 0.f;
-#pragma unroll
-    for (int j = 0; j < kRowNormMaxH / 4096; ++j) {
-        const int c = (tid + 1024 * j) * 4;
-        if (c < H) {
-            const float *p = part + (size_t)m * H + c;
-            float4 s = *(const float4 *)p;
-            int k = 1;
-            for (; k + 3 < S; k += 4) {   // four loads in flight, added in segment order
-                const float4 t0 = *(const float4 *)(p + k * seg), t1 = *(const float4 *)(p + (k + 1) * seg);
-                const float4 t2 = *(const float4 *)(p + (k + 2) * seg), t3 = *(const float4 *)(p + (k + 3) * seg);
-                s.x += t0.x; s.y += t0.y; s.z += t0.z; s.w += t0.w;
-                s.x += t1.x; s.y += t1.y; s.z += t1.z; s.w += t1.w;
-                s.x += t2.x; s.y += t2.y; s.z += t2.z; s.w += t2.w;
-                s.x += t3.x; s.y += t3.y; s.z += t3.z; s.w += t3.w;
-            }
-            for (; k < S; ++k) {
-                const float4 t = *(const float4 *)(p + k * seg);
-                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
-            }
-            const uint2 r = *(const uint2 *)(res + (size_t)m * H + c);
-            const uint2 o = make_uint2(pack2bf(s.x + bf_lo(r.x), s.y + bf_hi(r.x)), pack2bf(s.z + bf_lo(r.y), s.w + bf_hi(r.y)));
-            *(uint2 *)(x1 + (size_t)m * H + c) = o;
-            v[j][0] = bf_lo(o.x); v[j][1] = bf_hi(o.x); v[j][2] = bf_lo(o.y); v[j][3] = bf_hi(o.y);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) ss = fmaf(v[j][e], v[j][e], ss);
-        }
-    }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) wsum[tid >> 6] = ss;
-    __syncthreads();
-    float tot = wsum[0];
-#pragma unroll
-    for (int w = 1; w < 16; ++w) tot += wsum[w];
-    const float r = 1.0f / sqrtf(tot / (float)H + eps);
-#pragma unroll
-    for (int j = 0; j < kRowNormMaxH / 4096; ++j) {
-        const int c = (tid + 1024 * j) * 4;
-        if (c < H) {
-            const uint2 gv = *(const uint2 *)(g + c);
-            *(uint2 *)(h2 + packed_index(m, c, H >> 5)) =
-                make_uint2(pack2bf(v[j][0] * r * bf_lo(gv.x), v[j][1] * r * bf_hi(gv.x)),
-                           pack2bf(v[j][2] * r * bf_lo(gv.y), v[j][3] * r * bf_hi(gv.y)));
-        }
-    }
-}
-
-hipError_t launch_reduce_residual_rmsnorm(const float *partials, int S, int M, int H, const void *res, const void *g,
-                                          float eps, void *x1, void *h2, hipStream_t st)
-{
-    if (M <= 0) return hipSuccess;
-    if (H > kRowNormMaxH || (H & 3)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(reduce_residual_rmsnorm_kernel, dim3(M), dim3(1024), 0, st, partials, S, M, H, (const bf16_t *)res,
-                       (const bf16_t *)g, eps, (bf16_t *)x1, (bf16_t *)h2);
-    return hipGetLastError();
-}
-
-// RMSNorm for few rows (decode): one workgroup per row, same fixed reduction order as above.
-__global__ __launch_bounds__(256) void rmsnorm_bf16_row_kernel(const bf16_t *__restrict__ x,
-                                                               const bf16_t *__restrict__ g,
-                                                               bf16_t *__restrict__ out, int H, float eps)
-{
-    __shared__ float wsum[4];
-    const int m = blockIdx.x, tid = threadIdx.x;
-    float v[kRowNormMaxH / 1024][4];
-    float ss = 0.f;
-#pragma unroll
-    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
-        const int c = (tid + 256 * j) * 4;
-        if (c < H) {
-            const uint2 o = *(const uint2 *)(x + (size_t)m * H + c);
-            v[j][0] = bf_lo(o.x); v[j][1] = bf_hi(o.x); v[j][2] = bf_lo(o.y); v[j][3] = bf_hi(o.y);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) ss = fmaf(v[j][e], v[j][e], ss);
-        }
-    }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) wsum[tid >> 6] = ss;
-    __syncthreads();
-    const float tot = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
-    const float r = 1.0f / sqrtf(tot / (float)H + eps);
-#pragma unroll
-    for (int j = 0; j < kRowNormMaxH / 1024; ++j) {
-        const int c = (tid + 256 * j) * 4;
-        if (c < H) {
-            const uint2 gv = *(const uint2 *)(g + c);
-            *(uint2 *)(out + packed_index(m, c, H >> 5)) =
-                make_uint2(pack2bf(v[j][0] * r * bf_lo(gv.x), v[j][1] * r * bf_hi(gv.x)),
-                           pack2bf(v[j][2] * r * bf_lo(gv.y), v[j][3] * r * bf_hi(gv.y)));
-        }
-    }
-}
-
-hipError_t launch_rmsnorm_rows(const void *x, const void *g, void *out, int rows, int H, float eps, hipStream_t st)
-{
-    if (rows <= 0) return hipSuccess;
-    if (H > kRowNormMaxH || (H & 3)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(rmsnorm_bf16_row_kernel, dim3(rows), dim3(256), 0, st, (const bf16_t *)x, (const bf16_t *)g,
-                       (bf16_t *)out, H, eps);
     return hipGetLastError();
 }
 

@@ -8,10 +8,11 @@
 //  * gemm_tiled_dma: LDS-tiled, for compute-bound row counts (prefill): 256 x 128 x 32 workgroup
 //    tiles of v_mfma_f32_32x32x16_bf16, operands brought in by direct-to-LDS loads through a
 //    3-stage ring, optional deterministic K split for launches that cannot fill the GPU.
-//  * gemm_skinny: weight-streaming for <= 64 rows (decode), v_mfma_f32_16x16x32_bf16: no LDS
+//  * gemm_skinny: weight-streaming with a K split for <= 64 rows, v_mfma_f32_16x16x32_bf16: no LDS
 //    staging of operands, each wavefront streams 8 KiB weight pieces straight into MFMA operands;
 //    K is cut into segments whose count depends on the weight shape only and partial sums are
-//    reduced in a fixed order, so a row's bits never depend on which other rows share the launch.
+//    reduced in a fixed order by a second kernel.  Used where the one-launch form
+//    (ccs_gemm_stream.hip) is slower: 33..64 rows against a long-K weight.
 //  * gemm_f32: plain FMA kernel for the fp32 path.
 #include "ccs_common.h"
 #include "ccs_kernels.h"
@@ -73,7 +74,6 @@ constexpr int kSkU = 2;          // most k-steps (8 KiB of weights each) per reg
 // one workgroup per CU - long streams per wavefront beat more, shorter ones (every wavefront
 // pays a pipeline fill and an epilogue) - so K is cut into floor(256 / tiles) segments.
 constexpr int kSkWaves = 4;
-enum { SK_PARTIALS = 0, SK_STORE_RM = 1, SK_SWIGLU_PACKED = 2 };   // what the kernel writes
 
 static inline int sk_tiles(int N) { return (N / 16 + kSkNB - 1) / kSkNB; }
 
@@ -95,10 +95,10 @@ size_t skinny_partial_bytes(int M, int N, int K)
 
 // (3 or 4 row blocks: 128 accumulator registers plus two 2-step register sets need more than 256
 // registers, so one workgroup per CU; measured faster than 1-step sets at two workgroups per CU)
-template <int MB, int EPI>
+template <int MB>
 __global__ __launch_bounds__(kSkWaves * 64, MB <= 2 ? 2 : 1) void gemm_skinny_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, float *__restrict__ part, int nblk,
-    int kfrags, int ntiles, int kf_seg, int M, int N, const bf16_t *__restrict__ res, bf16_t *__restrict__ out)
+    int kfrags, int ntiles, int kf_seg, int M, int N)
 {
     extern __shared__ float red[];   // two buffers of MB*16 padded rows
     const int lane = threadIdx.x & 63;
@@ -191,34 +191,10 @@ __global__ __launch_bounds__(kSkWaves * 64, MB <= 2 ? 2 : 1) void gemm_skinny_ke
         return v;
     };
     constexpr int QUADS = MB * 16 * (kSkNB * 4);   // float4 outputs of the tile
-    if (EPI == SK_PARTIALS) {
-        for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
-            const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
-            const int n = tile * (kSkNB * 16) + c;
-            if (m < M && n < N) *(float4 *)(part + ((size_t)seg * M + m) * N + n) = fetch(m, c);
-        }
-    } else if (EPI == SK_STORE_RM) {   // the launch has one K segment: the tile is final
-        for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
-            const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
-            const int n = tile * (kSkNB * 16) + c;
-            if (m >= M || n >= N) continue;
-            float4 v = fetch(m, c);
-            if (res) {
-                const uint2 r = *(const uint2 *)(res + (size_t)m * N + n);
-                v.x += bf_lo(r.x); v.y += bf_hi(r.x); v.z += bf_lo(r.y); v.w += bf_hi(r.y);
-            }
-            *(uint2 *)(out + (size_t)m * N + n) = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
-        }
-    } else {   // SK_SWIGLU_PACKED, one K segment: the tile's 8 weight blocks are 4 (gate, up) pairs, 64 columns of u
-        for (int q = threadIdx.x; q < QUADS / 2; q += kSkWaves * 64) {
-            const int m = q / (kSkNB * 2), pr = (q % (kSkNB * 2)) / 4, c4 = (q % 4) * 4;
-            const int col = (tile * (kSkNB / 2) + pr) * 16 + c4;   // column of u
-            if (m >= M || col >= N / 2) continue;
-            const float4 g = fetch(m, pr * 32 + c4), u = fetch(m, pr * 32 + 16 + c4);
-            const float o0 = g.x / (1.0f + __expf(-g.x)) * u.x, o1 = g.y / (1.0f + __expf(-g.y)) * u.y;
-            const float o2 = g.z / (1.0f + __expf(-g.z)) * u.z, o3 = g.w / (1.0f + __expf(-g.w)) * u.w;
-            *(uint2 *)(out + packed_index(m, col, (N / 2) >> 5)) = make_uint2(pack2bf(o0, o1), pack2bf(o2, o3));
-        }
+    for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
+        const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
+        const int n = tile * (kSkNB * 16) + c;
+        if (m < M && n < N) *(float4 *)(part + ((size_t)seg * M + m) * N + n) = fetch(m, c);
     }
 }
 
@@ -226,7 +202,8 @@ __global__ __launch_bounds__(kSkWaves * 64, MB <= 2 ? 2 : 1) void gemm_skinny_ke
 __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restrict__ part, int S, int M,
                                                             int N, int epi,
                                                             const bf16_t *__restrict__ res,
-                                                            bf16_t *__restrict__ out)
+                                                            bf16_t *__restrict__ out,
+                                                            bf16_t *__restrict__ out_packed)
 {
     const int ncols = (epi == EPI_SWIGLU_PACKED) ? N / 2 : N;  // output columns
     const int q_per_row = ncols / 4;
@@ -245,7 +222,9 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restr
             uint2 r = *(const uint2 *)(res + (size_t)m * N + c);
             s.x += bf_lo(r.x); s.y += bf_hi(r.x); s.z += bf_lo(r.y); s.w += bf_hi(r.y);
         }
-        *(uint2 *)(out + (size_t)m * N + c) = make_uint2(pack2bf(s.x, s.y), pack2bf(s.z, s.w));
+        const uint2 o = make_uint2(pack2bf(s.x, s.y), pack2bf(s.z, s.w));
+        *(uint2 *)(out + (size_t)m * N + c) = o;
+        if (out_packed) *(uint2 *)(out_packed + packed_index(m, c, N >> 5)) = o;
     } else {
         // gate columns of output block jb live at packed-weight block 2*jb, up columns at 2*jb+1
         const int gcol = (c >> 4) * 32 + (c & 15);
@@ -264,73 +243,46 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restr
 
 constexpr int sk_lds_bytes(int MB) { return 2 * MB * 16 * (kSkNB * 16 + 4) * (int)sizeof(float); }
 
-template <int MB, int EPI>
+template <int MB>
 static hipError_t sk_launch(dim3 grid, hipStream_t st, const uint4 *Wp, const uint4 *Xp, float *partials, int nblk,
-                            int kfrags, int ntiles, int kf_seg, int M, int N, const bf16_t *res, bf16_t *out)
+                            int kfrags, int ntiles, int kf_seg, int M, int N)
 {
     constexpr int kLds = sk_lds_bytes(MB);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MB, EPI>), grid, dim3(kSkWaves * 64), kLds, st, Wp, Xp, partials, nblk,
-                       kfrags, ntiles, kf_seg, M, N, res, out);
+    hipLaunchKernelGGL((gemm_skinny_kernel<MB>), grid, dim3(kSkWaves * 64), kLds, st, Wp, Xp, partials, nblk, kfrags,
+                       ntiles, kf_seg, M, N);
     return hipGetLastError();
 }
 
-// With one K segment the kernel applies the epilogue itself (no partial sums, no second kernel);
-// with several it writes partial sums and the caller runs the reduction (launch_gemm_skinny_reduce
-// or a fused one).  *fused tells which.  (Letting the workgroup that completes a tile's last
-// segment do the reduction needs device-scope fences in every workgroup; measured, they cost
-// 25-35 us per launch, several times the reduction kernel they would save.)
-hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, int M, int N, int K, int epi,
-                              const void *res, void *out, bool *fused, hipStream_t st)
+// (Letting the workgroup that completes a tile's last segment do the reduction needs device-scope
+// fences in every workgroup; measured, they cost 25-35 us per launch, several times the reduction
+// kernel they would save.)
+hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N, int K, hipStream_t st)
 {
-    if (fused) *fused = false;
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows) return hipErrorInvalidValue;
     const int kfrags = K / 32, nblk = N / 16, ntiles = sk_tiles(N);
     const int S = skinny_segments(N, K);
     const int kf_seg = (kfrags + S - 1) / S;
-    const int kind = (S == 1 && epi == EPI_STORE_RM) ? SK_STORE_RM : (S == 1 && epi == EPI_SWIGLU_PACKED) ? SK_SWIGLU_PACKED : SK_PARTIALS;
-    if (fused) *fused = kind != SK_PARTIALS;
     dim3 grid(ntiles * S);
     const int mb = (M + 15) / 16;
-    hipError_t e = hipSuccess;
-#define CCS_SK2(MBV, EPIV) e = sk_launch<MBV, EPIV>(grid, st, (const uint4 *)Wp, (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N, (const bf16_t *)res, (bf16_t *)out)
-#define CCS_SK(MBV)                                         \
-    switch (kind) {                                         \
-        case SK_STORE_RM: CCS_SK2(MBV, SK_STORE_RM); break; \
-        case SK_SWIGLU_PACKED: CCS_SK2(MBV, SK_SWIGLU_PACKED); break; \
-        default: CCS_SK2(MBV, SK_PARTIALS);                 \
-    }
+#define CCS_SK(MBV) return sk_launch<MBV>(grid, st, (const uint4 *)Wp, (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N)
     switch (mb) {
-        case 1: CCS_SK(1); break;
-        case 2: CCS_SK(2); break;
-        case 3: CCS_SK(3); break;
-        default: CCS_SK(4); break;
+        case 1: CCS_SK(1);
+        case 2: CCS_SK(2);
+        case 3: CCS_SK(3);
+        default: CCS_SK(4);
     }
 #undef CCS_SK
-#undef CCS_SK2
-    return e;
 }
 
-hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
-                                   int K, hipStream_t st)
-{
-    return launch_gemm_skinny(Wp, Xp, partials, M, N, K, -1, nullptr, nullptr, nullptr, st);
-}
-
-hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,
-                                     int M, int N, int K, hipStream_t st)
-{
-    return launch_partial_reduce(partials, skinny_segments(N, K), epi, res, out, M, N, st);
-}
-
-hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, int M,
-                                 int N, hipStream_t st)
+hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, void *out_packed,
+                                 int M, int N, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     const int ncols = (epi == EPI_SWIGLU_PACKED) ? N / 2 : N;
     const int total = M * (ncols / 4);
     hipLaunchKernelGGL(skinny_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, partials, S, M, N,
-                       epi, (const bf16_t *)res, (bf16_t *)out);
+                       epi, (const bf16_t *)res, (bf16_t *)out, (bf16_t *)out_packed);
     return hipGetLastError();
 }
 
@@ -650,7 +602,7 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
     if (S > 1) {
         hipError_t e = launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, nullptr, nullptr, M, N, K, partials, S, st);
         if (e != hipSuccess) return e;
-        return launch_partial_reduce(partials, S, epi, res, out, M, N, st);
+        return launch_partial_reduce(partials, S, epi, res, out, nullptr, M, N, st);
     }
     // 256 x 128 tiles, 3-stage ring (72 KiB): two workgroups share a CU, so one's epilogue and
     // prologue run under the other's main loop - measured 5-20 % faster than one 256 x 256 or
@@ -660,24 +612,16 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
 
 // Function attributes (dynamic LDS sizes) of this file's kernels; once per process, outside any
 // stream capture (ccs_module_create calls it).
-template <int MB>
-static hipError_t init_skinny_mb()
-{
-    const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, SK_PARTIALS>, attr, sk_lds_bytes(MB));
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, SK_STORE_RM>, attr, sk_lds_bytes(MB));
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<MB, SK_SWIGLU_PACKED>, attr, sk_lds_bytes(MB));
-    return e;
-}
-
 hipError_t init_gemm_kernels()
 {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_tiled_dma_kernel<128, 3>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)DmaCfg<128, 3>::LDS_BYTES);
-    if (e == hipSuccess) e = init_skinny_mb<1>();
-    if (e == hipSuccess) e = init_skinny_mb<2>();
-    if (e == hipSuccess) e = init_skinny_mb<3>();
-    if (e == hipSuccess) e = init_skinny_mb<4>();
+    const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<1>, attr, sk_lds_bytes(1));
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<2>, attr, sk_lds_bytes(2));
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<3>, attr, sk_lds_bytes(3));
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<4>, attr, sk_lds_bytes(4));
+    if (e == hipSuccess) e = init_gemm_stream_kernels();
     return e;
 }
 

@@ -7,20 +7,19 @@
 //     stream contiguous quarters of K (1 KiB weight fragments straight into MFMA A operands, two
 //     rolling register sets so that loads stay in flight under the MFMAs) and their accumulators
 //     are added through LDS in the fixed order (0 + 2) + (1 + 3);
-//   * the activation operand is either fragment-packed (what the attention combine and the SwiGLU
-//     epilogue produce) or the plain row-major rows of the residual stream.  For row-major rows a
-//     lane's 16 bytes of fragment slot (row r, k quarter q) are 8 consecutive k of row r, so the
-//     fragment is loaded directly; with a gain vector the kernel is also the RMSNorm in front of
-//     the projection: it multiplies by the gains on the way in (rounded to bf16, the matrix cores'
-//     input), accumulates the row's sum of squares from the same registers, and scales the
-//     accumulators by rsqrt(mean square + eps) in the epilogue - a row's scale is a scalar, so it
-//     commutes with the projection;
-//   * epilogues: store (+ residual) row-major; SwiGLU into a fragment-packed u; and for the
-//     decode Q/K/V projection the rotary embedding, the q store and the KV-cache append (a tile
-//     holds dims [32 s, 32 s + 32) and [64 + 32 s, 64 + 32 s + 32) of one head, i.e. whole rotary
-//     pairs).
-// Tile width NB and everything else about the launch depend on the weight shape only, and every
-// output row is computed from its own input row alone, so a row's bits do not depend on the batch.
+//   * the activation operand is fragment-packed.  With `norm` the kernel is also the RMSNorm in
+//     front of the projection: the weights carry the norm's gains already (folded in when the
+//     module is created), the activations are the raw rows of the residual stream, the row's sum
+//     of squares comes from one extra MFMA per fragment (the diagonal of X X^T, accumulated in
+//     fp32 in a fixed order) and the accumulators are scaled by rsqrt(mean square + eps) in the
+//     epilogue - a row's scale is a scalar, so it commutes with the projection;
+//   * epilogues: store (+ residual) row-major, optionally also fragment-packed for the next
+//     projection; SwiGLU into a fragment-packed u; and for the decode Q/K/V projection the rotary
+//     embedding, the q store and the KV-cache append (a tile holds dims [32 s, 32 s + 32) and
+//     [64 + 32 s, 64 + 32 s + 32) of one head, i.e. whole rotary pairs).
+// Tile width NB and everything else about the launch depend on the weight shape and on the row
+// count of the full batch only, and every output row is computed from its own input row alone,
+// so a row's bits do not depend on the batch.
 #include "ccs_common.h"
 #include "ccs_kernels.h"
 
@@ -28,7 +27,6 @@ namespace ccs {
 
 namespace {
 
-constexpr int kGsWaves = 4;
 
 __device__ __forceinline__ f32x4_t gs_mfma(const uint4 &a, const uint4 &b, f32x4_t c)
 {
@@ -37,18 +35,19 @@ __device__ __forceinline__ f32x4_t gs_mfma(const uint4 &a, const uint4 &b, f32x4
 }
 
 // k-steps per register set: enough bytes in flight per wavefront without spilling
-constexpr int gs_u(int MB, int NB) { return (NB + MB) <= 3 ? 6 : (NB + MB) <= 6 ? 3 : 2; }
+constexpr int gs_u(int MB, int NB) { return (NB + MB) <= 3 ? 6 : (NB + MB) <= 6 ? 4 : 2; }
 
 struct GsArgs {
     const uint4 *Wp;      // grouped fragment-packed weight
     int kfrags;           // K / 32
     int G;                // 16-row blocks per weight group (layout of Wp)
-    const void *X;        // packed fragments, or row-major bf16 rows [M, K]
-    const bf16_t *gain;   // row-major X only: RMSNorm gains (null: X is used as it is)
+    const uint4 *X;       // fragment-packed rows [M16, K]
+    int norm;             // X holds raw rows: scale row m of the result by rsqrt(mean_k x[m, k]^2 + eps)
     float eps;
     int M, N;             // rows; valid output columns
     const bf16_t *res;    // GS_STORE: optional residual, row-major [M, N]
     bf16_t *out;
+    bf16_t *out_packed;   // GS_STORE: optional second copy of the result, fragment-packed [M16, N]
     // GS_QKV_DECODE
     int nq, nkv;
     const float2 *tab;
@@ -57,11 +56,10 @@ struct GsArgs {
     int cap;
 };
 
-template <int MB, int NB, int XROWS, int EPI>
-__global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8) ? 2 : 1) void gemm_stream_kernel(const GsArgs a)
+template <int MB, int NB, int EPI, int kGsWaves, int U>
+__global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 : 1) void gemm_stream_kernel(const GsArgs a)
 {
     extern __shared__ float red[];
-    constexpr int U = gs_u(MB, NB);
     constexpr int ROWF = NB * 16 + 4;      // floats per padded LDS row: conflict-free 16-byte accesses
     constexpr int BUF = MB * 16 * ROWF;    // floats per reduction buffer
     const int lane = threadIdx.x & 63;
@@ -86,103 +84,88 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8) ? 2 : 1) void gemm_st
     }
     const size_t wstep = (size_t)G * 64;   // uint4 from one k-step of a block to the next
 
-    // activation fragments: slot `lane` of fragment (row block i, k-step kb) = row i * 16 + lane % 16,
-    // k = kb * 32 + (lane / 16) * 8 .. + 8
     const uint4 *xp[MB];
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
-        if (XROWS) {
-            const int row = min(i * 16 + (lane & 15), a.M - 1);   // rows past M repeat the last one; never stored
-            xp[i] = (const uint4 *)((const bf16_t *)a.X + (size_t)row * kfrags * 32 + (lane >> 4) * 8);
-        } else {
-            const int blk = min(i, (a.M - 1) >> 4);   // row blocks past the batch repeat the last one; never stored
-            xp[i] = (const uint4 *)a.X + (size_t)blk * kfrags * 64 + lane;
-        }
+        const int blk = min(i, (a.M - 1) >> 4);   // row blocks past the batch repeat the last one; never stored
+        xp[i] = a.X + (size_t)blk * kfrags * 64 + lane;
     }
-    constexpr int XSTEP = XROWS ? 4 : 64;   // uint4 per k-step
-    const bool norm = XROWS && a.gain != nullptr;
-    const uint4 *gp = (const uint4 *)(a.gain + (lane >> 4) * 8);   // + kb * 4 uint4
+    const bool norm = a.norm != 0;
 
     f32x4_t acc[NB][MB];
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
         for (int i = 0; i < MB; ++i) acc[j][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float ssq[MB];
+    f32x4_t sq[MB];   // X X^T per row block; the diagonal is the rows' sum of squares
 #pragma unroll
-    for (int i = 0; i < MB; ++i) ssq[i] = 0.f;
+    for (int i = 0; i < MB; ++i) sq[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // Two register sets of U k-steps each, rolling: while one set is multiplied the other is in
     // flight.  The loop body has no branch around a load - past the end a set re-loads the last
     // k-step (a cache hit) and is not multiplied - so that the compiler's wait counts stay exact.
-    uint4 w0[U][NB], x0[U][MB], g0[U], w1[U][NB], x1[U][MB], g1[U];
+    // (Starting each tile's K walk at a different offset, so that the workgroups do not ask the L2
+    // for the same activation lines at the same moment, was measured: no gain.)
+    uint4 w0[U][NB], x0[U][MB], w1[U][NB], x1[U][MB];
     const int n_sets = (kb_hi - kb_lo + U - 1) / U;
-#define GS_LOAD(W_, X_, G_, SET)                                                                          \
+#define GS_LOAD(W_, X_, SET)                                                                              \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
         const int kk = min(kb_lo + (SET) * U + u, kb_hi - 1);                                             \
         _Pragma("unroll") for (int j = 0; j < NB; ++j) W_[u][j] = ld_stream(wp[j] + (size_t)kk * wstep);  \
-        _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * XSTEP];              \
-        if (XROWS) G_[u] = norm ? gp[(size_t)kk * 4] : make_uint4(0, 0, 0, 0);                            \
+        _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * 64];                 \
     }
-#define GS_MUL(W_, X_, G_, SET)                                                                           \
+#define GS_MUL(W_, X_, SET)                                                                               \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
         if (kb_lo + (SET) * U + u < kb_hi) {                                                              \
-            if (XROWS && norm) {                                                                          \
-                const uint32_t ge[4] = {G_[u].x, G_[u].y, G_[u].z, G_[u].w};                              \
-                _Pragma("unroll") for (int i = 0; i < MB; ++i) {                                          \
-                    uint32_t xe[4] = {X_[u][i].x, X_[u][i].y, X_[u][i].z, X_[u][i].w};                    \
-                    _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                       \
-                        const float lo = bf_lo(xe[e]), hi = bf_hi(xe[e]);                                 \
-                        ssq[i] = fmaf(lo, lo, ssq[i]);                                                    \
-                        ssq[i] = fmaf(hi, hi, ssq[i]);                                                    \
-                        xe[e] = pack2bf(lo * bf_lo(ge[e]), hi * bf_hi(ge[e]));                            \
-                    }                                                                                     \
-                    X_[u][i] = make_uint4(xe[0], xe[1], xe[2], xe[3]);                                    \
-                }                                                                                         \
-            }                                                                                             \
             _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                 \
                 _Pragma("unroll") for (int i = 0; i < MB; ++i) acc[j][i] = gs_mfma(W_[u][j], X_[u][i], acc[j][i]); \
+            if (EPI != GS_STORE || norm) {                                                                \
+                _Pragma("unroll") for (int i = 0; i < MB; ++i) sq[i] = gs_mfma(X_[u][i], X_[u][i], sq[i]); \
+            }                                                                                             \
         }                                                                                                 \
     }
     if (n_sets > 0) {
-        GS_LOAD(w0, x0, g0, 0);
-        GS_LOAD(w1, x1, g1, 1);
+        GS_LOAD(w0, x0, 0);
+        GS_LOAD(w1, x1, 1);
         for (int s = 0; s < n_sets; s += 2) {
-            GS_MUL(w0, x0, g0, s);
-            GS_LOAD(w0, x0, g0, s + 2);
-            GS_MUL(w1, x1, g1, s + 1);
-            GS_LOAD(w1, x1, g1, s + 3);
+            GS_MUL(w0, x0, s);
+            GS_LOAD(w0, x0, s + 2);
+            GS_MUL(w1, x1, s + 1);
+            GS_LOAD(w1, x1, s + 3);
         }
     }
 #undef GS_LOAD
 #undef GS_MUL
 
-    // In-workgroup reduction through two LDS buffers of row-major [row][NB * 16 columns] tiles:
-    // wavefronts 2, 3 write their accumulators, wavefronts 0, 1 add them to their own (0 + 2, 1 + 3)
-    // and write the sums; then every thread adds the two buffers for the outputs it stores.
-    float *wssq = red + 2 * BUF;            // [4 wavefronts][MB * 16 rows]
+    // In-workgroup reduction through kGsWaves / 2 LDS buffers of row-major [row][NB * 16 columns]
+    // tiles: the upper half of the wavefronts write their accumulators, the lower half add them to
+    // their own (w + (w + kGsWaves / 2)) and write the sums; then every thread adds the buffers in
+    // index order for the outputs it stores.
+    constexpr int HALF = kGsWaves / 2;
+    float *wssq = red + HALF * BUF;         // [wavefronts][MB * 16 rows]
     float *rsv = wssq + kGsWaves * MB * 16; // [MB * 16]: rsqrt(mean square + eps) per row
-    float *slot = red + (wave & 1) * BUF + (lane & 15) * ROWF + (lane >> 4) * 4;   // + i * 16 * ROWF + j * 16
-    if (wave >= 2) {
+    float *slot = red + (wave % HALF) * BUF + (lane & 15) * ROWF + (lane >> 4) * 4;   // + i * 16 * ROWF + j * 16
+    if (wave >= HALF) {
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int i = 0; i < MB; ++i)
                 *(float4 *)(slot + i * 16 * ROWF + j * 16) = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
     }
-    if (XROWS) {
-        // a row's sum of squares: the four k quarters of a fragment by two butterfly steps, then the
-        // four wavefronts (K quarters) in index order below
+    {
+        // a row's sum of squares over this wavefront's part of K: element (m, m) of X X^T, which lane
+        // m + 16 * (m / 4) holds in register m % 4; the wavefronts are added in index order below
+        const int m16 = lane & 15;
+        if ((lane >> 4) == (m16 >> 2)) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            float s = ssq[i];
-            s += __shfl_xor(s, 16, 64);
-            s += __shfl_xor(s, 32, 64);
-            if (lane < 16) wssq[wave * (MB * 16) + i * 16 + lane] = s;
+            for (int i = 0; i < MB; ++i) {
+                const float s = (m16 & 3) == 0 ? sq[i][0] : (m16 & 3) == 1 ? sq[i][1] : (m16 & 3) == 2 ? sq[i][2] : sq[i][3];
+                wssq[wave * (MB * 16) + i * 16 + m16] = s;
+            }
         }
     }
     __syncthreads();
-    if (wave < 2) {
+    if (wave < HALF) {
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
@@ -192,21 +175,24 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8) ? 2 : 1) void gemm_st
                 *p = make_float4(acc[j][i][0] + t.x, acc[j][i][1] + t.y, acc[j][i][2] + t.z, acc[j][i][3] + t.w);
             }
     }
-    if (XROWS && threadIdx.x < MB * 16) {
+    if (threadIdx.x < MB * 16) {
         const int m = threadIdx.x;
-        const float tot = ((wssq[m] + wssq[MB * 16 + m]) + wssq[2 * MB * 16 + m]) + wssq[3 * MB * 16 + m];
+        float tot = wssq[m];
+#pragma unroll
+        for (int w = 1; w < kGsWaves; ++w) tot += wssq[w * (MB * 16) + m];
         rsv[m] = norm ? 1.0f / sqrtf(tot / (float)(kfrags * 32) + a.eps) : 1.0f;
     }
     __syncthreads();
     // value of the tile at (row m, column c of NB * 16), scaled by the row's norm factor
     auto fetch = [&](int m, int c) -> float4 {
         float4 v = *(const float4 *)(red + m * ROWF + c);
-        const float4 t = *(const float4 *)(red + BUF + m * ROWF + c);
-        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
-        if (XROWS) {
-            const float r = rsv[m];
-            v.x *= r; v.y *= r; v.z *= r; v.w *= r;
+#pragma unroll
+        for (int w = 1; w < HALF; ++w) {
+            const float4 t = *(const float4 *)(red + w * BUF + m * ROWF + c);
+            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
         }
+        const float r = rsv[m];
+        v.x *= r; v.y *= r; v.z *= r; v.w *= r;
         return v;
     };
     constexpr int QUADS = MB * 16 * (NB * 4);   // float4 outputs of the tile
@@ -220,7 +206,9 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8) ? 2 : 1) void gemm_st
                 const uint2 r = *(const uint2 *)(a.res + (size_t)m * a.N + n);
                 v.x += bf_lo(r.x); v.y += bf_hi(r.x); v.z += bf_lo(r.y); v.w += bf_hi(r.y);
             }
-            *(uint2 *)(a.out + (size_t)m * a.N + n) = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
+            const uint2 o = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
+            *(uint2 *)(a.out + (size_t)m * a.N + n) = o;
+            if (a.out_packed) *(uint2 *)(a.out_packed + packed_index(m, n, a.N >> 5)) = o;
         }
     } else if (EPI == GS_SWIGLU) {   // the tile's blocks are (gate, up) pairs: NB / 2 blocks of u
         for (int q = threadIdx.x; q < QUADS / 2; q += kGsWaves * 64) {
@@ -264,46 +252,52 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8) ? 2 : 1) void gemm_st
     }
 }
 
-constexpr int gs_lds_bytes(int MB, int NB)
+constexpr int gs_lds_bytes(int MB, int NB, int W)
 {
-    return (2 * MB * 16 * (NB * 16 + 4) + kGsWaves * MB * 16 + MB * 16) * (int)sizeof(float);
+    return ((W / 2) * MB * 16 * (NB * 16 + 4) + W * MB * 16 + MB * 16) * (int)sizeof(float);
 }
 
-template <int MB, int NB, int XROWS, int EPI>
+// wavefronts per workgroup and k-steps per register set of each instantiation
+constexpr int gs_waves(int MB, int NB) { return 4; }
+
+template <int MB, int NB, int EPI>
 hipError_t gs_launch(int tiles, const GsArgs &a, hipStream_t st)
 {
-    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, XROWS, EPI>), dim3(tiles), dim3(kGsWaves * 64), gs_lds_bytes(MB, NB), st, a);
+    constexpr int W = gs_waves(MB, NB), U = gs_u(MB, NB);
+    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, W, U>), dim3(tiles), dim3(W * 64), gs_lds_bytes(MB, NB, W), st, a);
     return hipGetLastError();
 }
 
-template <int NB, int XROWS, int EPI>
+template <int NB, int EPI>
 hipError_t gs_launch_mb(int tiles, const GsArgs &a, hipStream_t st)
 {
     const int mb = (a.M + 15) / 16;
-    if (mb <= 1) return gs_launch<1, NB, XROWS, EPI>(tiles, a, st);
-    if (mb == 2) return gs_launch<2, NB, XROWS, EPI>(tiles, a, st);
-    return gs_launch<4, NB, XROWS, EPI>(tiles, a, st);
+    if (mb <= 1) return gs_launch<1, NB, EPI>(tiles, a, st);
+    if (mb == 2) return gs_launch<2, NB, EPI>(tiles, a, st);
+    return gs_launch<4, NB, EPI>(tiles, a, st);
 }
 
-template <int MB, int NB, int XROWS, int EPI>
+template <int MB, int NB, int EPI>
 hipError_t gs_attr()
 {
-    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, XROWS, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               gs_lds_bytes(MB, NB));
+    constexpr int W = gs_waves(MB, NB), U = gs_u(MB, NB);
+    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, W, U>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               gs_lds_bytes(MB, NB, W));
 }
-template <int NB, int XROWS, int EPI>
+template <int NB, int EPI>
 hipError_t gs_attr_mb()
 {
-    hipError_t e = gs_attr<1, NB, XROWS, EPI>();
-    if (e == hipSuccess) e = gs_attr<2, NB, XROWS, EPI>();
-    if (e == hipSuccess) e = gs_attr<4, NB, XROWS, EPI>();
+    hipError_t e = gs_attr<1, NB, EPI>();
+    if (e == hipSuccess) e = gs_attr<2, NB, EPI>();
+    if (e == hipSuccess) e = gs_attr<4, NB, EPI>();
     return e;
 }
 
 }  // namespace
 
-// Tile width (16-column blocks per workgroup) of a store-type projection with N output columns:
-// the widest of 8, 4, 2, 1 that still gives about one workgroup per compute unit.
+// Tile width (16-column blocks per workgroup) of a store-type projection with N output columns
+// for a batch of `variant_rows` rows: the widest of 8, 4, 2, 1 that still gives about one
+// workgroup per compute unit.
 int stream_store_nb(int N)
 {
     const int nblk = (N + 15) / 16;
@@ -315,68 +309,61 @@ int stream_store_nb(int N)
 // fill the GPU.
 int stream_qkv_nb(int heads) { return heads >= 192 ? 8 : 4; }
 
-hipError_t launch_gemm_stream_store(const void *Wp, int G, int nb, const void *X, bool x_rows, const void *gain, float eps,
-                                    const void *res, void *out, int M, int N, int K, hipStream_t st)
+hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *Xp, bool norm, float eps, const void *res,
+                                    void *out, void *out_packed, int M, int N, int K, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31) || (N & 15)) return hipErrorInvalidValue;
-    if ((nb != 1 && nb != 2 && nb != 4 && nb != 8) || G % nb) return hipErrorInvalidValue;   // a tile lies inside one weight group
+    if (nb != 1 && nb != 2 && nb != 4 && nb != 8) return hipErrorInvalidValue;   // a tile lies inside one weight group
     GsArgs a{};
-    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = G; a.X = X; a.gain = (const bf16_t *)gain; a.eps = eps;
-    a.M = M; a.N = N; a.res = (const bf16_t *)res; a.out = (bf16_t *)out;
+    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)Xp; a.norm = norm ? 1 : 0; a.eps = eps;
+    a.M = M; a.N = N; a.res = (const bf16_t *)res; a.out = (bf16_t *)out; a.out_packed = (bf16_t *)out_packed;
     const int tiles = ((N / 16) + nb - 1) / nb;
-#define CCS_GS(NBV)                                                                   \
-    (x_rows ? gs_launch_mb<NBV, 1, GS_STORE>(tiles, a, st) : gs_launch_mb<NBV, 0, GS_STORE>(tiles, a, st))
     switch (nb) {
-        case 1: return CCS_GS(1);
-        case 2: return CCS_GS(2);
-        case 4: return CCS_GS(4);
-        default: return CCS_GS(8);
+        case 1: return gs_launch_mb<1, GS_STORE>(tiles, a, st);
+        case 2: return gs_launch_mb<2, GS_STORE>(tiles, a, st);
+        case 4: return gs_launch_mb<4, GS_STORE>(tiles, a, st);
+        default: return gs_launch_mb<8, GS_STORE>(tiles, a, st);
     }
-#undef CCS_GS
 }
 
-hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *x_rows, const void *gain, float eps, void *u_packed,
-                                     int M, int N2, int K, hipStream_t st)
+hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *Xp, float eps, void *u_packed, int M, int N2, int K,
+                                     hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31) || (N2 & 31)) return hipErrorInvalidValue;
     GsArgs a{};
-    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = x_rows; a.gain = (const bf16_t *)gain; a.eps = eps;
+    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)Xp; a.norm = 1; a.eps = eps;
     a.M = M; a.N = N2; a.out = (bf16_t *)u_packed;
     const int tiles = ((N2 / 16) + 7) / 8;
-    return gs_launch_mb<8, 1, GS_SWIGLU>(tiles, a, st);
+    return gs_launch_mb<8, GS_SWIGLU>(tiles, a, st);
 }
 
-hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *x_rows, const void *gain, float eps, void *qkv,
-                                         int M, int nq, int nkv, int K, const void *tab, const int32_t *lens_dev,
-                                         void *k_cache, void *v_cache, int cap, hipStream_t st)
+hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *Xp, float eps, void *qkv, int M, int nq, int nkv,
+                                         int K, const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache,
+                                         int cap, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31)) return hipErrorInvalidValue;
     GsArgs a{};
-    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = x_rows; a.gain = (const bf16_t *)gain; a.eps = eps;
+    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)Xp; a.norm = 1; a.eps = eps;
     a.M = M; a.N = (nq + 2 * nkv) * 128; a.out = (bf16_t *)qkv;
     a.nq = nq; a.nkv = nkv; a.tab = (const float2 *)tab; a.lens = lens_dev; a.kc = (bf16_t *)k_cache; a.vc = (bf16_t *)v_cache;
     a.cap = cap;
     const int heads = nq + 2 * nkv;
-    if (stream_qkv_nb(heads) == 8) return gs_launch_mb<8, 1, GS_QKV_DECODE>(heads, a, st);
-    return gs_launch_mb<4, 1, GS_QKV_DECODE>(heads * 2, a, st);
+    if (stream_qkv_nb(heads) == 8) return gs_launch_mb<8, GS_QKV_DECODE>(heads, a, st);
+    return gs_launch_mb<4, GS_QKV_DECODE>(heads * 2, a, st);
 }
 
 hipError_t init_gemm_stream_kernels()
 {
-    hipError_t e = gs_attr_mb<1, 0, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<2, 0, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<4, 0, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<8, 0, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<1, 1, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<2, 1, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<4, 1, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<8, 1, GS_STORE>();
-    if (e == hipSuccess) e = gs_attr_mb<8, 1, GS_SWIGLU>();
-    if (e == hipSuccess) e = gs_attr_mb<8, 1, GS_QKV_DECODE>();
-    if (e == hipSuccess) e = gs_attr_mb<4, 1, GS_QKV_DECODE>();
+    hipError_t e = gs_attr_mb<1, GS_STORE>();
+    if (e == hipSuccess) e = gs_attr_mb<2, GS_STORE>();
+    if (e == hipSuccess) e = gs_attr_mb<4, GS_STORE>();
+    if (e == hipSuccess) e = gs_attr_mb<8, GS_STORE>();
+    if (e == hipSuccess) e = gs_attr_mb<8, GS_SWIGLU>();
+    if (e == hipSuccess) e = gs_attr_mb<8, GS_QKV_DECODE>();
+    if (e == hipSuccess) e = gs_attr_mb<4, GS_QKV_DECODE>();
     return e;
 }
 

@@ -19,25 +19,18 @@ hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st
 // Row-major bf16 [N, K] -> fragment-packed rows; 16-row block nb of the source lands at packed
 // block nb * blk_stride + blk_offset of a packed matrix with K/32 fragments per block row.
 // `grouped`: weight order (groups of 8 blocks, see ccs_common.h); the caller zeroes the padding.
+// `gain` (bf16 [K], may be null): every row is multiplied element-wise by it on the way (rounded to
+// bf16) - how the gains of the RMSNorm in front of a projection are folded into its weight.
 hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int blk_stride,
-                            int blk_offset, bool grouped, hipStream_t st);
+                            int blk_offset, bool grouped, const void *gain, hipStream_t st);
 // out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g.  x row-major [rows, H].
-// bf16: out is fragment-packed [rows16, H]; f32: out row-major.
+// bf16: out is fragment-packed [rows16, H] and g may be null (gains folded into the next weight);
+// f32: out row-major.
 hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H,
                           float eps, hipStream_t st);
 // Inverse-frequency table of the rotary embedding, d/2 float2 entries (fp32 head and tail of
 // base^(-2i/d)); part of the weight arena.  All rope kernels take it as `tab`.
 hipError_t launch_rope_table(void *tab, int d, float base, hipStream_t st);
-// Decode (bf16, head_dim 128) epilogues of the weight-streaming projections:
-// Q/K/V: segment sum + rotary embedding + q store + KV-cache append at slot lens[row];
-hipError_t launch_qkv_reduce_rope_decode(const float *partials, int S, int M, int nq, int nkv, const void *tab,
-                                         const int32_t *lens_dev, void *qkv, void *k_cache, void *v_cache,
-                                         int cap, hipStream_t st);
-// O: segment sum + residual -> x1 (row-major) and RMSNorm(x1; g) -> h2 (fragment-packed); H <= 8192.
-hipError_t launch_reduce_residual_rmsnorm(const float *partials, int S, int M, int H, const void *res, const void *g,
-                                          float eps, void *x1, void *h2, hipStream_t st);
-// bf16 RMSNorm with one workgroup per row (few rows), output fragment-packed; H <= 8192.
-hipError_t launch_rmsnorm_rows(const void *x, const void *g, void *out, int rows, int H, float eps, hipStream_t st);
 // Rotary embedding (split-half pairs) in place on the q and k parts of qkv [rows, (nq+2nkv)*d]
 // row-major.  prefill (decode == 0): position = row % seq_pad; when caches are non-null the
 // rotated k and v of rows with position < lens[row / seq_pad] are stored at slot = position.
@@ -74,27 +67,19 @@ enum GemmEpilogue {
     EPI_STORE_RM = 0,   // y row-major bf16 [M, N], optional residual (row-major bf16 [M, N])
     EPI_SWIGLU_PACKED = 1  // N = 2I with gate/up interleaved in 16-row blocks; u fragment-packed [M16, I]
 };
-// Number of K segments the weight-streaming GEMM uses for a [N, K] weight; depends on the
-// weight shape only, never on the number of rows, so that a row's bits do not depend on the
-// batch it is computed in.
+// Largest row count the weight-streaming variants accept in one launch.
+constexpr int kSkinnyMaxRows = 64;
+// Weight-streaming GEMM with a K split, for the projections whose one-launch form (above) is slower:
+// 128-column tiles, K cut into skinny_segments(N, K) segments (a function of the weight shape only),
+// fp32 partial sums [S, M, N] into `partials`; the caller follows with launch_partial_reduce.
 int skinny_segments(int N, int K);
 size_t skinny_partial_bytes(int M, int N, int K);
-// Largest row count the weight-streaming variant accepts in one launch.
-constexpr int kSkinnyMaxRows = 64;
-// bf16 weight-streaming GEMM for M <= kSkinnyMaxRows rows, two launches: partial sums per K
-// segment into `partials` (fp32 [S, M, N]), then a fixed-order reduction with the epilogue.
-// Weight-streaming GEMM with epilogue `epi` (EPI_*).  When the launch has a single K segment the
-// kernel applies the epilogue itself and *fused is true; otherwise it leaves partial sums in
-// `partials` and the caller follows with launch_gemm_skinny_reduce (or its own fused reduction).
-hipError_t launch_gemm_skinny(const void *Wp, const void *Xp, float *partials, int M, int N, int K, int epi,
-                              const void *res, void *out, bool *fused, hipStream_t st);
 hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
                                    int K, hipStream_t st);
-hipError_t launch_gemm_skinny_reduce(const float *partials, int epi, const void *res, void *out,
-                                     int M, int N, int K, hipStream_t st);
 // Fixed-order sum of S partial buffers (fp32 [S, M, N]) + epilogue; used by both GEMM variants.
-hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, int M,
-                                 int N, hipStream_t st);
+// EPI_STORE_RM: out_packed (may be null) receives a second, fragment-packed copy of the result.
+hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, void *out_packed,
+                                 int M, int N, hipStream_t st);
 // bf16 LDS-tiled MFMA GEMM for any M (Xp readable up to M rounded up to 16 rows).  When the batch
 // is too small to fill the GPU, K is cut into tiled_segments(N, K, variant_rows) segments whose
 // partial sums go through `partials` (tiled_partial_bytes) and launch_partial_reduce;
@@ -105,28 +90,30 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
                              int M, int N, int K, long variant_rows, float *partials, hipStream_t st);
 
 // ---- weight-streaming projections, one launch each (ccs_gemm_stream.hip) -----------------------
-// For M <= kSkinnyMaxRows rows.  Weights are fragment-packed in groups of G 16-row blocks
-// (ccs_common.h); x is either fragment-packed or the row-major bf16 rows [M, K] themselves, and
-// with `gain` (row-major x only) the kernel also applies RMSNorm(x; gain, eps) in front of the
-// projection.  A row's result depends on that row alone.
+// For M <= kSkinnyMaxRows rows.  Weights are fragment-packed in groups of kWGroup 16-row blocks
+// (ccs_common.h), x is fragment-packed [M16, K].  With `norm` x holds the raw rows of the residual
+// stream and the kernel is also the RMSNorm in front of the projection (the weight already carries
+// the norm's gains): row m of the result is scaled by rsqrt(mean_k x[m, k]^2 + eps).  A row's
+// result depends on that row alone.
 enum { GS_STORE = 0, GS_SWIGLU = 1, GS_QKV_DECODE = 2 };
 hipError_t init_gemm_stream_kernels();
-// Group size of a store-type weight [N, K] (O, down, a single projection): also its tile width.
+// Tile width (16-column blocks, one of 1, 2, 4, 8) of a store-type projection with N output columns.
 int stream_store_nb(int N);
-// out[m, n] = sum_k x'[m, k] W[n, k] (+ res[m, n]), row-major bf16 [M, N]; the tile is one group.
-hipError_t launch_gemm_stream_store(const void *Wp, int G, int nb, const void *X, bool x_rows, const void *gain, float eps,
-                                    const void *res, void *out, int M, int N, int K, hipStream_t st);
-// u = silu(gate) * up, fragment-packed [M16, N2 / 2]; weight [N2, K] with gate / up interleaved in
-// 16-row blocks, grouped by kWGroup; x row-major with RMSNorm gains.
-hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *x_rows, const void *gain, float eps, void *u_packed,
-                                     int M, int N2, int K, hipStream_t st);
-// Decode Q/K/V projection (head_dim 128, weight [Wq; Wk; Wv] grouped by kWGroup = one head) with
-// RMSNorm in front and, behind it, the rotary embedding at position lens[m], the q store into the
+// out[m, n] = sum_k x'[m, k] W[n, k] (+ res[m, n]) as row-major bf16 [M, N] and, when out_packed
+// is not null, also fragment-packed [M16, N] (the operand of the next projection).
+hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *Xp, bool norm, float eps, const void *res,
+                                    void *out, void *out_packed, int M, int N, int K, hipStream_t st);
+// u = silu(gate) * up of RMSNorm(x), fragment-packed [M16, N2 / 2]; weight [N2, K] with gate / up
+// interleaved in 16-row blocks; x raw.
+hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *Xp, float eps, void *u_packed, int M, int N2, int K,
+                                     hipStream_t st);
+// Decode Q/K/V projection (head_dim 128, weight [Wq; Wk; Wv]: one head = one weight group) of
+// RMSNorm(x), x raw, and behind it the rotary embedding at position lens[m], the q store into the
 // row-major qkv buffer [M, (nq + 2 nkv) * 128] and the append of the rotated key and the value at
 // cache slot lens[m] (caches [M, nkv, cap, 128]).
-hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *x_rows, const void *gain, float eps, void *qkv,
-                                         int M, int nq, int nkv, int K, const void *tab, const int32_t *lens_dev,
-                                         void *k_cache, void *v_cache, int cap, hipStream_t st);
+hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *Xp, float eps, void *qkv, int M, int nq, int nkv,
+                                         int K, const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache,
+                                         int cap, hipStream_t st);
 
 // ---- attention (ccs_attention.hip) ---------------------------------------------------------
 // Generic (slow, any head_dim <= 256) softmax attention: one wavefront per query row.

@@ -83,8 +83,18 @@ struct ArenaPlan {
 };
 
 struct WsPlan {
-    size_t h, qkv, a, x1, gu, u, xp, kp, vtp, xa, xb, xc, yc, offs, scratch, scratch_bytes, total;  // xa, xb: activations between layers of a run; xc, yc, offs: dense prefill rows in / out and their per-sequence offsets
+    // h: normalised rows (LDS-tiled path); xp, x1p: fragment-packed raw rows of the layer input and of
+    // the residual stream after the attention block (weight-streaming path: the projections apply the
+    // norm themselves); xa, xb: activations between layers of a run; xc, yc, offs: dense prefill
+    // rows in / out and their per-sequence offsets
+    size_t h, qkv, a, x1, gu, u, xp, x1p, kp, vtp, xa, xb, xc, yc, offs, scratch, scratch_bytes, total;
 };
+
+// A store-type projection (O, down, a single projection) of a batch of `variant_rows` <= 64 rows runs
+// as one launch over narrow tiles, except for 33..64 rows against a long K, where 128-column tiles
+// with a K split and a reduction kernel stream faster (measured on the 70B down projection: 80 us
+// against 102 us).  Decided from the weight shape and the FULL batch's row count.
+inline bool store_split(int K, long long variant_rows) { return variant_rows > 32 && K > 8192; }
 
 int check_desc(const ccs_module_desc *D, Dims *out)
 {
@@ -174,6 +184,8 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
         }
     } else if (D->dtype == CCS_BF16) {
         p.h = take(r16 * d.H * 2);
+        p.xp = take(r16 * d.H * 2);
+        p.x1p = take(r16 * d.H * 2);
         p.qkv = take(rows * d.W3 * 2);
         p.a = take(r16 * d.QD * 2);
         p.x1 = take(rows * d.H * 2);
@@ -191,10 +203,8 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
             p.xb = take(rows * d.H * 2);
         }
         size_t s = 0;
-        if (skinny) {
-            s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.W3, d.H));
+        if (skinny) {   // partial sums of the projections that may take the K-split form
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.QD));
-            s = max_sz(s, ccs::skinny_partial_bytes((int)rows, 2 * d.I, d.H));
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.I));
         } else {
             s = max_sz(s, ccs::tiled_partial_bytes((int)rows, d.W3, d.H, vrows));
@@ -404,11 +414,12 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         }
         WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false, 0, (long)variant_rows);
         if (p.total > ws_bytes) return fail(CCS_ENOMEM, "%s workspace has %zu bytes, batch needs %zu", ws_static ? "the static" : "the replica's", ws_bytes, p.total);
-        CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, st));
-        if (skinny) {
-            bool fused = false;
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, EPI_STORE_RM, nullptr, b->y, &fused, st));
-            if (!fused) CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_gemm_skinny_reduce((const float *)(ws + p.scratch), EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, st));
+        CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, nullptr, st));
+        if (skinny && store_split(d.in_f, variant_rows)) {
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, st));
+            CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_partial_reduce((const float *)(ws + p.scratch), skinny_segments(d.out_f, d.in_f), EPI_STORE_RM, nullptr, b->y, nullptr, M, d.out_f, st));
+        } else if (skinny) {
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.w, stream_store_nb(d.out_f), ws + p.xp, false, 0.f, nullptr, b->y, nullptr, M, d.out_f, d.in_f, st));
         } else {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, (long)variant_rows, (float *)(ws + p.scratch), st));
         }
@@ -425,7 +436,6 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     WsPlan p = ws_plan(&D, d, T, b->n_seqs, b->cache_cap, skinny, decode, (decode || rows_mode) ? 0 : seq_pad, (long)variant_rows);
     if (p.total > ws_bytes) return fail(CCS_ENOMEM, "%s workspace has %zu bytes, batch needs %zu", ws_static ? "the static" : "the replica's", ws_bytes, p.total);
     const int dt = bf ? DT_BF16 : DT_F32;
-    const bool row_norm = skinny && d.H <= 8192 && d.H % 4 == 0;  // few rows: one workgroup per row
 
     // A run of layers: layer l reads x_in and writes x_out, ping-ponging between two workspace
     // buffers; the first layer reads the batch's x, the last writes its y (Section 3.1: inside a
@@ -435,7 +445,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         CCS_STAGE(CCS_ST_COMPACT, launch_prefill_offsets(b->lens_dev, b->n_seqs, seq_pad, T, (int32_t *)(ws + p.offs), st));
         CCS_STAGE(CCS_ST_COMPACT, launch_prefill_rows(const_cast<void *>(b->x), ws + p.xc, offs, b->n_seqs, seq_pad, d.H, false, st));
     }
-    bool h_ready = false;   // h already holds RMSNorm_1 of x_in (fused into the previous layer's last reduction)
+    bool xp_ready = false;   // weight-streaming path: xp already holds the packed rows of x_in (written by the previous layer's down projection)
     for (int l = 0; l < d.L; ++l) {
         const char *A = A0 + (size_t)l * m->ap.layer;
         const void *x_first = dense ? (const void *)(ws + p.xc) : b->x;
@@ -446,75 +456,70 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         void *vc = b->v_cache ? (char *)b->v_cache + (size_t)l * (size_t)b->cache_layer_stride : nullptr;
         const bool last = l == d.L - 1;
 
-        // h = RMSNorm(x_in) with the gains of the block that comes first
-        const size_t g_first = attn ? m->ap.g1 : m->ap.g2;
-        if (!h_ready) {
-            if (row_norm)
-                CCS_STAGE(attn ? CCS_ST_RMSNORM1 : CCS_ST_RMSNORM2, launch_rmsnorm_rows(x_in, A + g_first, ws + p.h, T, d.H, D.rms_eps, st));
-            else
-                CCS_STAGE(attn ? CCS_ST_RMSNORM1 : CCS_ST_RMSNORM2, launch_rmsnorm(dt, x_in, A + g_first, ws + p.h, T, d.H, D.rms_eps, st));
-        }
         // x1: the residual stream between the two blocks (the block's input when attention is absent,
         // the module's output when the FFN is absent)
         const void *x1_in = attn ? (ffn ? (const void *)(ws + p.x1) : (const void *)x_out) : x_in;
         void *x1_out = ffn ? (void *)(ws + p.x1) : x_out;
-        h_ready = false;
         const void *tab = A + m->ap.rope;
-        if (bf) {
-            float *scratch = (float *)(ws + p.scratch);
-            // one projection: weight-streaming (one or two launches) or LDS-tiled (one launch)
-#define CCS_GEMM(sid, woff, xoff, epi, res, out, N, K)                                                        \
-    do {                                                                                                      \
-        if (skinny) {                                                                                         \
-            bool fused__ = false;                                                                             \
-            CCS_STAGE(sid, launch_gemm_skinny(A + (woff), ws + (xoff), scratch, T, (N), (K), (epi), (res), (out), &fused__, st)); \
-            if (!fused__) CCS_STAGE((sid) + 1, launch_gemm_skinny_reduce(scratch, (epi), (res), (out), T, (N), (K), st)); \
-        } else {                                                                                              \
-            CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st)); \
-        }                                                                                                     \
-    } while (0)
+        float *scratch = (float *)(ws + p.scratch);
+        if (bf && skinny) {
+            // Weight-streaming path (at most 64 rows in the full batch): every projection is one launch
+            // that also applies the RMSNorm in front of it (the gains are folded into the weights) and
+            // whatever follows it - rotary embedding and cache append, residual, SwiGLU - so a decode
+            // step is six launches per layer plus one that packs the first layer's input rows.
             if (attn) {
-            if (skinny && decode) {
-                // weight-streaming Q/K/V projection; its reduction also rotates and appends to the cache
-                CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_skinny_main(A + m->ap.qkv, ws + p.h, scratch, T, d.W3, d.H, st));
-                CCS_STAGE(CCS_ST_GEMM_QKV_REDUCE, launch_qkv_reduce_rope_decode(scratch, skinny_segments(d.W3, d.H), T, d.nq, d.nkv, tab, b->lens_dev, ws + p.qkv, kc, vc, b->cache_cap, st));
-            } else {
-                CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
-                if (decode)
-                    CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
-                else
+                if (!xp_ready) CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(x_in, ws + p.xp, T, d.H, 1, 0, false, nullptr, st));
+                if (decode) {
+                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_qkv_decode(A + m->ap.qkv, ws + p.xp, D.rms_eps, ws + p.qkv, T, d.nq, d.nkv, d.H, tab, b->lens_dev, kc, vc, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
+                } else {
+                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_store(A + m->ap.qkv, kWGroup, ws + p.xp, true, D.rms_eps, nullptr, ws + p.qkv, nullptr, T, d.W3, d.H, st));
                     CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, offs, kc, vc, b->cache_cap, st));
-            }
-            if (decode) {
-                CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
-                CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, offs, st));
+                }
+                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_stream_store(A + m->ap.o, stream_store_nb(d.H), ws + p.a, false, 0.f, x_in, x1_out, ffn ? ws + p.x1p : nullptr, T, d.H, d.QD, st));
             } else {
-                CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, offs, st));
-            }
-            if (row_norm && ffn) {
-                // weight-streaming O projection; its reduction adds the residual and applies the second norm
-                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_skinny_main(A + m->ap.o, ws + p.a, scratch, T, d.H, d.QD, st));
-                CCS_STAGE(CCS_ST_GEMM_O_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.QD), T, d.H, x_in, A + m->ap.g2, D.rms_eps, ws + p.x1, ws + p.h, st));
-            } else {
-                CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, x_in, x1_out, d.H, d.QD);
-                if (ffn) CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, A + m->ap.g2, ws + p.h, T, d.H, D.rms_eps, st));
-            }
+                CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(x_in, ws + p.x1p, T, d.H, 1, 0, false, nullptr, st));
             }
             if (ffn) {
-            CCS_GEMM(CCS_ST_GEMM_GU, m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H);
-            if (row_norm && !last) {
-                // inside a run: the down projection's reduction adds the residual and already applies
-                // the next layer's first norm (same kernel as after the O projection)
-                CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.dn, ws + p.u, scratch, T, d.H, d.I, st));
-                CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_reduce_residual_rmsnorm(scratch, skinny_segments(d.H, d.I), T, d.H, ws + p.x1, A + m->ap.layer + m->ap.g1, D.rms_eps, x_out, ws + p.h, st));
-                h_ready = true;
-            } else {
-                CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, x1_in, x_out, d.H, d.I);
+                CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, ws + p.x1p, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
+                void *next_xp = last ? nullptr : (void *)(ws + p.xp);   // inside a run: the next layer's packed input rows
+                if (store_split(d.I, variant_rows)) {
+                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.dn, ws + p.u, scratch, T, d.H, d.I, st));
+                    CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_partial_reduce(scratch, skinny_segments(d.H, d.I), EPI_STORE_RM, x1_in, x_out, next_xp, T, d.H, st));
+                } else {
+                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.dn, stream_store_nb(d.H), ws + p.u, false, 0.f, x1_in, x_out, next_xp, T, d.H, d.I, st));
+                }
+                xp_ready = !last;
             }
+        } else if (bf) {
+            // LDS-tiled path: normalised rows h (no gains: they are folded into the weights), one launch
+            // per projection (two when K is split)
+#define CCS_GEMM(sid, woff, xoff, epi, res, out, N, K) \
+    CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st))
+            CCS_STAGE(attn ? CCS_ST_RMSNORM1 : CCS_ST_RMSNORM2, launch_rmsnorm(dt, x_in, nullptr, ws + p.h, T, d.H, D.rms_eps, st));
+            if (attn) {
+                CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);
+                if (decode) {
+                    CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
+                } else {
+                    CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, offs, kc, vc, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, offs, st));
+                }
+                CCS_GEMM(CCS_ST_GEMM_O, m->ap.o, p.a, EPI_STORE_RM, x_in, x1_out, d.H, d.QD);
+                if (ffn) CCS_STAGE(CCS_ST_RMSNORM2, launch_rmsnorm(dt, ws + p.x1, nullptr, ws + p.h, T, d.H, D.rms_eps, st));
+            }
+            if (ffn) {
+                CCS_GEMM(CCS_ST_GEMM_GU, m->ap.gu, p.h, EPI_SWIGLU_PACKED, nullptr, ws + p.u, 2 * d.I, d.H);
+                CCS_GEMM(CCS_ST_GEMM_DOWN, m->ap.dn, p.u, EPI_STORE_RM, x1_in, x_out, d.H, d.I);
             }
 #undef CCS_GEMM
         } else {
             auto W = [&](size_t off) { return (const float *)(A + off); };
+            CCS_STAGE(attn ? CCS_ST_RMSNORM1 : CCS_ST_RMSNORM2, launch_rmsnorm(dt, x_in, A + (attn ? m->ap.g1 : m->ap.g2), ws + p.h, T, d.H, D.rms_eps, st));
             if (attn) {
                 CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_f32((const float *)(ws + p.h), W(m->ap.qkv), nullptr, (float *)(ws + p.qkv), T, d.W3, d.H, st));
                 CCS_STAGE(CCS_ST_ROPE, launch_rope(dt, ws + p.qkv, T, d.nq, d.nkv, d.d, tab, decode, seq_pad, b->lens_dev, kc, vc, b->cache_cap, st));
@@ -636,8 +641,10 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
         char *A = (char *)arena0 + (size_t)l * m->ap.layer;
         const ccs_weights *wl = w + l;
         auto rm_copy = [&](size_t off, const void *src, size_t bytes) { if (e == hipSuccess) e = launch_clone(A + off, src, bytes, st); };
-        auto pack = [&](size_t off, const void *src, int N, int K, int stride, int blk_off) {
-            if (e == hipSuccess) e = launch_pack_bf16(src, A + off, N, K, stride, blk_off, true, st);
+        // gain: the gains of the RMSNorm in front of the projection, folded into its weight
+        // (W[n, k] * g[k], rounded to bf16): RMSNorm(x; g) W^T = (x / rms(x)) (W diag(g))^T
+        auto pack = [&](size_t off, const void *src, int N, int K, int stride, int blk_off, const void *gain = nullptr) {
+            if (e == hipSuccess) e = launch_pack_bf16(src, A + off, N, K, stride, blk_off, true, gain, st);
         };
         // padding fragments of a weight whose block count is not a multiple of the group must be zero
         auto zero_if_padded = [&](size_t off, int N, int K) {
@@ -652,17 +659,17 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
             if (has_attn(desc->kind)) {
                 zero_if_padded(m->ap.qkv, d.W3, d.H);
                 zero_if_padded(m->ap.o, d.H, d.QD);
-                pack(m->ap.qkv, wl->wq, d.QD, d.H, 1, 0);
-                pack(m->ap.qkv, wl->wk, d.KD, d.H, 1, d.QD / 16);
-                pack(m->ap.qkv, wl->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16);
+                pack(m->ap.qkv, wl->wq, d.QD, d.H, 1, 0, wl->g1);
+                pack(m->ap.qkv, wl->wk, d.KD, d.H, 1, d.QD / 16, wl->g1);
+                pack(m->ap.qkv, wl->wv, d.KD, d.H, 1, (d.QD + d.KD) / 16, wl->g1);
                 pack(m->ap.o, wl->wo, d.H, d.QD, 1, 0);
                 rm_copy(m->ap.g1, wl->g1, (size_t)d.H * 2);
             }
             if (has_ffn(desc->kind)) {
                 zero_if_padded(m->ap.gu, 2 * d.I, d.H);
                 zero_if_padded(m->ap.dn, d.H, d.I);
-                pack(m->ap.gu, wl->wgate, d.I, d.H, 2, 0);  // gate blocks even, up blocks odd
-                pack(m->ap.gu, wl->wup, d.I, d.H, 2, 1);
+                pack(m->ap.gu, wl->wgate, d.I, d.H, 2, 0, wl->g2);  // gate blocks even, up blocks odd
+                pack(m->ap.gu, wl->wup, d.I, d.H, 2, 1, wl->g2);
                 pack(m->ap.dn, wl->wdown, d.H, d.I, 1, 0);
                 rm_copy(m->ap.g2, wl->g2, (size_t)d.H * 2);
             }

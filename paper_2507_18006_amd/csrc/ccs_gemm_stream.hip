@@ -7,7 +7,12 @@
 //     stream contiguous quarters of K (1 KiB weight fragments straight into MFMA A operands, two
 //     rolling register sets so that loads stay in flight under the MFMAs) and their accumulators
 //     are added through LDS in the fixed order (0 + 2) + (1 + 3);
-//   * the activation operand is fragment-packed.  With `norm` the kernel is also the RMSNorm in
+//   * the activation operand is fragment-packed, or (XROWS) the plain row-major rows of the caller:
+//     then a wavefront fetches its k-steps with coalesced loads (four lanes per 64-byte row piece)
+//     and turns them into fragment order through a private, XOR-swizzled piece of LDS (one
+//     conflict-free 16-byte write and read per lane and fragment) - fetching fragment slots
+//     straight from the rows costs the address unit four times as many cycles, which made a
+//     32-row launch 60 % slower.  With `norm` the kernel is also the RMSNorm in
 //     front of the projection: the weights carry the norm's gains already (folded in when the
 //     module is created), the activations are the raw rows of the residual stream, the row's sum
 //     of squares comes from one extra MFMA per fragment (the diagonal of X X^T, accumulated in
@@ -37,11 +42,14 @@ __device__ __forceinline__ f32x4_t gs_mfma(const uint4 &a, const uint4 &b, f32x4
 // k-steps per register set: enough bytes in flight per wavefront without spilling
 constexpr int gs_u(int MB, int NB) { return (NB + MB) <= 3 ? 6 : (NB + MB) <= 6 ? 4 : 2; }
 
+// floats of LDS the reduction and the row statistics take: W / 2 tile buffers, per-wavefront sums of squares, scales
+constexpr int gs_red_floats(int MB, int NB, int W) { return (W / 2) * MB * 16 * (NB * 16 + 4) + W * MB * 16 + MB * 16; }
+
 struct GsArgs {
     const uint4 *Wp;      // grouped fragment-packed weight
     int kfrags;           // K / 32
     int G;                // 16-row blocks per weight group (layout of Wp)
-    const uint4 *X;       // fragment-packed rows [M16, K]
+    const uint4 *X;       // fragment-packed rows [M16, K]; XROWS: row-major bf16 rows [M, K]
     int norm;             // X holds raw rows: scale row m of the result by rsqrt(mean_k x[m, k]^2 + eps)
     float eps;
     int M, N;             // rows; valid output columns
@@ -56,7 +64,7 @@ struct GsArgs {
     int cap;
 };
 
-template <int MB, int NB, int EPI, int kGsWaves, int U>
+template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS>
 __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 : 1) void gemm_stream_kernel(const GsArgs a)
 {
     extern __shared__ float red[];
@@ -87,10 +95,22 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     const uint4 *xp[MB];
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
-        const int blk = min(i, (a.M - 1) >> 4);   // row blocks past the batch repeat the last one; never stored
-        xp[i] = a.X + (size_t)blk * kfrags * 64 + lane;
+        if (XROWS) {   // lane -> row i * 16 + lane / 4, 16-byte piece lane % 4 of the k-step's 64 bytes
+            const int row = min(i * 16 + (lane >> 2), a.M - 1);   // rows past the batch repeat the last one; never stored
+            xp[i] = a.X + (size_t)row * kfrags * 4 + (lane & 3);
+        } else {
+            const int blk = min(i, (a.M - 1) >> 4);   // row blocks past the batch repeat the last one; never stored
+            xp[i] = a.X + (size_t)blk * kfrags * 64 + lane;
+        }
     }
+    constexpr int XSTEP = XROWS ? 4 : 64;   // uint4 per k-step
     const bool norm = a.norm != 0;
+    // XROWS: this wavefront's staging area, one 1 KiB fragment per (k-step of a set, row block), behind
+    // the reduction buffers.  Row r's piece c sits at slot 4 r + (c ^ (r / 4 % 4)): the writes (lane =
+    // 4 r + c) and the reads in fragment order (lane = r + 16 c) both touch every bank once per 16 lanes.
+    uint4 *stage = (uint4 *)(red + gs_red_floats(MB, NB, kGsWaves)) + wave * (U * MB * 64);
+    const int st_wr = ((lane >> 2) << 2) + ((lane & 3) ^ ((lane >> 4) & 3));
+    const int st_rd = ((lane & 15) << 2) + ((lane >> 4) ^ (((lane & 15) >> 2) & 3));
 
     f32x4_t acc[NB][MB];
 #pragma unroll
@@ -112,9 +132,15 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
         const int kk = min(kb_lo + (SET) * U + u, kb_hi - 1);                                             \
         _Pragma("unroll") for (int j = 0; j < NB; ++j) W_[u][j] = ld_stream(wp[j] + (size_t)kk * wstep);  \
-        _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * 64];                 \
+        _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * XSTEP];              \
     }
 #define GS_MUL(W_, X_, SET)                                                                               \
+    if (XROWS) {   /* row pieces -> fragment order through the wavefront's own LDS */                     \
+        _Pragma("unroll") for (int u = 0; u < U; ++u)                                                     \
+            _Pragma("unroll") for (int i = 0; i < MB; ++i) stage[(u * MB + i) * 64 + st_wr] = X_[u][i];   \
+        _Pragma("unroll") for (int u = 0; u < U; ++u)                                                     \
+            _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = stage[(u * MB + i) * 64 + st_rd];   \
+    }                                                                                                     \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
         if (kb_lo + (SET) * U + u < kb_hi) {                                                              \
             _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                 \
@@ -137,6 +163,7 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
 #undef GS_LOAD
 #undef GS_MUL
 
+    if (XROWS) __syncthreads();   // (kept apart from the staging areas anyway; the wavefronts meet here before the epilogue)
     // In-workgroup reduction through kGsWaves / 2 LDS buffers of row-major [row][NB * 16 columns]
     // tiles: the upper half of the wavefronts write their accumulators, the lower half add them to
     // their own (w + (w + kGsWaves / 2)) and write the sums; then every thread adds the buffers in
@@ -252,44 +279,47 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     }
 }
 
-constexpr int gs_lds_bytes(int MB, int NB, int W)
+constexpr int gs_lds_bytes(int MB, int NB, int W, int U, int XROWS)
 {
-    return ((W / 2) * MB * 16 * (NB * 16 + 4) + W * MB * 16 + MB * 16) * (int)sizeof(float);
+    return gs_red_floats(MB, NB, W) * (int)sizeof(float) + (XROWS ? W * U * MB * 1024 : 0);
 }
 
-// wavefronts per workgroup and k-steps per register set of each instantiation
+// wavefronts per workgroup of each instantiation (eight were measured: never faster)
 constexpr int gs_waves(int MB, int NB) { return 4; }
 
-template <int MB, int NB, int EPI>
+template <int MB, int NB, int EPI, int XROWS>
 hipError_t gs_launch(int tiles, const GsArgs &a, hipStream_t st)
 {
     constexpr int W = gs_waves(MB, NB), U = gs_u(MB, NB);
-    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, W, U>), dim3(tiles), dim3(W * 64), gs_lds_bytes(MB, NB, W), st, a);
+    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, W, U, XROWS>), dim3(tiles), dim3(W * 64), gs_lds_bytes(MB, NB, W, U, XROWS), st, a);
     return hipGetLastError();
 }
 
-template <int NB, int EPI>
+template <int NB, int EPI, int XROWS>
 hipError_t gs_launch_mb(int tiles, const GsArgs &a, hipStream_t st)
 {
     const int mb = (a.M + 15) / 16;
-    if (mb <= 1) return gs_launch<1, NB, EPI>(tiles, a, st);
-    if (mb == 2) return gs_launch<2, NB, EPI>(tiles, a, st);
-    return gs_launch<4, NB, EPI>(tiles, a, st);
+    if (mb <= 1) return gs_launch<1, NB, EPI, XROWS>(tiles, a, st);
+    if (mb == 2) return gs_launch<2, NB, EPI, XROWS>(tiles, a, st);
+    return gs_launch<4, NB, EPI, XROWS>(tiles, a, st);
 }
 
-template <int MB, int NB, int EPI>
+template <int MB, int NB, int EPI, int XROWS>
 hipError_t gs_attr()
 {
     constexpr int W = gs_waves(MB, NB), U = gs_u(MB, NB);
-    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, W, U>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               gs_lds_bytes(MB, NB, W));
+    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, W, U, XROWS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               gs_lds_bytes(MB, NB, W, U, XROWS));
 }
 template <int NB, int EPI>
 hipError_t gs_attr_mb()
 {
-    hipError_t e = gs_attr<1, NB, EPI>();
-    if (e == hipSuccess) e = gs_attr<2, NB, EPI>();
-    if (e == hipSuccess) e = gs_attr<4, NB, EPI>();
+    hipError_t e = gs_attr<1, NB, EPI, 0>();
+    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 0>();
+    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 0>();
+    if (e == hipSuccess) e = gs_attr<1, NB, EPI, 1>();
+    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 1>();
+    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 1>();
     return e;
 }
 
@@ -309,50 +339,53 @@ int stream_store_nb(int N)
 // fill the GPU.
 int stream_qkv_nb(int heads) { return heads >= 192 ? 8 : 4; }
 
-hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *Xp, bool norm, float eps, const void *res,
-                                    void *out, void *out_packed, int M, int N, int K, hipStream_t st)
+hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *X, bool x_rows, bool norm, float eps,
+                                    const void *res, void *out, void *out_packed, int M, int N, int K, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31) || (N & 15)) return hipErrorInvalidValue;
     if (nb != 1 && nb != 2 && nb != 4 && nb != 8) return hipErrorInvalidValue;   // a tile lies inside one weight group
     GsArgs a{};
-    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)Xp; a.norm = norm ? 1 : 0; a.eps = eps;
+    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = norm ? 1 : 0; a.eps = eps;
     a.M = M; a.N = N; a.res = (const bf16_t *)res; a.out = (bf16_t *)out; a.out_packed = (bf16_t *)out_packed;
     const int tiles = ((N / 16) + nb - 1) / nb;
+#define CCS_GS(NBV) (x_rows ? gs_launch_mb<NBV, GS_STORE, 1>(tiles, a, st) : gs_launch_mb<NBV, GS_STORE, 0>(tiles, a, st))
     switch (nb) {
-        case 1: return gs_launch_mb<1, GS_STORE>(tiles, a, st);
-        case 2: return gs_launch_mb<2, GS_STORE>(tiles, a, st);
-        case 4: return gs_launch_mb<4, GS_STORE>(tiles, a, st);
-        default: return gs_launch_mb<8, GS_STORE>(tiles, a, st);
+        case 1: return CCS_GS(1);
+        case 2: return CCS_GS(2);
+        case 4: return CCS_GS(4);
+        default: return CCS_GS(8);
     }
+#undef CCS_GS
 }
 
-hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *Xp, float eps, void *u_packed, int M, int N2, int K,
-                                     hipStream_t st)
+hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *X, bool x_rows, float eps, void *u_packed, int M, int N2,
+                                     int K, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31) || (N2 & 31)) return hipErrorInvalidValue;
     GsArgs a{};
-    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)Xp; a.norm = 1; a.eps = eps;
+    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = 1; a.eps = eps;
     a.M = M; a.N = N2; a.out = (bf16_t *)u_packed;
     const int tiles = ((N2 / 16) + 7) / 8;
-    return gs_launch_mb<8, GS_SWIGLU>(tiles, a, st);
+    return x_rows ? gs_launch_mb<8, GS_SWIGLU, 1>(tiles, a, st) : gs_launch_mb<8, GS_SWIGLU, 0>(tiles, a, st);
 }
 
-hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *Xp, float eps, void *qkv, int M, int nq, int nkv,
-                                         int K, const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache,
-                                         int cap, hipStream_t st)
+hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *X, bool x_rows, float eps, void *qkv, int M, int nq,
+                                         int nkv, int K, const void *tab, const int32_t *lens_dev, void *k_cache,
+                                         void *v_cache, int cap, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31)) return hipErrorInvalidValue;
     GsArgs a{};
-    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)Xp; a.norm = 1; a.eps = eps;
+    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = 1; a.eps = eps;
     a.M = M; a.N = (nq + 2 * nkv) * 128; a.out = (bf16_t *)qkv;
     a.nq = nq; a.nkv = nkv; a.tab = (const float2 *)tab; a.lens = lens_dev; a.kc = (bf16_t *)k_cache; a.vc = (bf16_t *)v_cache;
     a.cap = cap;
     const int heads = nq + 2 * nkv;
-    if (stream_qkv_nb(heads) == 8) return gs_launch_mb<8, GS_QKV_DECODE>(heads, a, st);
-    return gs_launch_mb<4, GS_QKV_DECODE>(heads * 2, a, st);
+    if (stream_qkv_nb(heads) == 8)
+        return x_rows ? gs_launch_mb<8, GS_QKV_DECODE, 1>(heads, a, st) : gs_launch_mb<8, GS_QKV_DECODE, 0>(heads, a, st);
+    return x_rows ? gs_launch_mb<4, GS_QKV_DECODE, 1>(heads * 2, a, st) : gs_launch_mb<4, GS_QKV_DECODE, 0>(heads * 2, a, st);
 }
 
 hipError_t init_gemm_stream_kernels()

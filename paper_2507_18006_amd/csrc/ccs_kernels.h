@@ -91,7 +91,8 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void
 
 // ---- weight-streaming projections, one launch each (ccs_gemm_stream.hip) -----------------------
 // For M <= kSkinnyMaxRows rows.  Weights are fragment-packed in groups of kWGroup 16-row blocks
-// (ccs_common.h), x is fragment-packed [M16, K].  With `norm` x holds the raw rows of the residual
+// (ccs_common.h), x is fragment-packed [M16, K] or (x_rows) plain row-major bf16 rows [M, K], which
+// the kernel turns into fragments itself.  With `norm` x holds the raw rows of the residual
 // stream and the kernel is also the RMSNorm in front of the projection (the weight already carries
 // the norm's gains): row m of the result is scaled by rsqrt(mean_k x[m, k]^2 + eps).  A row's
 // result depends on that row alone.
@@ -101,19 +102,19 @@ hipError_t init_gemm_stream_kernels();
 int stream_store_nb(int N);
 // out[m, n] = sum_k x'[m, k] W[n, k] (+ res[m, n]) as row-major bf16 [M, N] and, when out_packed
 // is not null, also fragment-packed [M16, N] (the operand of the next projection).
-hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *Xp, bool norm, float eps, const void *res,
-                                    void *out, void *out_packed, int M, int N, int K, hipStream_t st);
+hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *X, bool x_rows, bool norm, float eps,
+                                    const void *res, void *out, void *out_packed, int M, int N, int K, hipStream_t st);
 // u = silu(gate) * up of RMSNorm(x), fragment-packed [M16, N2 / 2]; weight [N2, K] with gate / up
 // interleaved in 16-row blocks; x raw.
-hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *Xp, float eps, void *u_packed, int M, int N2, int K,
-                                     hipStream_t st);
+hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *X, bool x_rows, float eps, void *u_packed, int M, int N2,
+                                     int K, hipStream_t st);
 // Decode Q/K/V projection (head_dim 128, weight [Wq; Wk; Wv]: one head = one weight group) of
 // RMSNorm(x), x raw, and behind it the rotary embedding at position lens[m], the q store into the
 // row-major qkv buffer [M, (nq + 2 nkv) * 128] and the append of the rotated key and the value at
 // cache slot lens[m] (caches [M, nkv, cap, 128]).
-hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *Xp, float eps, void *qkv, int M, int nq, int nkv,
-                                         int K, const void *tab, const int32_t *lens_dev, void *k_cache, void *v_cache,
-                                         int cap, hipStream_t st);
+hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *X, bool x_rows, float eps, void *qkv, int M, int nq,
+                                         int nkv, int K, const void *tab, const int32_t *lens_dev, void *k_cache,
+                                         void *v_cache, int cap, hipStream_t st);
 
 // ---- attention (ccs_attention.hip) ---------------------------------------------------------
 // Generic (slow, any head_dim <= 256) softmax attention: one wavefront per query row.

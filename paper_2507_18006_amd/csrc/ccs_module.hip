@@ -414,12 +414,14 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         }
         WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false, 0, (long)variant_rows);
         if (p.total > ws_bytes) return fail(CCS_ENOMEM, "%s workspace has %zu bytes, batch needs %zu", ws_static ? "the static" : "the replica's", ws_bytes, p.total);
+        if (skinny && !store_split(d.in_f, variant_rows)) {   // one launch, straight from the caller's rows
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.w, stream_store_nb(d.out_f), b->x, true, false, 0.f, nullptr, b->y, nullptr, M, d.out_f, d.in_f, st));
+            return CCS_OK;
+        }
         CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, nullptr, st));
-        if (skinny && store_split(d.in_f, variant_rows)) {
+        if (skinny) {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, st));
             CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_partial_reduce((const float *)(ws + p.scratch), skinny_segments(d.out_f, d.in_f), EPI_STORE_RM, nullptr, b->y, nullptr, M, d.out_f, st));
-        } else if (skinny) {
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.w, stream_store_nb(d.out_f), ws + p.xp, false, 0.f, nullptr, b->y, nullptr, M, d.out_f, d.in_f, st));
         } else {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, (long)variant_rows, (float *)(ws + p.scratch), st));
         }
@@ -466,30 +468,31 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             // Weight-streaming path (at most 64 rows in the full batch): every projection is one launch
             // that also applies the RMSNorm in front of it (the gains are folded into the weights) and
             // whatever follows it - rotary embedding and cache append, residual, SwiGLU - so a decode
-            // step is six launches per layer plus one that packs the first layer's input rows.
+            // step is six launches per layer.
+            // x of the first projection: the packed copy the previous layer of a run left, else the rows themselves
+            const void *xq = xp_ready ? (const void *)(ws + p.xp) : x_in;
+            const bool xq_rows = !xp_ready;
             if (attn) {
-                if (!xp_ready) CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(x_in, ws + p.xp, T, d.H, 1, 0, false, nullptr, st));
                 if (decode) {
-                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_qkv_decode(A + m->ap.qkv, ws + p.xp, D.rms_eps, ws + p.qkv, T, d.nq, d.nkv, d.H, tab, b->lens_dev, kc, vc, b->cache_cap, st));
+                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_qkv_decode(A + m->ap.qkv, xq, xq_rows, D.rms_eps, ws + p.qkv, T, d.nq, d.nkv, d.H, tab, b->lens_dev, kc, vc, b->cache_cap, st));
                     CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
                     CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
                 } else {
-                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_store(A + m->ap.qkv, kWGroup, ws + p.xp, true, D.rms_eps, nullptr, ws + p.qkv, nullptr, T, d.W3, d.H, st));
+                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_store(A + m->ap.qkv, kWGroup, xq, xq_rows, true, D.rms_eps, nullptr, ws + p.qkv, nullptr, T, d.W3, d.H, st));
                     CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, offs, kc, vc, b->cache_cap, st));
                     CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, offs, st));
                 }
-                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_stream_store(A + m->ap.o, stream_store_nb(d.H), ws + p.a, false, 0.f, x_in, x1_out, ffn ? ws + p.x1p : nullptr, T, d.H, d.QD, st));
-            } else {
-                CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(x_in, ws + p.x1p, T, d.H, 1, 0, false, nullptr, st));
+                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_stream_store(A + m->ap.o, stream_store_nb(d.H), ws + p.a, false, false, 0.f, x_in, x1_out, ffn ? ws + p.x1p : nullptr, T, d.H, d.QD, st));
             }
             if (ffn) {
-                CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, ws + p.x1p, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
+                if (attn) CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, ws + p.x1p, false, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
+                else CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, x_in, true, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
                 void *next_xp = last ? nullptr : (void *)(ws + p.xp);   // inside a run: the next layer's packed input rows
                 if (store_split(d.I, variant_rows)) {
                     CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.dn, ws + p.u, scratch, T, d.H, d.I, st));
                     CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_partial_reduce(scratch, skinny_segments(d.H, d.I), EPI_STORE_RM, x1_in, x_out, next_xp, T, d.H, st));
                 } else {
-                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.dn, stream_store_nb(d.H), ws + p.u, false, 0.f, x1_in, x_out, next_xp, T, d.H, d.I, st));
+                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.dn, stream_store_nb(d.H), ws + p.u, false, false, 0.f, x1_in, x_out, next_xp, T, d.H, d.I, st));
                 }
                 xp_ready = !last;
             }

@@ -692,8 +692,8 @@ def test_stage_profile_reports_every_kernel_of_a_decode_step():
             m.forward_split(db.batch)
         m.sync()
         prof = m.profile_read(0, reset=True)
-        # a decode step of up to 32 sequences: the input rows are packed, then six launches
-        assert set(prof) == {"pack_x", "gemm_qkv", "attn", "attn_combine", "gemm_o", "gemm_gu", "gemm_down"}
+        # a decode step of up to 32 sequences: six launches
+        assert set(prof) == {"gemm_qkv", "attn", "attn_combine", "gemm_o", "gemm_gu", "gemm_down"}
         for stage, (ms, n) in prof.items():
             assert n == 3 and 0.0 < ms < 50.0, (stage, ms, n)
         m.profile(("attn",))

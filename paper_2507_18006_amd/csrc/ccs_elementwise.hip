@@ -47,21 +47,23 @@ hipError_t launch_clone(void *dst, const void *src, size_t bytes, hipStream_t st
 
 // ---------------------------------------------------------------------------------------------
 // Packing: row-major [N, K] bf16 -> fragment-packed (activations) or grouped fragment-packed
-// (weights, module_create).  One thread per 16-byte chunk (8 consecutive k of one row).
+// (weights, module_create).  One thread per 16-byte slot of the OUTPUT, a wavefront per 1 KiB
+// fragment: the writes are whole contiguous fragments, the reads 64-byte pieces of 16 rows (the
+// other way round - reads in row order, 16-byte writes 256 bytes apart - ran at a third of the rate).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4 *__restrict__ src,
                                                         uint4 *__restrict__ dst, int N, int K,
                                                         int blk_stride, int blk_offset, int grouped,
                                                         const uint4 *__restrict__ gain)
 {
-    const int kchunks = K >> 3;
-    const size_t total = (size_t)N * kchunks;
-    const int kfrags = K >> 5;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        int n = (int)(i / kchunks), kc = (int)(i % kchunks);
-        int nb = (n >> 4) * blk_stride + blk_offset;
-        const size_t frag = grouped ? weight_fragment(nb, kc >> 2, kfrags) : (size_t)nb * kfrags + (kc >> 2);
-        uint4 v = src[i];
+    const int kchunks = K >> 3, kfrags = K >> 5;
+    const int lane = threadIdx.x & 63;
+    const size_t n_frags = (size_t)((N + 15) >> 4) * kfrags;
+    for (size_t f = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6); f < n_frags; f += (size_t)gridDim.x * 4) {
+        const int rb = (int)(f / kfrags), kb = (int)(f % kfrags);
+        const int n = rb * 16 + (lane & 15), kc = kb * 4 + (lane >> 4);
+        if (n >= N) continue;   // rows past the end of the last block stay as they are (never part of a result)
+        uint4 v = src[(size_t)n * kchunks + kc];
         if (gain) {   // fold the gains of the RMSNorm in front of this projection into the weight
             const uint4 g = gain[kc];
             v.x = pack2bf(bf_lo(v.x) * bf_lo(g.x), bf_hi(v.x) * bf_hi(g.x));
@@ -69,16 +71,18 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4 *__restrict_
             v.z = pack2bf(bf_lo(v.z) * bf_lo(g.z), bf_hi(v.z) * bf_hi(g.z));
             v.w = pack2bf(bf_lo(v.w) * bf_lo(g.w), bf_hi(v.w) * bf_hi(g.w));
         }
-        dst[frag * 64 + (n & 15) + 16 * (kc & 3)] = v;
+        const int nb = rb * blk_stride + blk_offset;
+        const size_t frag = grouped ? weight_fragment(nb, kb, kfrags) : (size_t)nb * kfrags + kb;
+        dst[frag * 64 + lane] = v;
     }
 }
 
 hipError_t launch_pack_bf16(const void *src, void *dst_packed, int N, int K, int blk_stride,
                             int blk_offset, bool grouped, const void *gain, hipStream_t st)
 {
-    size_t total = (size_t)N * (K / 8);
-    if (!total) return hipSuccess;
-    int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
+    const size_t frags = (size_t)((N + 15) / 16) * (K / 32);
+    if (!frags) return hipSuccess;
+    int blocks = (int)((frags + 3) / 4 < 16384 ? (frags + 3) / 4 : 16384);
     hipLaunchKernelGGL(pack_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const uint4 *)src,
                        (uint4 *)dst_packed, N, K, blk_stride, blk_offset, grouped ? 1 : 0, (const uint4 *)gain);
     return hipGetLastError();

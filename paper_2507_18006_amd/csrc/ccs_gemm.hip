@@ -351,7 +351,7 @@ template <int BM, int NST>
 __global__ __launch_bounds__(256, (BM == 128 && NST <= 3) ? 2 : 1) void gemm_tiled_dma_kernel(
     const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, int epi, const bf16_t *__restrict__ res,
     bf16_t *__restrict__ out, int M, int N, int kfrags, int tiles_m, int tiles, float *__restrict__ part,
-    int kt_per_seg)
+    int kt_per_seg, int x_rows)
 {
     using C = DmaCfg<BM, NST>;
     extern __shared__ uint4 lds[];
@@ -383,6 +383,14 @@ __global__ __launch_bounds__(256, (BM == 128 && NST <= 3) ? 2 : 1) void gemm_til
         const int blk = is_x ? min(mb0 + f - C::TN, mblk - 1) : min(nb0 + f, nblk - 1);
         src[i] = is_x ? Xp + ((size_t)blk * kfrags + kt0) * 64 + lane : Wp + weight_fragment(blk, kt0, kfrags) * 64 + lane;
         kstep[i] = is_x ? 64 : kWGroup * 64;
+        if (is_x && x_rows) {
+            // activations as plain row-major rows [M, K]: fragment slot `lane` (row lane % 16, k quarter
+            // lane / 16) is 16 contiguous bytes of its row, so the direct-to-LDS load can fetch it from
+            // there (the LDS side stays in fragment order); rows past M repeat the last row, never stored
+            const int row = min(blk * 16 + (lane & 15), M - 1);
+            src[i] = Xp + (size_t)row * kfrags * 4 + (size_t)kt0 * 4 + (lane >> 4);
+            kstep[i] = 4;
+        }
     }
     // (a __device__ helper, not a lambda: the host pass cannot instantiate a lambda that holds the
     // direct-to-LDS builtin and then silently drops the kernel's launch stub)
@@ -556,14 +564,14 @@ __global__ __launch_bounds__(256, (BM == 128 && NST <= 3) ? 2 : 1) void gemm_til
 
 template <int BM, int NST>
 hipError_t launch_gemm_tiled_dma(const void *Wp, const void *Xp, int epi, const void *res, void *out,
-                                 int M, int N, int K, float *part, int S, hipStream_t st)
+                                 int M, int N, int K, float *part, int S, bool x_rows, hipStream_t st)
 {
     using C = DmaCfg<BM, NST>;
     auto kern = gemm_tiled_dma_kernel<BM, NST>;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + 255) / 256, tiles = tiles_m * tiles_n;
     const int kfrags = K / 32, per = (kfrags + S - 1) / S;
     hipLaunchKernelGGL(kern, dim3(tiles * S), dim3(256), C::LDS_BYTES, st, (const uint4 *)Wp, (const uint4 *)Xp, epi,
-                       (const bf16_t *)res, (bf16_t *)out, M, N, kfrags, tiles_m, tiles, part, per);
+                       (const bf16_t *)res, (bf16_t *)out, M, N, kfrags, tiles_m, tiles, part, per, x_rows ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -594,20 +602,20 @@ size_t tiled_partial_bytes(int M, int N, int K, long variant_rows)
     return S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
 }
 
-hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void *res, void *out,
+hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, bool x_rows, int epi, const void *res, void *out,
                              int M, int N, int K, long variant_rows, float *partials, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     const int S = tiled_segments(N, K, variant_rows);
     if (S > 1) {
-        hipError_t e = launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, nullptr, nullptr, M, N, K, partials, S, st);
+        hipError_t e = launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, nullptr, nullptr, M, N, K, partials, S, x_rows, st);
         if (e != hipSuccess) return e;
         return launch_partial_reduce(partials, S, epi, res, out, nullptr, M, N, st);
     }
     // 256 x 128 tiles, 3-stage ring (72 KiB): two workgroups share a CU, so one's epilogue and
     // prologue run under the other's main loop - measured 5-20 % faster than one 256 x 256 or
     // 256 x 128 workgroup per CU with a deeper ring on every projection shape of the 13B layer.
-    return launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, st);
+    return launch_gemm_tiled_dma<128, 3>(Wp, Xp, epi, res, out, M, N, K, nullptr, 1, x_rows, st);
 }
 
 // Function attributes (dynamic LDS sizes) of this file's kernels; once per process, outside any

@@ -80,13 +80,14 @@ hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partia
 // EPI_STORE_RM: out_packed (may be null) receives a second, fragment-packed copy of the result.
 hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, void *out_packed,
                                  int M, int N, hipStream_t st);
-// bf16 LDS-tiled MFMA GEMM for any M (Xp readable up to M rounded up to 16 rows).  When the batch
+// bf16 LDS-tiled MFMA GEMM for any M (Xp fragment-packed and readable up to M rounded up to 16 rows,
+// or, with x_rows, the plain row-major bf16 rows [M, K]).  When the batch
 // is too small to fill the GPU, K is cut into tiled_segments(N, K, variant_rows) segments whose
 // partial sums go through `partials` (tiled_partial_bytes) and launch_partial_reduce;
 // variant_rows is the row count of the full batch the launch belongs to.
 int tiled_segments(int N, int K, long variant_rows);
 size_t tiled_partial_bytes(int M, int N, int K, long variant_rows);
-hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, int epi, const void *res, void *out,
+hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, bool x_rows, int epi, const void *res, void *out,
                              int M, int N, int K, long variant_rows, float *partials, hipStream_t st);
 
 // ---- weight-streaming projections, one launch each (ccs_gemm_stream.hip) -----------------------

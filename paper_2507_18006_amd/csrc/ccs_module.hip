@@ -95,6 +95,10 @@ struct WsPlan {
 // with a K split and a reduction kernel stream faster (measured on the 70B down projection: 80 us
 // against 102 us).  Decided from the weight shape and the FULL batch's row count.
 inline bool store_split(int K, long long variant_rows) { return variant_rows > 32 && K > 8192; }
+// A single projection of up to this many rows (of the FULL batch) reads the caller's row-major rows in
+// the LDS-tiled GEMM itself; larger batches are packed first.
+constexpr long long kDirectRowsMax = 512;
+constexpr long long kLinearStreamRowsMax = 32;
 
 int check_desc(const ccs_module_desc *D, Dims *out)
 {
@@ -178,8 +182,7 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
     if (D->kind == CCS_LINEAR) {
         if (D->dtype == CCS_BF16) {
             p.xp = take(r16 * d.in_f * 2);
-            p.scratch_bytes = skinny ? ccs::skinny_partial_bytes((int)rows, d.out_f, d.in_f)
-                                     : ccs::tiled_partial_bytes((int)rows, d.out_f, d.in_f, vrows);
+            p.scratch_bytes = vrows <= kLinearStreamRowsMax ? 0 : ccs::tiled_partial_bytes((int)rows, d.out_f, d.in_f, vrows);
             p.scratch = take(p.scratch_bytes);
         }
     } else if (D->dtype == CCS_BF16) {
@@ -408,23 +411,29 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     if (D.kind == CCS_LINEAR) {
         const char *A = A0;
         const int M = b->n_seqs;
+        // a single projection streams its weight in one launch up to 32 rows; from 33 rows on the
+        // LDS-tiled GEMM with its K split is faster (measured on the 11008 -> 4096 projection: 26 us at
+        // 65 rows against 28 us at 32 rows in the streaming form)
+        const bool skinny = bf && variant_rows <= kLinearStreamRowsMax;
         if (!bf) {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)b->x, (const float *)(A + m->ap.w), nullptr, (float *)b->y, M, d.out_f, d.in_f, st));
             return CCS_OK;
         }
         WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false, 0, (long)variant_rows);
         if (p.total > ws_bytes) return fail(CCS_ENOMEM, "%s workspace has %zu bytes, batch needs %zu", ws_static ? "the static" : "the replica's", ws_bytes, p.total);
-        if (skinny && !store_split(d.in_f, variant_rows)) {   // one launch, straight from the caller's rows
+        if (skinny) {   // one launch, straight from the caller's rows
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.w, stream_store_nb(d.out_f), b->x, true, false, 0.f, nullptr, b->y, nullptr, M, d.out_f, d.in_f, st));
             return CCS_OK;
         }
-        CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, nullptr, st));
-        if (skinny) {
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.w, ws + p.xp, (float *)(ws + p.scratch), M, d.out_f, d.in_f, st));
-            CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_partial_reduce((const float *)(ws + p.scratch), skinny_segments(d.out_f, d.in_f), EPI_STORE_RM, nullptr, b->y, nullptr, M, d.out_f, st));
-        } else {
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, (long)variant_rows, (float *)(ws + p.scratch), st));
+        if (variant_rows <= kDirectRowsMax) {
+            // LDS-tiled; its direct-to-LDS loads fetch the fragments straight from the caller's rows.  Those
+            // are 16-byte pieces 64 lanes apart, four times the address unit's work of a packed fragment:
+            // worth it while the launch is short (it saves the packing launch), a loss of 10 % at 1024 rows
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, b->x, true, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, (long)variant_rows, (float *)(ws + p.scratch), st));
+            return CCS_OK;
         }
+        CCS_STAGE(CCS_ST_PACK_X, launch_pack_bf16(b->x, ws + p.xp, M, d.in_f, 1, 0, false, nullptr, st));
+        CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_tiled(A + m->ap.w, ws + p.xp, false, EPI_STORE_RM, nullptr, b->y, M, d.out_f, d.in_f, (long)variant_rows, (float *)(ws + p.scratch), st));
         return CCS_OK;
     }
 
@@ -500,7 +509,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             // LDS-tiled path: normalised rows h (no gains: they are folded into the weights), one launch
             // per projection (two when K is split)
 #define CCS_GEMM(sid, woff, xoff, epi, res, out, N, K) \
-    CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st))
+    CCS_STAGE(sid, launch_gemm_tiled(A + (woff), ws + (xoff), false, (epi), (res), (out), T, (N), (K), (long)variant_rows, scratch, st))
             CCS_STAGE(attn ? CCS_ST_RMSNORM1 : CCS_ST_RMSNORM2, launch_rmsnorm(dt, x_in, nullptr, ws + p.h, T, d.H, D.rms_eps, st));
             if (attn) {
                 CCS_GEMM(CCS_ST_GEMM_QKV, m->ap.qkv, p.h, EPI_STORE_RM, nullptr, ws + p.qkv, d.W3, d.H);

@@ -496,6 +496,68 @@ hipError_t launch_rope_table(void *tab, int d, float base, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Decode, bf16, head_dim 128: what follows a K-split Q/K/V projection of raw rows.  Sums the K
+// segments' partials in segment order, scales by the row's RMSNorm factor (from the segments' sums of
+// squares, also in segment order), rotates q and k to position lens[row], stores q (bf16) into the
+// row-major qkv buffer and appends the rotated key and the value at cache slot lens[row].  One
+// thread owns 4 columns of the first half of a head and their partners 64 up.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void qkv_partials_rope_decode_kernel(
+    const float *__restrict__ part, const float *__restrict__ ssq, int S, int M, int nq, int nkv, int K, float eps,
+    const float2 *__restrict__ tab, const int32_t *__restrict__ lens, bf16_t *__restrict__ qkv,
+    bf16_t *__restrict__ k_cache, bf16_t *__restrict__ v_cache, int cap)
+{
+    const int heads = nq + 2 * nkv, width = heads * 128;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * heads * 16) return;
+    const int m = idx / (heads * 16), hu = idx % (heads * 16);
+    const int head = hu >> 4, c = (hu & 15) * 4;
+    const size_t seg = (size_t)M * width;
+    const float *p = part + (size_t)m * width + head * 128 + c;
+    float4 lo = *(const float4 *)p, hi = *(const float4 *)(p + 64);
+    float tot = ssq[m];
+    for (int k = 1; k < S; ++k) {
+        const float4 a = *(const float4 *)(p + k * seg), b = *(const float4 *)(p + k * seg + 64);
+        lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+        hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+        tot += ssq[k * M + m];
+    }
+    const float rs = 1.0f / sqrtf(tot / (float)K + eps);
+    const int pos = cached_len(lens, m, cap);
+    float l[4] = {lo.x * rs, lo.y * rs, lo.z * rs, lo.w * rs}, h[4] = {hi.x * rs, hi.y * rs, hi.z * rs, hi.w * rs};
+    if (head < nq + nkv) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float cs, sn;
+            rope_cs(tab, c + e, pos, cs, sn);
+            const float a = l[e], b = h[e];
+            l[e] = a * cs - b * sn;
+            h[e] = b * cs + a * sn;
+        }
+    }
+    const uint2 plo = make_uint2(pack2bf(l[0], l[1]), pack2bf(l[2], l[3]));
+    const uint2 phi = make_uint2(pack2bf(h[0], h[1]), pack2bf(h[2], h[3]));
+    bf16_t *dst;
+    if (head < nq) dst = qkv + (size_t)m * width + head * 128 + c;
+    else if (head < nq + nkv) dst = k_cache + (((size_t)m * nkv + (head - nq)) * cap + pos) * 128 + c;
+    else dst = v_cache + (((size_t)m * nkv + (head - nq - nkv)) * cap + pos) * 128 + c;
+    *(uint2 *)dst = plo;
+    *(uint2 *)(dst + 64) = phi;
+}
+
+hipError_t launch_qkv_partials_rope_decode(const float *partials, const float *ssq_partials, int S, int M, int nq,
+                                           int nkv, int K, float eps, const void *tab, const int32_t *lens_dev,
+                                           void *qkv, void *k_cache, void *v_cache, int cap, hipStream_t st)
+{
+    if (M <= 0) return hipSuccess;
+    const int total = M * (nq + 2 * nkv) * 16;
+    hipLaunchKernelGGL(qkv_partials_rope_decode_kernel, dim3((total + 255) / 256), dim3(256), 0, st, partials, ssq_partials, S,
+                       M, nq, nkv, K, eps, (const float2 *)tab, lens_dev, (bf16_t *)qkv, (bf16_t *)k_cache,
+                       (bf16_t *)v_cache, cap);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void swiglu_f32_kernel(const float *__restrict__ gu,
                                                          float *__restrict__ u, size_t total, int I)
 {

@@ -8,11 +8,8 @@
 //  * gemm_tiled_dma: LDS-tiled, for compute-bound row counts (prefill): 256 x 128 x 32 workgroup
 //    tiles of v_mfma_f32_32x32x16_bf16, operands brought in by direct-to-LDS loads through a
 //    3-stage ring, optional deterministic K split for launches that cannot fill the GPU.
-//  * gemm_skinny: weight-streaming with a K split for <= 64 rows, v_mfma_f32_16x16x32_bf16: no LDS
-//    staging of operands, each wavefront streams 8 KiB weight pieces straight into MFMA operands;
-//    K is cut into segments whose count depends on the weight shape only and partial sums are
-//    reduced in a fixed order by a second kernel.  Used where the one-launch form
-//    (ccs_gemm_stream.hip) is slower: 33..64 rows against a long-K weight.
+//  * skinny_reduce: fixed-order sum of K-split partial sums + epilogue (the weight-streaming
+//    projections for <= 64 rows live in ccs_gemm_stream.hip).
 //  * gemm_f32: plain FMA kernel for the fp32 path.
 #include "ccs_common.h"
 #include "ccs_kernels.h"
@@ -60,144 +57,8 @@ hipError_t launch_gemm_f32(const float *x, const float *W, const float *res, flo
 }
 
 // =============================================================================================
-// Weight-streaming GEMM (decode-sized row counts)
+// Reduction of K-split partial sums (both the LDS-tiled GEMM and the weight-streaming projections)
 // =============================================================================================
-constexpr int kSkNB = kWGroup;   // 16-row weight blocks per wavefront: one block group (128 output columns)
-constexpr int kSkU = 2;          // most k-steps (8 KiB of weights each) per register set of a wavefront
-// The grouped weight layout makes the 8 fragments a wavefront needs for one k-step one
-// contiguous 8 KiB piece, and consecutive k-steps consecutive pieces (measured on a 940 MB
-// weight, loads only: 6.8 TB/s against 5.9 TB/s for 8 separate 1 KiB streams and 7.0 TB/s for a
-// flat read).  128 output columns per wavefront also halve the activation fragments (L2 hits)
-// fetched per weight byte against 64 columns; at 64 rows those cost 20 % of the rate before.
-// Launch shape from the weight shape alone.  Measured sweeps (32 and 64 rows, 33 MB to 940 MB
-// weights): four wavefronts per workgroup, each a contiguous quarter of the K segment, and about
-// one workgroup per CU - long streams per wavefront beat more, shorter ones (every wavefront
-// pays a pipeline fill and an epilogue) - so K is cut into floor(256 / tiles) segments.
-constexpr int kSkWaves = 4;
-
-static inline int sk_tiles(int N) { return (N / 16 + kSkNB - 1) / kSkNB; }
-
-int skinny_segments(int N, int K)
-{
-    const int kfrags = K / 32, tiles = sk_tiles(N);
-    int S = 256 / tiles;
-    int max_s = kfrags / (kSkWaves * kSkU * 2);  // at least two full register sets per wavefront
-    if (S > max_s) S = max_s;
-    if (S < 1) S = 1;
-    const int per = (kfrags + S - 1) / S;
-    return (kfrags + per - 1) / per;
-}
-
-size_t skinny_partial_bytes(int M, int N, int K)
-{
-    return (size_t)skinny_segments(N, K) * (size_t)M * (size_t)N * sizeof(float);
-}
-
-// (3 or 4 row blocks: 128 accumulator registers plus two 2-step register sets need more than 256
-// registers, so one workgroup per CU; measured faster than 1-step sets at two workgroups per CU)
-template <int MB>
-__global__ __launch_bounds__(kSkWaves * 64, MB <= 2 ? 2 : 1) void gemm_skinny_kernel(
-    const uint4 *__restrict__ Wp, const uint4 *__restrict__ Xp, float *__restrict__ part, int nblk,
-    int kfrags, int ntiles, int kf_seg, int M, int N)
-{
-    extern __shared__ float red[];   // two buffers of MB*16 padded rows
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x % ntiles, seg = blockIdx.x / ntiles;
-    const int seg_lo = seg * kf_seg;
-    const int seg_hi = min(kfrags, seg_lo + kf_seg);
-    const int per_wave = (seg_hi - seg_lo + kSkWaves - 1) / kSkWaves;
-    const int kb_lo = min(seg_hi, seg_lo + wave * per_wave);
-    const int kb_hi = min(seg_hi, kb_lo + per_wave);
-
-    // fragment (j, kb) of this tile's block group: wp + (kb * kSkNB + j) * 64
-    const uint4 *wp = Wp + (size_t)tile * kfrags * (kSkNB * 64) + lane;
-    const uint4 *xp[MB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i) xp[i] = Xp + (size_t)i * kfrags * 64 + lane;
-
-    f32x4_t acc[kSkNB][MB];
-#pragma unroll
-    for (int j = 0; j < kSkNB; ++j)
-#pragma unroll
-        for (int i = 0; i < MB; ++i) acc[j][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    // Two register sets of U k-steps each, rolling: while one set is multiplied the other is in
-    // flight, and a set is reloaded as soon as its MFMAs have issued (a wavefront that only loads,
-    // waits and multiplies leaves the memory system idle during its MFMA phase).  The loop body
-    // has no branch around a load - past the end a set re-loads the last k-step (a cache hit) and
-    // is not multiplied - so that the compiler's wait counts stay exact.
-    constexpr int U = kSkU;
-    uint4 w0[U][kSkNB], x0[U][MB], w1[U][kSkNB], x1[U][MB];
-    const int n_sets = (kb_hi - kb_lo + U - 1) / U;
-#define SK_LOAD(W_, X_, SET)                                                                              \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
-        const int kk = min(kb_lo + (SET) * U + u, kb_hi - 1);                                             \
-        _Pragma("unroll") for (int j = 0; j < kSkNB; ++j) W_[u][j] = ld_stream(wp + ((size_t)kk * kSkNB + j) * 64); \
-        _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * 64];                 \
-    }
-#define SK_MUL(W_, X_, SET)                                                                               \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
-        if (kb_lo + (SET) * U + u < kb_hi) {                                                              \
-            _Pragma("unroll") for (int j = 0; j < kSkNB; ++j)                                              \
-                _Pragma("unroll") for (int i = 0; i < MB; ++i) acc[j][i] = mfma16(W_[u][j], X_[u][i], acc[j][i]); \
-        }                                                                                                 \
-    }
-    if (n_sets > 0) {
-        SK_LOAD(w0, x0, 0);
-        SK_LOAD(w1, x1, 1);
-        for (int i = 0; i < n_sets; i += 2) {
-            SK_MUL(w0, x0, i);
-            SK_LOAD(w0, x0, i + 2);
-            SK_MUL(w1, x1, i + 1);
-            SK_LOAD(w1, x1, i + 3);
-        }
-    }
-#undef SK_LOAD
-#undef SK_MUL
-
-    // In-workgroup reduction and store through two LDS buffers of row-major [row][128 columns]
-    // outputs (rows padded to 528 bytes: conflict-free 16-byte accesses): wavefronts 2, 3 write
-    // their accumulators, wavefronts 0, 1 add them to their own (0 + 2, 1 + 3) and write the
-    // sums; then every thread adds the two buffers for its outputs and stores them - a wavefront
-    // writes whole 512-byte row segments.  The order (0 + 2) + (1 + 3) is fixed.
-    constexpr int ROWF = kSkNB * 16 + 4;   // floats per padded row
-    constexpr int BUF = MB * 16 * ROWF;    // floats per buffer
-    float *slot = red + (wave & 1) * BUF + (lane & 15) * ROWF + (lane >> 4) * 4;   // + i * 16 * ROWF + j * 16
-    if (wave >= 2) {
-#pragma unroll
-        for (int j = 0; j < kSkNB; ++j)
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-                *(float4 *)(slot + i * 16 * ROWF + j * 16) = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
-    }
-    __syncthreads();
-    if (wave < 2) {
-#pragma unroll
-        for (int j = 0; j < kSkNB; ++j)
-#pragma unroll
-            for (int i = 0; i < MB; ++i) {
-                float4 *p = (float4 *)(slot + i * 16 * ROWF + j * 16);
-                const float4 t = *p;
-                *p = make_float4(acc[j][i][0] + t.x, acc[j][i][1] + t.y, acc[j][i][2] + t.z, acc[j][i][3] + t.w);
-            }
-    }
-    __syncthreads();
-    // value of the tile at (row m, column c of 128)
-    auto fetch = [&](int m, int c) -> float4 {
-        float4 v = *(const float4 *)(red + m * ROWF + c);
-        const float4 t = *(const float4 *)(red + BUF + m * ROWF + c);
-        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
-        return v;
-    };
-    constexpr int QUADS = MB * 16 * (kSkNB * 4);   // float4 outputs of the tile
-    for (int q = threadIdx.x; q < QUADS; q += kSkWaves * 64) {
-        const int m = q / (kSkNB * 4), c = (q % (kSkNB * 4)) * 4;
-        const int n = tile * (kSkNB * 16) + c;
-        if (m < M && n < N) *(float4 *)(part + ((size_t)seg * M + m) * N + n) = fetch(m, c);
-    }
-}
-
 // Fixed-order sum over the K segments + epilogue.  One thread per 4 consecutive outputs.
 __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restrict__ part, int S, int M,
                                                             int N, int epi,
@@ -239,40 +100,6 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const float *__restr
         float o2 = g.z / (1.0f + __expf(-g.z)) * u.z, o3 = g.w / (1.0f + __expf(-g.w)) * u.w;
         *(uint2 *)(out + packed_index(m, c, ncols >> 5)) = make_uint2(pack2bf(o0, o1), pack2bf(o2, o3));
     }
-}
-
-constexpr int sk_lds_bytes(int MB) { return 2 * MB * 16 * (kSkNB * 16 + 4) * (int)sizeof(float); }
-
-template <int MB>
-static hipError_t sk_launch(dim3 grid, hipStream_t st, const uint4 *Wp, const uint4 *Xp, float *partials, int nblk,
-                            int kfrags, int ntiles, int kf_seg, int M, int N)
-{
-    constexpr int kLds = sk_lds_bytes(MB);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MB>), grid, dim3(kSkWaves * 64), kLds, st, Wp, Xp, partials, nblk, kfrags,
-                       ntiles, kf_seg, M, N);
-    return hipGetLastError();
-}
-
-// (Letting the workgroup that completes a tile's last segment do the reduction needs device-scope
-// fences in every workgroup; measured, they cost 25-35 us per launch, several times the reduction
-// kernel they would save.)
-hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N, int K, hipStream_t st)
-{
-    if (M <= 0) return hipSuccess;
-    if (M > kSkinnyMaxRows) return hipErrorInvalidValue;
-    const int kfrags = K / 32, nblk = N / 16, ntiles = sk_tiles(N);
-    const int S = skinny_segments(N, K);
-    const int kf_seg = (kfrags + S - 1) / S;
-    dim3 grid(ntiles * S);
-    const int mb = (M + 15) / 16;
-#define CCS_SK(MBV) return sk_launch<MBV>(grid, st, (const uint4 *)Wp, (const uint4 *)Xp, partials, nblk, kfrags, ntiles, kf_seg, M, N)
-    switch (mb) {
-        case 1: CCS_SK(1);
-        case 2: CCS_SK(2);
-        case 3: CCS_SK(3);
-        default: CCS_SK(4);
-    }
-#undef CCS_SK
 }
 
 hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, void *out_packed,
@@ -624,11 +451,6 @@ hipError_t init_gemm_kernels()
 {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_tiled_dma_kernel<128, 3>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)DmaCfg<128, 3>::LDS_BYTES);
-    const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<1>, attr, sk_lds_bytes(1));
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<2>, attr, sk_lds_bytes(2));
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<3>, attr, sk_lds_bytes(3));
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<4>, attr, sk_lds_bytes(4));
     if (e == hipSuccess) e = init_gemm_stream_kernels();
     return e;
 }

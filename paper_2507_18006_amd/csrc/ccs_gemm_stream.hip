@@ -22,6 +22,11 @@
 //     projection; SwiGLU into a fragment-packed u; and for the decode Q/K/V projection the rotary
 //     embedding, the q store and the KV-cache append (a tile holds dims [32 s, 32 s + 32) and
 //     [64 + 32 s, 64 + 32 s + 32) of one head, i.e. whole rotary pairs).
+//   * GS_PARTIALS: for 33..64 rows against a large weight the activations are re-read too often by
+//     narrow tiles (the time grows with the activation bytes), so those launches keep 128-column
+//     tiles and cut K into segments over the workgroups instead (a count that depends on the weight
+//     shape only); the kernel then leaves fp32 partial sums (and per-segment sums of squares) and a
+//     small second kernel adds them in segment order and applies the epilogue.
 // Tile width NB and everything else about the launch depend on the weight shape and on the row
 // count of the full batch only, and every output row is computed from its own input row alone,
 // so a row's bits do not depend on the batch.
@@ -56,6 +61,11 @@ struct GsArgs {
     const bf16_t *res;    // GS_STORE: optional residual, row-major [M, N]
     bf16_t *out;
     bf16_t *out_packed;   // GS_STORE: optional second copy of the result, fragment-packed [M16, N]
+    // K segments over workgroups (GS_PARTIALS; otherwise one segment = all of K)
+    int ntiles;           // column tiles of the launch: workgroup b works on tile b % ntiles, segment b / ntiles
+    int kf_seg;           // k-steps per segment
+    float *part;          // fp32 partial sums [S, M, N]
+    float *ssq_part;      // optional: the rows' sums of squares per segment [S, M]
     // GS_QKV_DECODE
     int nq, nkv;
     const float2 *tab;
@@ -72,11 +82,12 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     constexpr int BUF = MB * 16 * ROWF;    // floats per reduction buffer
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x;
+    const int tile = blockIdx.x % a.ntiles, seg = blockIdx.x / a.ntiles;
     const int kfrags = a.kfrags, G = a.G;
-    const int per_wave = (kfrags + kGsWaves - 1) / kGsWaves;
-    const int kb_lo = min(kfrags, wave * per_wave);
-    const int kb_hi = min(kfrags, kb_lo + per_wave);
+    const int seg_lo = seg * a.kf_seg, seg_hi = min(kfrags, seg_lo + a.kf_seg);
+    const int per_wave = (seg_hi - seg_lo + kGsWaves - 1) / kGsWaves;
+    const int kb_lo = min(seg_hi, seg_lo + wave * per_wave);
+    const int kb_hi = min(seg_hi, kb_lo + per_wave);
 
     // 16-row weight blocks of this tile
     constexpr int HH = NB >= 2 ? NB / 2 : 1;   // GS_QKV_DECODE: blocks per half of the head
@@ -145,7 +156,7 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
         if (kb_lo + (SET) * U + u < kb_hi) {                                                              \
             _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                 \
                 _Pragma("unroll") for (int i = 0; i < MB; ++i) acc[j][i] = gs_mfma(W_[u][j], X_[u][i], acc[j][i]); \
-            if (EPI != GS_STORE || norm) {                                                                \
+            if (EPI == GS_SWIGLU || EPI == GS_QKV_DECODE || norm) {                                       \
                 _Pragma("unroll") for (int i = 0; i < MB; ++i) sq[i] = gs_mfma(X_[u][i], X_[u][i], sq[i]); \
             }                                                                                             \
         }                                                                                                 \
@@ -207,7 +218,8 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
         float tot = wssq[m];
 #pragma unroll
         for (int w = 1; w < kGsWaves; ++w) tot += wssq[w * (MB * 16) + m];
-        rsv[m] = norm ? 1.0f / sqrtf(tot / (float)(kfrags * 32) + a.eps) : 1.0f;
+        rsv[m] = (norm && EPI != GS_PARTIALS) ? 1.0f / sqrtf(tot / (float)(kfrags * 32) + a.eps) : 1.0f;
+        if (EPI == GS_PARTIALS && a.ssq_part && tile == 0 && m < a.M) a.ssq_part[seg * a.M + m] = tot;
     }
     __syncthreads();
     // value of the tile at (row m, column c of NB * 16), scaled by the row's norm factor
@@ -223,7 +235,13 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
         return v;
     };
     constexpr int QUADS = MB * 16 * (NB * 4);   // float4 outputs of the tile
-    if (EPI == GS_STORE) {
+    if (EPI == GS_PARTIALS) {
+        for (int q = threadIdx.x; q < QUADS; q += kGsWaves * 64) {
+            const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
+            const int n = tile * (NB * 16) + c;
+            if (m < a.M && n < a.N) *(float4 *)(a.part + ((size_t)seg * a.M + m) * a.N + n) = fetch(m, c);
+        }
+    } else if (EPI == GS_STORE) {
         for (int q = threadIdx.x; q < QUADS; q += kGsWaves * 64) {
             const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
             const int n = tile * (NB * 16) + c;
@@ -349,6 +367,7 @@ hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *X, bool 
     a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = norm ? 1 : 0; a.eps = eps;
     a.M = M; a.N = N; a.res = (const bf16_t *)res; a.out = (bf16_t *)out; a.out_packed = (bf16_t *)out_packed;
     const int tiles = ((N / 16) + nb - 1) / nb;
+    a.ntiles = tiles; a.kf_seg = a.kfrags;
 #define CCS_GS(NBV) (x_rows ? gs_launch_mb<NBV, GS_STORE, 1>(tiles, a, st) : gs_launch_mb<NBV, GS_STORE, 0>(tiles, a, st))
     switch (nb) {
         case 1: return CCS_GS(1);
@@ -368,6 +387,7 @@ hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *X, bool x_rows,
     a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = 1; a.eps = eps;
     a.M = M; a.N = N2; a.out = (bf16_t *)u_packed;
     const int tiles = ((N2 / 16) + 7) / 8;
+    a.ntiles = tiles; a.kf_seg = a.kfrags;
     return x_rows ? gs_launch_mb<8, GS_SWIGLU, 1>(tiles, a, st) : gs_launch_mb<8, GS_SWIGLU, 0>(tiles, a, st);
 }
 
@@ -383,9 +403,46 @@ hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *X, bool x_r
     a.nq = nq; a.nkv = nkv; a.tab = (const float2 *)tab; a.lens = lens_dev; a.kc = (bf16_t *)k_cache; a.vc = (bf16_t *)v_cache;
     a.cap = cap;
     const int heads = nq + 2 * nkv;
+    a.kf_seg = a.kfrags;
+    a.ntiles = stream_qkv_nb(heads) == 8 ? heads : heads * 2;
     if (stream_qkv_nb(heads) == 8)
         return x_rows ? gs_launch_mb<8, GS_QKV_DECODE, 1>(heads, a, st) : gs_launch_mb<8, GS_QKV_DECODE, 0>(heads, a, st);
     return x_rows ? gs_launch_mb<4, GS_QKV_DECODE, 1>(heads * 2, a, st) : gs_launch_mb<4, GS_QKV_DECODE, 0>(heads * 2, a, st);
+}
+
+// K segments of the GS_PARTIALS form for a [N, K] weight: from the weight shape alone.  Measured sweeps
+// (32 and 64 rows, 33 MB to 940 MB weights): about one workgroup per compute unit with long streams
+// beats more, shorter ones, so K is cut into floor(256 / tiles) segments of at least 32 k-steps.
+int skinny_segments(int N, int K)
+{
+    const int kfrags = K / 32, tiles = ((N + 15) / 16 + 7) / 8;
+    int S = 256 / tiles;
+    const int max_s = kfrags / 32;
+    if (S > max_s) S = max_s;
+    if (S > 64) S = 64;
+    if (S < 1) S = 1;
+    const int per = (kfrags + S - 1) / S;
+    return (kfrags + per - 1) / per;
+}
+
+size_t skinny_partial_bytes(int M, int N, int K)
+{
+    return (size_t)skinny_segments(N, K) * (size_t)M * (size_t)N * sizeof(float);
+}
+
+hipError_t launch_gemm_stream_partials(const void *Wp, const void *X, bool x_rows, bool norm, float *partials,
+                                       float *ssq_partials, int M, int N, int K, hipStream_t st)
+{
+    if (M <= 0) return hipSuccess;
+    if (M > kSkinnyMaxRows || (K & 31) || (N & 15)) return hipErrorInvalidValue;
+    GsArgs a{};
+    a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = norm ? 1 : 0;
+    a.M = M; a.N = N; a.part = partials; a.ssq_part = norm ? ssq_partials : nullptr;
+    const int S = skinny_segments(N, K);
+    a.ntiles = ((N / 16) + 7) / 8;
+    a.kf_seg = (a.kfrags + S - 1) / S;
+    const int grid = a.ntiles * S;
+    return x_rows ? gs_launch_mb<8, GS_PARTIALS, 1>(grid, a, st) : gs_launch_mb<8, GS_PARTIALS, 0>(grid, a, st);
 }
 
 hipError_t init_gemm_stream_kernels()
@@ -395,6 +452,7 @@ hipError_t init_gemm_stream_kernels()
     if (e == hipSuccess) e = gs_attr_mb<4, GS_STORE>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_STORE>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_SWIGLU>();
+    if (e == hipSuccess) e = gs_attr_mb<8, GS_PARTIALS>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_QKV_DECODE>();
     if (e == hipSuccess) e = gs_attr_mb<4, GS_QKV_DECODE>();
     return e;

@@ -69,13 +69,21 @@ enum GemmEpilogue {
 };
 // Largest row count the weight-streaming variants accept in one launch.
 constexpr int kSkinnyMaxRows = 64;
-// Weight-streaming GEMM with a K split, for the projections whose one-launch form (above) is slower:
-// 128-column tiles, K cut into skinny_segments(N, K) segments (a function of the weight shape only),
-// fp32 partial sums [S, M, N] into `partials`; the caller follows with launch_partial_reduce.
+// The same with a K split, for the projections whose one-launch form is slower (33..64 rows against
+// a large weight): 128-column tiles, K cut into skinny_segments(N, K) segments (a function of the
+// weight shape only), fp32 partial sums [S, M, N] into `partials` and, with `norm`, the rows' sums of
+// squares per segment [S, M] into `ssq_partials`; the caller follows with launch_partial_reduce or
+// launch_qkv_partials_rope_decode.
 int skinny_segments(int N, int K);
 size_t skinny_partial_bytes(int M, int N, int K);
-hipError_t launch_gemm_skinny_main(const void *Wp, const void *Xp, float *partials, int M, int N,
-                                   int K, hipStream_t st);
+hipError_t launch_gemm_stream_partials(const void *Wp, const void *X, bool x_rows, bool norm, float *partials,
+                                       float *ssq_partials, int M, int N, int K, hipStream_t st);
+// Decode Q/K/V (head_dim 128) behind a K-split projection of raw rows: segment sums in segment order,
+// the RMSNorm scale rsqrt(sum_s ssq[s, m] / K + eps), rotary embedding at position lens[m], q store
+// and KV-cache append at slot lens[m].
+hipError_t launch_qkv_partials_rope_decode(const float *partials, const float *ssq_partials, int S, int M, int nq,
+                                           int nkv, int K, float eps, const void *tab, const int32_t *lens_dev,
+                                           void *qkv, void *k_cache, void *v_cache, int cap, hipStream_t st);
 // Fixed-order sum of S partial buffers (fp32 [S, M, N]) + epilogue; used by both GEMM variants.
 // EPI_STORE_RM: out_packed (may be null) receives a second, fragment-packed copy of the result.
 hipError_t launch_partial_reduce(const float *partials, int S, int epi, const void *res, void *out, void *out_packed,
@@ -97,7 +105,7 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, bool x_rows, int ep
 // stream and the kernel is also the RMSNorm in front of the projection (the weight already carries
 // the norm's gains): row m of the result is scaled by rsqrt(mean_k x[m, k]^2 + eps).  A row's
 // result depends on that row alone.
-enum { GS_STORE = 0, GS_SWIGLU = 1, GS_QKV_DECODE = 2 };
+enum { GS_STORE = 0, GS_SWIGLU = 1, GS_QKV_DECODE = 2, GS_PARTIALS = 3 };
 hipError_t init_gemm_stream_kernels();
 // Tile width (16-column blocks, one of 1, 2, 4, 8) of a store-type projection with N output columns.
 int stream_store_nb(int N);

@@ -87,7 +87,7 @@ struct WsPlan {
     // the residual stream after the attention block (weight-streaming path: the projections apply the
     // norm themselves); xa, xb: activations between layers of a run; xc, yc, offs: dense prefill
     // rows in / out and their per-sequence offsets
-    size_t h, qkv, a, x1, gu, u, xp, x1p, kp, vtp, xa, xb, xc, yc, offs, scratch, scratch_bytes, total;
+    size_t h, qkv, a, x1, gu, u, xp, x1p, kp, vtp, xa, xb, xc, yc, offs, ssqp, scratch, scratch_bytes, total;   // ssqp: per-segment sums of squares of a K-split projection
 };
 
 // A store-type projection (O, down, a single projection) of a batch of `variant_rows` <= 64 rows runs
@@ -95,6 +95,10 @@ struct WsPlan {
 // with a K split and a reduction kernel stream faster (measured on the 70B down projection: 80 us
 // against 102 us).  Decided from the weight shape and the FULL batch's row count.
 inline bool store_split(int K, long long variant_rows) { return variant_rows > 32 && K > 8192; }
+// The decode Q/K/V projection likewise: one launch over half-head tiles up to 32 rows; for 33..64 rows
+// whole-head tiles with a K split and a reduction kernel that also rotates and appends (measured on
+// the 70B shape: 41 us against 55 us).
+inline bool qkv_split(long long variant_rows) { return variant_rows > 32; }
 // A single projection of up to this many rows (of the FULL batch) reads the caller's row-major rows in
 // the LDS-tiled GEMM itself; larger batches are packed first.
 constexpr long long kDirectRowsMax = 512;
@@ -206,7 +210,9 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
             p.xb = take(rows * d.H * 2);
         }
         size_t s = 0;
+        p.ssqp = take((size_t)64 * ccs::kSkinnyMaxRows * sizeof(float));
         if (skinny) {   // partial sums of the projections that may take the K-split form
+            s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.W3, d.H));
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.QD));
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.I));
         } else {
@@ -482,8 +488,13 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             const void *xq = xp_ready ? (const void *)(ws + p.xp) : x_in;
             const bool xq_rows = !xp_ready;
             if (attn) {
+                if (decode && qkv_split(variant_rows)) {
+                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_partials(A + m->ap.qkv, xq, xq_rows, true, scratch, (float *)(ws + p.ssqp), T, d.W3, d.H, st));
+                    CCS_STAGE(CCS_ST_GEMM_QKV_REDUCE, launch_qkv_partials_rope_decode(scratch, (const float *)(ws + p.ssqp), skinny_segments(d.W3, d.H), T, d.nq, d.nkv, d.H, D.rms_eps, tab, b->lens_dev, ws + p.qkv, kc, vc, b->cache_cap, st));
+                }
                 if (decode) {
-                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_qkv_decode(A + m->ap.qkv, xq, xq_rows, D.rms_eps, ws + p.qkv, T, d.nq, d.nkv, d.H, tab, b->lens_dev, kc, vc, b->cache_cap, st));
+                    if (!qkv_split(variant_rows))
+                        CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_qkv_decode(A + m->ap.qkv, xq, xq_rows, D.rms_eps, ws + p.qkv, T, d.nq, d.nkv, d.H, tab, b->lens_dev, kc, vc, b->cache_cap, st));
                     CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
                     CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
                 } else {
@@ -498,7 +509,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
                 else CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, x_in, true, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
                 void *next_xp = last ? nullptr : (void *)(ws + p.xp);   // inside a run: the next layer's packed input rows
                 if (store_split(d.I, variant_rows)) {
-                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_skinny_main(A + m->ap.dn, ws + p.u, scratch, T, d.H, d.I, st));
+                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_partials(A + m->ap.dn, ws + p.u, false, false, scratch, nullptr, T, d.H, d.I, st));
                     CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_partial_reduce(scratch, skinny_segments(d.H, d.I), EPI_STORE_RM, x1_in, x_out, next_xp, T, d.H, st));
                 } else {
                     CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.dn, stream_store_nb(d.H), ws + p.u, false, false, 0.f, x1_in, x_out, next_xp, T, d.H, d.I, st));

@@ -385,6 +385,10 @@ __device__ __forceinline__ void dm_issue_v(const uint4 *__restrict__ vrow, int j
 
 // K rows go to registers with hand-issued loads and hand-placed waits: left to the compiler, the
 // wait for them lands behind the loads of the next block (it waits for everything outstanding).
+// The compiler does not know that these registers are still being written after the asm statement:
+// between a load and its dm_wait_all the register set must not be live across a control-flow join
+// that could make the compiler copy it (a chunk loop around the block loop did: the copies read
+// registers whose loads had not landed).  Keep the two register sets in ONE flat block loop.
 __device__ __forceinline__ void dm_load_k(const uint4 *__restrict__ krow, int jb, int j1, int c16, int g4,
                                           u32x4_t (&kf)[2][4])
 {
@@ -582,6 +586,123 @@ __global__ __launch_bounds__(256, 2) void attn_decode_mfma_kernel(
             *(float4 *)(p + 4 + dt * 16 + g4 * 4) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
     }
 }
+
+// ---------------------------------------------------------------------------------------------
+// The same with ONE workgroup per (sequence, kv head) and no second kernel, for modules with many
+// kv heads (multi-head attention: 16 kv heads or more, so that the (sequence, kv head) pairs alone
+// fill the GPU and are all about equally long per sequence).  Wavefront w of the workgroup takes
+// the 128-key chunks w, w + 4, w + 8, ... of the cache one after the other, carrying its running
+// maximum, sum and values across them (the online softmax does not care where a chunk ends); the
+// four wavefronts' results are then merged through LDS in wavefront order and the normalised
+// output goes out fragment-packed.  No partial sums in memory, no combine launch; the chunking and
+// the merge order depend only on the sequence's own length.
+// ---------------------------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(256, 2) void attn_decode_whole_kernel(
+    const bf16_t *__restrict__ qkv, bf16_t *__restrict__ out, int n_seqs, int nq, int nkv,
+    const int32_t *__restrict__ lens, const uint4 *__restrict__ kc, const uint4 *__restrict__ vc, int cap,
+    int chunk_keys)
+{
+    extern __shared__ uint4 lds[];   // 4 wavefronts x 2 stages x 8 KiB; reused for the merge
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b = blockIdx.x / nkv, kvh = blockIdx.x % nkv;
+    const int n_keys = cached_len(lens, b, cap) + 1;
+    const int nch = (n_keys + chunk_keys - 1) / chunk_keys;
+    const int width = (nq + 2 * nkv) * 128;
+    const int c16 = lane & 15, g4 = lane >> 4;
+    const float sc = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
+
+    u32x4_t qf[4];
+#pragma unroll
+    for (int dblk = 0; dblk < 4; ++dblk) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (c16 < G) v = *(const uint4 *)(qkv + (size_t)b * width + (size_t)(kvh * G + c16) * 128 + dblk * 32 + g4 * 8);
+        qf[dblk] = u32x4_t{v.x, v.y, v.z, v.w};
+    }
+    const uint4 *krow = kc + ((size_t)b * nkv + kvh) * cap * 16;   // 16 uint4 per cached row
+    const uint4 *vrow = vc + ((size_t)b * nkv + kvh) * cap * 16;
+    uint4 *stage0 = lds + wv * 1024, *stage1 = stage0 + 512;
+    uint32_t vaddr[8];
+    {
+        const int R = g4 * 4 + (c16 >> 2);
+        const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)stage0 + R * 256 +
+                              ((c16 >> 1) & 1) * 16 + (c16 & 1) * 8;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) vaddr[dt] = base + ((dt ^ (R & 7)) << 5);
+    }
+
+    float m_run = -INFINITY, l_run = 0.f;   // of head c16
+    f32x4_t o[8];                            // O^T: head c16, d = dt*16 + g4*4 + r
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // This wavefront's 32-key blocks, one stream: block i is block i % 4 of chunk wv + 4 (i / 4).  Only
+    // the sequence's last chunk can be short, so masking against n_keys is all the blocks need.  (One
+    // flat loop with the same shape as the per-chunk kernel's: the K registers and V stages that are
+    // in flight across the back edge are the same ones in every iteration.)
+    const int my_chunks = wv < nch ? (nch - wv + 3) / 4 : 0;
+    const int last_blocks = (n_keys - (nch - 1) * chunk_keys + 31) / 32;
+    const int my_blocks = my_chunks == 0 ? 0 : (((nch - 1) & 3) == wv ? (my_chunks - 1) * 4 + last_blocks : my_chunks * 4);
+    auto key0 = [&](int i) { return (wv + 4 * (i >> 2)) * chunk_keys + (i & 3) * 32; };
+    u32x4_t ka[2][4], kb2[2][4];
+    if (my_blocks > 0) {
+        dm_load_k(krow, key0(0), n_keys, c16, g4, ka);
+        dm_issue_v(vrow, key0(0), n_keys, lane, stage0);
+        dm_wait_all(ka);
+        for (int i = 0;; i += 2) {
+            const bool more1 = i + 1 < my_blocks;
+            if (more1) {
+                dm_load_k(krow, key0(i + 1), n_keys, c16, g4, kb2);
+                dm_issue_v(vrow, key0(i + 1), n_keys, lane, stage1);
+            }
+            dm_block<0>(ka, qf, vaddr, key0(i), n_keys, g4, sc, m_run, l_run, o);
+            if (!more1) break;
+            dm_wait_all(kb2);
+            const bool more2 = i + 2 < my_blocks;
+            if (more2) {
+                dm_load_k(krow, key0(i + 2), n_keys, c16, g4, ka);
+                dm_issue_v(vrow, key0(i + 2), n_keys, lane, stage0);
+            }
+            dm_block<1>(kb2, qf, vaddr, key0(i + 1), n_keys, g4, sc, m_run, l_run, o);
+            if (!more2) break;
+            dm_wait_all(ka);
+        }
+    }
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+
+    // merge the four wavefronts in wavefront order: part[w][head] = (max, sum, 128 values), kDecPart floats each
+    __syncthreads();   // every wavefront is done with its V stages
+    float *part = (float *)lds;
+    if (c16 < G) {
+        float *p = part + (wv * G + c16) * kDecPart;
+        if (g4 == 0) {
+            p[0] = m_run;
+            p[1] = l_run;
+        }
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+            *(float4 *)(p + 4 + dt * 16 + g4 * 4) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * 128; idx += 256) {
+        const int h = idx >> 7, c = idx & 127;
+        const float *p = part + h * kDecPart;
+        float M = p[0];                       // wavefront 0 always holds chunk 0, which has a key
+#pragma unroll
+        for (int w = 1; w < 4; ++w) M = fmaxf(M, p[w * G * kDecPart]);
+        float L = 0.f, a = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float *q = p + w * G * kDecPart;
+            const float wgt = fast_exp2(q[0] - M);   // a wavefront without a chunk has max -inf: weight 0
+            L = fmaf(q[1], wgt, L);
+            a = fmaf(q[4 + c], wgt, a);
+        }
+        out[packed_index(b, (kvh * G + h) * 128 + c, (nq * 128) >> 5)] = f2bf(a / L);
+    }
+}
 #undef DM_TR
 
 // Merge the chunk partials of one (sequence, head) in chunk order; thread c owns value c.
@@ -623,12 +744,32 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restri
     out[packed_index(b, h * 128 + c, (nq * 128) >> 5)] = f2bf(a / L);
 }
 
-hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs, int nq, int nkv,
+// One workgroup per (sequence, kv head) with the merge inside (no partial sums, no combine launch)
+// when the module has many kv heads; a property of the module's shape, never of the batch.
+bool attn_decode_is_whole(int nq, int nkv) { return nkv >= 16 && nq / nkv <= 8; }
+
+hipError_t launch_attn_decode_main(const void *qkv, float *partials, void *out_packed, int n_seqs, int nq, int nkv,
                                    const int32_t *lens_dev, const void *k_cache,
                                    const void *v_cache, int cap, hipStream_t st)
 {
     if (n_seqs <= 0) return hipSuccess;
     const int chunk_keys = dec_chunk_keys(nq, nkv), nchunks = dec_chunks(cap, chunk_keys), G = nq / nkv;
+    if (attn_decode_is_whole(nq, nkv)) {
+        dim3 wgrid((unsigned)n_seqs * nkv);
+#define CCS_WHOLE(GV)                                                                                      \
+    hipLaunchKernelGGL((attn_decode_whole_kernel<GV>), wgrid, dim3(256), 65536, st, (const bf16_t *)qkv,   \
+                       (bf16_t *)out_packed, n_seqs, nq, nkv, lens_dev, (const uint4 *)k_cache,            \
+                       (const uint4 *)v_cache, cap, chunk_keys)
+        switch (G) {
+            case 1: CCS_WHOLE(1); break;
+            case 2: CCS_WHOLE(2); break;
+            case 4: CCS_WHOLE(4); break;
+            case 8: CCS_WHOLE(8); break;
+            default: return hipErrorInvalidValue;
+        }
+#undef CCS_WHOLE
+        return hipGetLastError();
+    }
     const long units = (long)n_seqs * nkv * nchunks;
     dim3 grid((unsigned)((units + 3) / 4)), block(256);
 #define CCS_GQA(GV)                                                                                        \
@@ -668,6 +809,10 @@ hipError_t init_attention_kernels()
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<2>, (hipFuncAttribute)attr, 65536);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<4>, (hipFuncAttribute)attr, 65536);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_mfma_kernel<8>, (hipFuncAttribute)attr, 65536);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_whole_kernel<1>, (hipFuncAttribute)attr, 65536);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_whole_kernel<2>, (hipFuncAttribute)attr, 65536);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_whole_kernel<4>, (hipFuncAttribute)attr, 65536);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_decode_whole_kernel<8>, (hipFuncAttribute)attr, 65536);
     // the generic kernel keeps one score per key in LDS: allow it the whole 160 KiB here, so that no
     // forward (which a caller may be capturing into a graph) has to change a kernel attribute
     if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_generic_kernel<float>, (hipFuncAttribute)attr, 160 * 1024);

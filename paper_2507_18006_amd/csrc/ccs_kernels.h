@@ -139,9 +139,13 @@ hipError_t launch_attn_generic(int dtype, const void *qkv, void *out, int rows, 
 // launch_rope_pack_prefill; output fragment packed [rows16, nq*128] at the same dense rows.
 hipError_t launch_attn_prefill_mfma(const void *qkv, const void *kp, const void *vtp, void *out_packed,
                                     int n_seqs, int seq_pad, int nq, int nkv, const int32_t *offs, hipStream_t st);
-// bf16, head_dim 128 decode attention with split-KV partials (fp32) and an ordered combine.
+// bf16, head_dim 128 decode attention.  Modules with few kv heads (attn_decode_is_whole false): one
+// wavefront per (sequence, kv head, 128-key chunk) leaves fp32 partials and launch_attn_decode_combine
+// merges them in chunk order.  Modules with many kv heads: one workgroup per (sequence, kv head)
+// merges inside and writes out_packed itself; the combine launch is then skipped.
 size_t attn_decode_partial_bytes(int n_seqs, int nq, int cap);
-hipError_t launch_attn_decode_main(const void *qkv, float *partials, int n_seqs, int nq, int nkv,
+bool attn_decode_is_whole(int nq, int nkv);
+hipError_t launch_attn_decode_main(const void *qkv, float *partials, void *out_packed, int n_seqs, int nq, int nkv,
                                    const int32_t *lens_dev, const void *k_cache,
                                    const void *v_cache, int cap, hipStream_t st);
 hipError_t launch_attn_decode_combine(const float *partials, void *out_packed, int n_seqs, int nq, int nkv,

@@ -175,17 +175,17 @@ def test_bf16_long_sequences_prefill_and_decode():
     assert U.rel_err(y1, ref, mask) <= TOL["bf16"]
     assert np.array_equal(y1, y2)
 
-    dec = workloads.scaled(C["C4"], hidden=512, n_q_heads=8, n_kv_heads=2, intermediate=1408,
-                           n_seqs=3, len_lo=20000, len_hi=20000)
-    w = workloads.make_weights(dec, 22)
-    inp = workloads.make_inputs(dec, 22)
-    inp.lens[:] = [20000, 0, 100]
-    ref = U.oracle_forward(dec, 22, w, inp)
-    say("[case] decode lens=[20000, 0, 100]")
-    y1 = U.gpu_forward(dec, 1, 22, w, inp)
-    y3 = U.gpu_forward(dec, 3, 22, w, inp)
-    assert U.rel_err(y1, ref) <= TOL["bf16"]
-    assert np.array_equal(y1, y3)
+    for nq, nkv in ((8, 2), (16, 16)):     # wavefront-per-chunk and workgroup-per-(sequence, kv head) attention
+        dec = workloads.scaled(C["C4"], hidden=512, n_q_heads=nq, n_kv_heads=nkv, intermediate=1408,
+                               n_seqs=3, len_lo=20000, len_hi=20000)
+        w = workloads.make_weights(dec, 22)
+        inp = workloads.make_inputs(dec, 22, lens=[20000, 0, 100])
+        ref = U.oracle_forward(dec, 22, w, inp)
+        say(f"[case] decode lens=[20000, 0, 100] heads {nq}/{nkv}")
+        y1 = U.gpu_forward(dec, 1, 22, w, inp)
+        y3 = U.gpu_forward(dec, 3, 22, w, inp)
+        assert U.rel_err(y1, ref) <= TOL["bf16"]
+        assert np.array_equal(y1, y3)
 
 
 def test_bf16_seeded_random_shapes():
@@ -244,15 +244,17 @@ def test_bf16_weight_block_groups_with_padding():
 
 
 # ---------------------------------------------------------------- branch-dominated outputs: the MFMA kernels pinned
-DECODE_EDGE_LENS = [0, 1, 127, 128, 129, 1024, 2048]      # around the 128-key chunks of the decode attention
+DECODE_EDGE_LENS = [0, 1, 127, 128, 129, 383, 511, 512, 1024, 2048]      # around the 128-key chunks of the decode attention and groups of four of them
 PREFILL_EDGE_LENS = [1, 31, 32, 33, 64, 75, 127, 128, 129, 200]   # around its 32-key blocks and 128-query blocks
 
 
-@pytest.mark.parametrize("g,nkv", [(1, 8), (2, 4), (4, 2), (8, 2)])
+@pytest.mark.parametrize("g,nkv", [(1, 8), (2, 4), (4, 2), (8, 2), (1, 16), (2, 16)])
 def test_bf16_decode_attention_pinned_by_branch_dominated_outputs(g, nkv):
     """Attention block and whole layer, multi-head and grouped-query, cached lengths on the chunk
     edges; once with unit-variance keys (flat attention weights) and once with keys of standard
-    deviation 4 (a few keys carry the weight: a dropped or misplaced key shows)."""
+    deviation 4 (a few keys carry the weight: a dropped or misplaced key shows).  16 kv heads take
+    the decode attention with one workgroup per (sequence, kv head) and the merge inside, fewer the
+    one with a wavefront per chunk and the combine kernel."""
     for kind in ("attn_block", "decoder_layer"):
         cfg = workloads.scaled(C["C4"], kind=kind, hidden=1024, n_q_heads=g * nkv, n_kv_heads=nkv, intermediate=2752,
                                n_seqs=len(DECODE_EDGE_LENS), len_lo=0, len_hi=2048)

@@ -259,7 +259,8 @@ def bench_layer(args, name, sub=False):
 
     traffic, traffic_file = measured_traffic(name)
     if decode:
-        roof = {"kernel": "attn_decode_mfma_kernel", "bound": "hbm",
+        roof = {"kernel": "attn_decode_whole_kernel (one workgroup per sequence and kv head, merge inside)" if nkv >= 16
+                else "attn_decode_mfma_kernel (one wavefront per 128-key chunk; + attn_combine_kernel, not included)", "bound": "hbm",
                 "achieved": round(kv_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(kv_bytes / dom_s / 1e9 / HBM_PEAK_GBPS, 4),
                 "traffic": traffic, "traffic_source": traffic_file,

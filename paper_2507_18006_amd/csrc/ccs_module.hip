@@ -483,7 +483,8 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
             // Weight-streaming path (at most 64 rows in the full batch): every projection is one launch
             // that also applies the RMSNorm in front of it (the gains are folded into the weights) and
             // whatever follows it - rotary embedding and cache append, residual, SwiGLU - so a decode
-            // step is six launches per layer.
+            // step is five launches per layer when the attention kernel merges its own chunks (six
+            // with the combine launch, up to eight when Q/K/V and down split K over workgroups).
             // x of the first projection: the packed copy the previous layer of a run left, else the rows themselves
             const void *xq = xp_ready ? (const void *)(ws + p.xp) : x_in;
             const bool xq_rows = !xp_ready;

@@ -340,7 +340,7 @@ def test_attention_block_and_ffn_block_modules():
     oracle, split bit-exactly, and chained on the GPU they reproduce the whole-layer module."""
     shape = dict(hidden=1024, n_q_heads=8, n_kv_heads=4, intermediate=2752)
     dec = workloads.scaled(C["C2"], kind="attn_block", n_seqs=13, len_lo=20, len_hi=300, **shape)
-    run_case(dec, [1, 2, 4], seed=80)
+    run_case(dec, [1, 2, 4, 8], seed=80)     # 8 replica streams: more than the 4 hardware queues of a process
     pre = workloads.scaled(C["C3"], kind="attn_block", n_seqs=3, seq_pad=70, len_lo=9, len_hi=70, **shape)
     run_case(pre, [1, 2], seed=81)
     for n in (13, 200):      # weight-streaming and LDS-tiled GEMMs

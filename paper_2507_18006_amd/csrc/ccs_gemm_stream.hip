@@ -74,15 +74,16 @@ struct GsArgs {
     int cap;
 };
 
+// One tile of a launch: the NB 16-column blocks blk0 .. blk0 + NB - 1 of the weight (GS_QKV_DECODE:
+// the blocks that `tile` names, see below) over K segment `seg`, from the first load to the last store.
 template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS>
-__global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 : 1) void gemm_stream_kernel(const GsArgs a)
+__device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int blk0, const int tile, const int seg)
 {
-    extern __shared__ float red[];
     constexpr int ROWF = NB * 16 + 4;      // floats per padded LDS row: conflict-free 16-byte accesses
     constexpr int BUF = MB * 16 * ROWF;    // floats per reduction buffer
+    constexpr bool QKV3 = EPI == GS_QKV_DECODE && NB == 3;   // one rotary pair of blocks of a q or k head + one block of a v head
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x % a.ntiles, seg = blockIdx.x / a.ntiles;
     const int kfrags = a.kfrags, G = a.G;
     const int seg_lo = seg * a.kf_seg, seg_hi = min(kfrags, seg_lo + a.kf_seg);
     const int per_wave = (seg_hi - seg_lo + kGsWaves - 1) / kGsWaves;
@@ -90,15 +91,17 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     const int kb_hi = min(seg_hi, kb_lo + per_wave);
 
     // 16-row weight blocks of this tile
-    constexpr int HH = NB >= 2 ? NB / 2 : 1;   // GS_QKV_DECODE: blocks per half of the head
-    constexpr int PARTS = NB >= 8 ? 1 : 8 / NB;
+    constexpr int HH = QKV3 ? 1 : NB >= 2 ? NB / 2 : 1;   // GS_QKV_DECODE: blocks per half of the head
+    constexpr int PARTS = QKV3 ? 4 : NB >= 8 ? 1 : 8 / NB;
     const int hs = tile / PARTS, part = tile % PARTS;   // head slot and part of the head (GS_QKV_DECODE)
+    const int last_blk = (a.N >> 4) - 1;               // blocks past the weight repeat the last one; never stored
     const uint4 *wp[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         int nb;
-        if (EPI == GS_QKV_DECODE) nb = hs * 8 + (j / HH) * 4 + part * HH + (j % HH);
-        else nb = tile * NB + j;
+        if (QKV3) nb = j < 2 ? hs * 8 + j * 4 + part : (a.nq + a.nkv) * 8 + tile;
+        else if (EPI == GS_QKV_DECODE) nb = hs * 8 + (j / HH) * 4 + part * HH + (j % HH);
+        else nb = min(blk0 + j, last_blk);
         wp[j] = a.Wp + (((size_t)(nb / G) * kfrags) * G + (nb % G)) * 64 + lane;
     }
     const size_t wstep = (size_t)G * 64;   // uint4 from one k-step of a block to the next
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
 #pragma unroll
         for (int w = 1; w < kGsWaves; ++w) tot += wssq[w * (MB * 16) + m];
         rsv[m] = (norm && EPI != GS_PARTIALS) ? 1.0f / sqrtf(tot / (float)(kfrags * 32) + a.eps) : 1.0f;
-        if (EPI == GS_PARTIALS && a.ssq_part && tile == 0 && m < a.M) a.ssq_part[seg * a.M + m] = tot;
+        if (EPI == GS_PARTIALS && a.ssq_part && blk0 == 0 && m < a.M) a.ssq_part[seg * a.M + m] = tot;
     }
     __syncthreads();
     // value of the tile at (row m, column c of NB * 16), scaled by the row's norm factor
@@ -238,13 +241,13 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     if (EPI == GS_PARTIALS) {
         for (int q = threadIdx.x; q < QUADS; q += kGsWaves * 64) {
             const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
-            const int n = tile * (NB * 16) + c;
+            const int n = blk0 * 16 + c;
             if (m < a.M && n < a.N) *(float4 *)(a.part + ((size_t)seg * a.M + m) * a.N + n) = fetch(m, c);
         }
     } else if (EPI == GS_STORE) {
         for (int q = threadIdx.x; q < QUADS; q += kGsWaves * 64) {
             const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
-            const int n = tile * (NB * 16) + c;
+            const int n = blk0 * 16 + c;
             if (m >= a.M || n >= a.N) continue;
             float4 v = fetch(m, c);
             if (a.res) {
@@ -258,12 +261,42 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     } else if (EPI == GS_SWIGLU) {   // the tile's blocks are (gate, up) pairs: NB / 2 blocks of u
         for (int q = threadIdx.x; q < QUADS / 2; q += kGsWaves * 64) {
             const int m = q / (NB * 2), pr = (q % (NB * 2)) / 4, c4 = (q % 4) * 4;
-            const int col = (tile * (NB / 2) + pr) * 16 + c4;   // column of u
+            const int col = (blk0 / 2 + pr) * 16 + c4;   // column of u
             if (m >= a.M || col >= a.N / 2) continue;
             const float4 g = fetch(m, pr * 32 + c4), u = fetch(m, pr * 32 + 16 + c4);
             const float o0 = g.x / (1.0f + __expf(-g.x)) * u.x, o1 = g.y / (1.0f + __expf(-g.y)) * u.y;
             const float o2 = g.z / (1.0f + __expf(-g.z)) * u.z, o3 = g.w / (1.0f + __expf(-g.w)) * u.w;
             *(uint2 *)(a.out + packed_index(m, col, (a.N / 2) >> 5)) = make_uint2(pack2bf(o0, o1), pack2bf(o2, o3));
+        }
+    } else if (QKV3) {   // columns [0, 16): dims d0 + c of a q or k head, [16, 32): their rotary partners 64 up, [32, 48): 16 dims of a v head
+        const int width = (a.nq + 2 * a.nkv) * 128;
+        const int d0 = part * 16;
+        for (int q = threadIdx.x; q < MB * 16 * 8; q += kGsWaves * 64) {
+            const int m = q >> 3, e4 = q & 7;
+            if (m >= a.M) continue;
+            const int pos = cached_len(a.lens, m, a.cap);
+            if (e4 < 4) {   // the rotary pair
+                const int c = e4 * 4;
+                const float4 lo4 = fetch(m, c), hi4 = fetch(m, c + 16);
+                float l[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, h[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float cs, sn;
+                    rope_cs(a.tab, d0 + c + e, pos, cs, sn);
+                    const float x0v = l[e], x1v = h[e];
+                    l[e] = x0v * cs - x1v * sn;
+                    h[e] = x1v * cs + x0v * sn;
+                }
+                bf16_t *dst = hs < a.nq ? a.out + (size_t)m * width + hs * 128 + d0 + c
+                                        : a.kc + (((size_t)m * a.nkv + (hs - a.nq)) * a.cap + pos) * 128 + d0 + c;
+                *(uint2 *)dst = make_uint2(pack2bf(l[0], l[1]), pack2bf(l[2], l[3]));
+                *(uint2 *)(dst + 64) = make_uint2(pack2bf(h[0], h[1]), pack2bf(h[2], h[3]));
+            } else {        // the v block: block tile % 8 of v head tile / 8
+                const int c = (e4 - 4) * 4;
+                const float4 v = fetch(m, 32 + c);
+                bf16_t *dst = a.vc + (((size_t)m * a.nkv + (tile >> 3)) * a.cap + pos) * 128 + (tile & 7) * 16 + c;
+                *(uint2 *)dst = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
+            }
         }
     } else {   // GS_QKV_DECODE: columns [0, NB * 8) are dims d0 + c, columns [NB * 8, NB * 16) their rotary partners 64 up
         const int width = (a.nq + 2 * a.nkv) * 128;
@@ -297,47 +330,70 @@ __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 
     }
 }
 
+// The kernel: workgroup b works on column tile b % ntiles and K segment b / ntiles.  With NB2 > 0 a
+// tile is NB + NB2 blocks wide and is done in two passes (NB blocks, then NB2), which lets a launch
+// give every compute unit the same number of blocks when that number is too large for one pass's registers.
+template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int NB2>
+__global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 : 1) void gemm_stream_kernel(const GsArgs a)
+{
+    extern __shared__ float red[];
+    const int tile = blockIdx.x % a.ntiles, seg = blockIdx.x / a.ntiles;
+    gs_pass<MB, NB, EPI, kGsWaves, U, XROWS>(a, red, tile * (NB + NB2), tile, seg);
+    if (NB2 > 0) {
+        constexpr int NBB = NB2 > 0 ? NB2 : 1;
+        if ((tile * (NB + NB2) + NB) * 16 < a.N) {   // the same for the whole workgroup
+            __syncthreads();
+            gs_pass<MB, NBB, EPI, kGsWaves, gs_u(MB, NBB), XROWS>(a, red, tile * (NB + NB2) + NB, tile, seg);
+        }
+    }
+}
+
 constexpr int gs_lds_bytes(int MB, int NB, int W, int U, int XROWS)
 {
     return gs_red_floats(MB, NB, W) * (int)sizeof(float) + (XROWS ? W * U * MB * 1024 : 0);
 }
+constexpr int gs_lds_bytes2(int MB, int NB, int NB2, int W, int XROWS)
+{
+    const int a = gs_lds_bytes(MB, NB, W, gs_u(MB, NB), XROWS);
+    const int b = NB2 > 0 ? gs_lds_bytes(MB, NB2, W, gs_u(MB, NB2), XROWS) : 0;
+    return a > b ? a : b;
+}
 
-// wavefronts per workgroup of each instantiation (eight were measured: never faster)
-constexpr int gs_waves(int MB, int NB) { return 4; }
+// wavefronts per workgroup of every instantiation (eight were measured: never faster)
+constexpr int kGsW = 4;
 
-template <int MB, int NB, int EPI, int XROWS>
+template <int MB, int NB, int EPI, int XROWS, int NB2 = 0>
 hipError_t gs_launch(int tiles, const GsArgs &a, hipStream_t st)
 {
-    constexpr int W = gs_waves(MB, NB), U = gs_u(MB, NB);
-    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, W, U, XROWS>), dim3(tiles), dim3(W * 64), gs_lds_bytes(MB, NB, W, U, XROWS), st, a);
+    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2>), dim3(tiles), dim3(kGsW * 64),
+                       gs_lds_bytes2(MB, NB, NB2, kGsW, XROWS), st, a);
     return hipGetLastError();
 }
 
-template <int NB, int EPI, int XROWS>
+template <int NB, int EPI, int XROWS, int NB2 = 0>
 hipError_t gs_launch_mb(int tiles, const GsArgs &a, hipStream_t st)
 {
     const int mb = (a.M + 15) / 16;
-    if (mb <= 1) return gs_launch<1, NB, EPI, XROWS>(tiles, a, st);
-    if (mb == 2) return gs_launch<2, NB, EPI, XROWS>(tiles, a, st);
-    return gs_launch<4, NB, EPI, XROWS>(tiles, a, st);
+    if (mb <= 1) return gs_launch<1, NB, EPI, XROWS, NB2>(tiles, a, st);
+    if (mb == 2) return gs_launch<2, NB, EPI, XROWS, NB2>(tiles, a, st);
+    return gs_launch<4, NB, EPI, XROWS, NB2>(tiles, a, st);
 }
 
-template <int MB, int NB, int EPI, int XROWS>
+template <int MB, int NB, int EPI, int XROWS, int NB2>
 hipError_t gs_attr()
 {
-    constexpr int W = gs_waves(MB, NB), U = gs_u(MB, NB);
-    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, W, U, XROWS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               gs_lds_bytes(MB, NB, W, U, XROWS));
+    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, gs_lds_bytes2(MB, NB, NB2, kGsW, XROWS));
 }
-template <int NB, int EPI>
+template <int NB, int EPI, int NB2 = 0>
 hipError_t gs_attr_mb()
 {
-    hipError_t e = gs_attr<1, NB, EPI, 0>();
-    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 0>();
-    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 0>();
-    if (e == hipSuccess) e = gs_attr<1, NB, EPI, 1>();
-    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 1>();
-    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 1>();
+    hipError_t e = gs_attr<1, NB, EPI, 0, NB2>();
+    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 0, NB2>();
+    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 0, NB2>();
+    if (e == hipSuccess) e = gs_attr<1, NB, EPI, 1, NB2>();
+    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 1, NB2>();
+    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 1, NB2>();
     return e;
 }
 
@@ -353,9 +409,34 @@ int stream_store_nb(int N)
         if (nblk / nb >= 192) return nb;
     return 1;
 }
-// The Q/K/V projection works on heads (8 blocks): whole heads, or half heads when that is needed to
-// fill the GPU.
-int stream_qkv_nb(int heads) { return heads >= 192 ? 8 : 4; }
+// Blocks a compute unit ends up with when `tiles` tiles of `nb` blocks are dealt to 256 of them.
+static int blocks_per_cu(int tiles, int nb) { return ((tiles + 255) / 256) * nb; }
+
+// The decode Q/K/V projection works on whole rotary pairs: whole heads (8 blocks), half heads (4), or -
+// when there are as many q + k rotary pairs of blocks as v blocks, i.e. n_q == n_kv - one pair with one
+// v block (3).  The choice that leaves the fewest blocks on the busiest compute unit wins, the wider
+// tile on a tie (a 32-head module: 256 tiles of 3 blocks instead of 192 of 4).
+static int stream_qkv_nb(int nq, int nkv)
+{
+    const int heads = nq + 2 * nkv;
+    int best = 8, cost = blocks_per_cu(heads, 8);
+    if (blocks_per_cu(heads * 2, 4) < cost) { best = 4; cost = blocks_per_cu(heads * 2, 4); }
+    if (nq == nkv && blocks_per_cu(nkv * 8, 3) < cost) best = 3;
+    return best;
+}
+
+// Gate/up: (gate, up) pairs of blocks per workgroup so that 256 workgroups cover the weight; up to 4
+// pairs are one pass, 5 and 7 are two passes (6 + 4, 8 + 6 blocks), anything else tiles of 3 or 4 pairs.
+static void stream_gu_shape(int N2, int *nb1, int *nb2)
+{
+    const int pairs = N2 / 32, c = (pairs + 255) / 256;
+    *nb2 = 0;
+    if (c <= 4) *nb1 = 2 * c;
+    else if (c == 5) { *nb1 = 6; *nb2 = 4; }
+    else if (c == 6) *nb1 = 6;
+    else if (c == 7) { *nb1 = 8; *nb2 = 6; }
+    else *nb1 = 8;
+}
 
 hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *X, bool x_rows, bool norm, float eps,
                                     const void *res, void *out, void *out_packed, int M, int N, int K, hipStream_t st)
@@ -386,9 +467,20 @@ hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *X, bool x_rows,
     GsArgs a{};
     a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = 1; a.eps = eps;
     a.M = M; a.N = N2; a.out = (bf16_t *)u_packed;
-    const int tiles = ((N2 / 16) + 7) / 8;
+    int nb1, nb2;
+    stream_gu_shape(N2, &nb1, &nb2);
+    const int tiles = ((N2 / 16) + nb1 + nb2 - 1) / (nb1 + nb2);
     a.ntiles = tiles; a.kf_seg = a.kfrags;
-    return x_rows ? gs_launch_mb<8, GS_SWIGLU, 1>(tiles, a, st) : gs_launch_mb<8, GS_SWIGLU, 0>(tiles, a, st);
+#define CCS_GS(NB1, NB2) (x_rows ? gs_launch_mb<NB1, GS_SWIGLU, 1, NB2>(tiles, a, st) : gs_launch_mb<NB1, GS_SWIGLU, 0, NB2>(tiles, a, st))
+    if (nb2 == 4) return CCS_GS(6, 4);
+    if (nb2 == 6) return CCS_GS(8, 6);
+    switch (nb1) {
+        case 2: return CCS_GS(2, 0);
+        case 4: return CCS_GS(4, 0);
+        case 6: return CCS_GS(6, 0);
+        default: return CCS_GS(8, 0);
+    }
+#undef CCS_GS
 }
 
 hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *X, bool x_rows, float eps, void *qkv, int M, int nq,
@@ -404,10 +496,13 @@ hipError_t launch_gemm_stream_qkv_decode(const void *Wp, const void *X, bool x_r
     a.cap = cap;
     const int heads = nq + 2 * nkv;
     a.kf_seg = a.kfrags;
-    a.ntiles = stream_qkv_nb(heads) == 8 ? heads : heads * 2;
-    if (stream_qkv_nb(heads) == 8)
-        return x_rows ? gs_launch_mb<8, GS_QKV_DECODE, 1>(heads, a, st) : gs_launch_mb<8, GS_QKV_DECODE, 0>(heads, a, st);
-    return x_rows ? gs_launch_mb<4, GS_QKV_DECODE, 1>(heads * 2, a, st) : gs_launch_mb<4, GS_QKV_DECODE, 0>(heads * 2, a, st);
+#define CCS_GS(NBV) (x_rows ? gs_launch_mb<NBV, GS_QKV_DECODE, 1>(a.ntiles, a, st) : gs_launch_mb<NBV, GS_QKV_DECODE, 0>(a.ntiles, a, st))
+    switch (stream_qkv_nb(nq, nkv)) {
+        case 8: a.ntiles = heads; return CCS_GS(8);
+        case 4: a.ntiles = heads * 2; return CCS_GS(4);
+        default: a.ntiles = nkv * 8; return CCS_GS(3);
+    }
+#undef CCS_GS
 }
 
 // K segments of the GS_PARTIALS form for a [N, K] weight: from the weight shape alone.  Measured sweeps
@@ -451,10 +546,16 @@ hipError_t init_gemm_stream_kernels()
     if (e == hipSuccess) e = gs_attr_mb<2, GS_STORE>();
     if (e == hipSuccess) e = gs_attr_mb<4, GS_STORE>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_STORE>();
+    if (e == hipSuccess) e = gs_attr_mb<2, GS_SWIGLU>();
+    if (e == hipSuccess) e = gs_attr_mb<4, GS_SWIGLU>();
+    if (e == hipSuccess) e = gs_attr_mb<6, GS_SWIGLU>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_SWIGLU>();
+    if (e == hipSuccess) e = gs_attr_mb<6, GS_SWIGLU, 4>();
+    if (e == hipSuccess) e = gs_attr_mb<8, GS_SWIGLU, 6>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_PARTIALS>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_QKV_DECODE>();
     if (e == hipSuccess) e = gs_attr_mb<4, GS_QKV_DECODE>();
+    if (e == hipSuccess) e = gs_attr_mb<3, GS_QKV_DECODE>();
     return e;
 }
 

@@ -48,7 +48,7 @@ __device__ __forceinline__ f32x4_t gs_mfma(const uint4 &a, const uint4 &b, f32x4
 constexpr int gs_u(int MB, int NB) { return (NB + MB) <= 3 ? 6 : (NB + MB) <= 6 ? 4 : 2; }
 
 // floats of LDS the reduction and the row statistics take: W / 2 tile buffers, per-wavefront sums of squares, scales
-constexpr int gs_red_floats(int MB, int NB, int W) { return (W / 2) * MB * 16 * (NB * 16 + 4) + W * MB * 16 + MB * 16; }
+constexpr int gs_red_floats(int MB, int NB, int W) { return (W / 2) * MB * 16 * (NB * 16 + 4) + W * MB * 16 + MB * 16 + 4; }
 
 struct GsArgs {
     const uint4 *Wp;      // grouped fragment-packed weight
@@ -66,6 +66,9 @@ struct GsArgs {
     int kf_seg;           // k-steps per segment
     float *part;          // fp32 partial sums [S, M, N]
     float *ssq_part;      // optional: the rows' sums of squares per segment [S, M]
+    // SPLIT: K cut over nseg workgroups per tile, summed by the workgroup of a tile that finishes last
+    int nseg;
+    int *cnt;             // one arrival counter per tile; zero between launches
     // GS_QKV_DECODE
     int nq, nkv;
     const float2 *tab;
@@ -76,7 +79,7 @@ struct GsArgs {
 
 // One tile of a launch: the NB 16-column blocks blk0 .. blk0 + NB - 1 of the weight (GS_QKV_DECODE:
 // the blocks that `tile` names, see below) over K segment `seg`, from the first load to the last store.
-template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS>
+template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int SPLIT>
 __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int blk0, const int tile, const int seg)
 {
     constexpr int ROWF = NB * 16 + 4;      // floats per padded LDS row: conflict-free 16-byte accesses
@@ -223,13 +226,89 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
         for (int w = 1; w < kGsWaves; ++w) tot += wssq[w * (MB * 16) + m];
         rsv[m] = (norm && EPI != GS_PARTIALS) ? 1.0f / sqrtf(tot / (float)(kfrags * 32) + a.eps) : 1.0f;
         if (EPI == GS_PARTIALS && a.ssq_part && blk0 == 0 && m < a.M) a.ssq_part[seg * a.M + m] = tot;
+        if (SPLIT) rsv[m] = tot;   // this segment's part of the sum of squares, published below
     }
     __syncthreads();
+    constexpr int QUADS = MB * 16 * (NB * 4);   // float4 outputs of the tile
+    constexpr int NBUF = SPLIT ? 1 : HALF;      // buffers `fetch` adds
+    if (SPLIT) {
+        // K is cut over a.nseg workgroups per tile.  Every workgroup publishes its partial tile and
+        // its part of the rows' sums of squares with device-coherent (write-through) stores, waits
+        // until they are performed, and bumps the tile's arrival counter; the workgroup that finds
+        // nseg - 1 earlier arrivals reads all partial tiles back with device-coherent loads, adds
+        // them in SEGMENT order (its own included, so the sum does not depend on who came last) and
+        // runs the epilogue.  Nobody waits for anybody: there is no spinning.
+        constexpr int TILEF = MB * 16 * NB * 16;
+        constexpr int NT = kGsWaves * 64, QPT = (QUADS + NT - 1) / NT;
+        const int nseg = a.nseg;   // 2 .. 4
+        f32x4_t *mine = (f32x4_t *)(a.part + ((size_t)seg * a.ntiles + tile) * TILEF);
+        for (int q = threadIdx.x; q < QUADS; q += NT) {
+            const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
+            float4 v = *(const float4 *)(red + m * ROWF + c);
+#pragma unroll
+            for (int w = 1; w < HALF; ++w) {
+                const float4 t = *(const float4 *)(red + w * BUF + m * ROWF + c);
+                v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            }
+            const f32x4_t vv = {v.x, v.y, v.z, v.w};
+            asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(mine + q), "v"(vv) : "memory");
+        }
+        float *ssq_all = a.ssq_part + (size_t)tile * 4 * 64;   // [segment][row] of this tile
+        if (norm && threadIdx.x < MB * 16)
+            asm volatile("global_store_dword %0, %1, off sc1" ::"v"(ssq_all + seg * 64 + threadIdx.x), "v"(rsv[threadIdx.x]) : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the stores above are performed device-wide
+        __syncthreads();
+        int *arrived = (int *)(rsv + MB * 16);
+        if (threadIdx.x == 0) *arrived = __hip_atomic_fetch_add(a.cnt + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*arrived != nseg - 1) return;   // the same for the whole workgroup
+        // All loads are issued before the one wait (straight-line code: a register with a load in
+        // flight must not reach a control-flow join, where the compiler may copy it).  Segments past
+        // nseg repeat the last one and are not added.
+        f32x4_t r[QPT][4];
+#pragma unroll
+        for (int t = 0; t < QPT; ++t) {
+            const int q = min((int)threadIdx.x + t * NT, QUADS - 1);
+#pragma unroll
+            for (int sg = 0; sg < 4; ++sg) {
+                const f32x4_t *src = (const f32x4_t *)(a.part + ((size_t)min(sg, nseg - 1) * a.ntiles + tile) * TILEF) + q;
+                asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(r[t][sg]) : "v"(src) : "memory");
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < QPT; ++t)
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[t][0]), "+v"(r[t][1]), "+v"(r[t][2]), "+v"(r[t][3])::"memory");
+#pragma unroll
+        for (int t = 0; t < QPT; ++t) {
+            const int q = threadIdx.x + t * NT;
+            f32x4_t v = r[t][0] + r[t][1];
+            if (nseg > 2) v += r[t][2];
+            if (nseg > 3) v += r[t][3];
+            if (q < QUADS) *(float4 *)(red + (q / (NB * 4)) * ROWF + (q % (NB * 4)) * 4) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+        if (norm) {   // the rows' sums of squares, the same way (one more round trip; only projections with the norm in front)
+            float sv[4];
+#pragma unroll
+            for (int sg = 0; sg < 4; ++sg) {
+                const float *sp = ssq_all + min(sg, nseg - 1) * 64 + (threadIdx.x & 63);
+                asm volatile("global_load_dword %0, %1, off sc1" : "=v"(sv[sg]) : "v"(sp) : "memory");
+            }
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(sv[0]), "+v"(sv[1]), "+v"(sv[2]), "+v"(sv[3])::"memory");
+            float tot = sv[0] + sv[1];
+            if (nseg > 2) tot += sv[2];
+            if (nseg > 3) tot += sv[3];
+            if (threadIdx.x < MB * 16) rsv[threadIdx.x] = 1.0f / sqrtf(tot / (float)(kfrags * 32) + a.eps);
+        } else if (threadIdx.x < MB * 16) {
+            rsv[threadIdx.x] = 1.0f;
+        }
+        if (threadIdx.x == 0) __hip_atomic_store(a.cnt + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+        __syncthreads();
+    }
     // value of the tile at (row m, column c of NB * 16), scaled by the row's norm factor
     auto fetch = [&](int m, int c) -> float4 {
         float4 v = *(const float4 *)(red + m * ROWF + c);
 #pragma unroll
-        for (int w = 1; w < HALF; ++w) {
+        for (int w = 1; w < NBUF; ++w) {
             const float4 t = *(const float4 *)(red + w * BUF + m * ROWF + c);
             v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
         }
@@ -237,7 +316,6 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
         v.x *= r; v.y *= r; v.z *= r; v.w *= r;
         return v;
     };
-    constexpr int QUADS = MB * 16 * (NB * 4);   // float4 outputs of the tile
     if (EPI == GS_PARTIALS) {
         for (int q = threadIdx.x; q < QUADS; q += kGsWaves * 64) {
             const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
@@ -333,17 +411,17 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
 // The kernel: workgroup b works on column tile b % ntiles and K segment b / ntiles.  With NB2 > 0 a
 // tile is NB + NB2 blocks wide and is done in two passes (NB blocks, then NB2), which lets a launch
 // give every compute unit the same number of blocks when that number is too large for one pass's registers.
-template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int NB2>
+template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int NB2, int SPLIT>
 __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 : 1) void gemm_stream_kernel(const GsArgs a)
 {
     extern __shared__ float red[];
     const int tile = blockIdx.x % a.ntiles, seg = blockIdx.x / a.ntiles;
-    gs_pass<MB, NB, EPI, kGsWaves, U, XROWS>(a, red, tile * (NB + NB2), tile, seg);
+    gs_pass<MB, NB, EPI, kGsWaves, U, XROWS, SPLIT>(a, red, tile * (NB + NB2), tile, seg);
     if (NB2 > 0) {
         constexpr int NBB = NB2 > 0 ? NB2 : 1;
         if ((tile * (NB + NB2) + NB) * 16 < a.N) {   // the same for the whole workgroup
             __syncthreads();
-            gs_pass<MB, NBB, EPI, kGsWaves, gs_u(MB, NBB), XROWS>(a, red, tile * (NB + NB2) + NB, tile, seg);
+            gs_pass<MB, NBB, EPI, kGsWaves, gs_u(MB, NBB), XROWS, 0>(a, red, tile * (NB + NB2) + NB, tile, seg);
         }
     }
 }
@@ -362,53 +440,81 @@ constexpr int gs_lds_bytes2(int MB, int NB, int NB2, int W, int XROWS)
 // wavefronts per workgroup of every instantiation (eight were measured: never faster)
 constexpr int kGsW = 4;
 
-template <int MB, int NB, int EPI, int XROWS, int NB2 = 0>
-hipError_t gs_launch(int tiles, const GsArgs &a, hipStream_t st)
+template <int MB, int NB, int EPI, int XROWS, int NB2 = 0, int SPLIT = 0>
+hipError_t gs_launch(int grid, const GsArgs &a, hipStream_t st)
 {
-    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2>), dim3(tiles), dim3(kGsW * 64),
+    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2, SPLIT>), dim3(grid), dim3(kGsW * 64),
                        gs_lds_bytes2(MB, NB, NB2, kGsW, XROWS), st, a);
     return hipGetLastError();
 }
 
-template <int NB, int EPI, int XROWS, int NB2 = 0>
-hipError_t gs_launch_mb(int tiles, const GsArgs &a, hipStream_t st)
+template <int NB, int EPI, int XROWS, int NB2 = 0, int SPLIT = 0>
+hipError_t gs_launch_mb(int grid, const GsArgs &a, hipStream_t st)
 {
     const int mb = (a.M + 15) / 16;
-    if (mb <= 1) return gs_launch<1, NB, EPI, XROWS, NB2>(tiles, a, st);
-    if (mb == 2) return gs_launch<2, NB, EPI, XROWS, NB2>(tiles, a, st);
-    return gs_launch<4, NB, EPI, XROWS, NB2>(tiles, a, st);
+    if (mb <= 1) return gs_launch<1, NB, EPI, XROWS, NB2, SPLIT>(grid, a, st);
+    if (mb == 2) return gs_launch<2, NB, EPI, XROWS, NB2, SPLIT>(grid, a, st);
+    return gs_launch<4, NB, EPI, XROWS, NB2, SPLIT>(grid, a, st);
 }
 
-template <int MB, int NB, int EPI, int XROWS, int NB2>
+template <int MB, int NB, int EPI, int XROWS, int NB2, int SPLIT>
 hipError_t gs_attr()
 {
-    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2>,
+    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2, SPLIT>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, gs_lds_bytes2(MB, NB, NB2, kGsW, XROWS));
 }
-template <int NB, int EPI, int NB2 = 0>
+template <int NB, int EPI, int NB2 = 0, int SPLIT = 0>
 hipError_t gs_attr_mb()
 {
-    hipError_t e = gs_attr<1, NB, EPI, 0, NB2>();
-    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 0, NB2>();
-    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 0, NB2>();
-    if (e == hipSuccess) e = gs_attr<1, NB, EPI, 1, NB2>();
-    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 1, NB2>();
-    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 1, NB2>();
+    hipError_t e = gs_attr<1, NB, EPI, 0, NB2, SPLIT>();
+    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 0, NB2, SPLIT>();
+    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 0, NB2, SPLIT>();
+    if (e == hipSuccess) e = gs_attr<1, NB, EPI, 1, NB2, SPLIT>();
+    if (e == hipSuccess) e = gs_attr<2, NB, EPI, 1, NB2, SPLIT>();
+    if (e == hipSuccess) e = gs_attr<4, NB, EPI, 1, NB2, SPLIT>();
     return e;
 }
 
 }  // namespace
 
-// Tile width (16-column blocks per workgroup) of a store-type projection with N output columns
-// for a batch of `variant_rows` rows: the widest of 8, 4, 2, 1 that still gives about one
-// workgroup per compute unit.
-int stream_store_nb(int N)
+// Shape of a store-type projection [N, K] for a batch of `variant_rows` rows (of the FULL batch).
+// Unsplit: tiles of the widest of 8, 4, 2, 1 blocks that still gives about one workgroup per
+// compute unit.  Narrow tiles re-read the activations once per tile, which is what bounds them when
+// the batch has more than 16 rows; so when K is long enough to leave every wavefront at least 20
+// k-steps, tiles of 8, 4 or 2 blocks with K cut over 2..4 workgroups (about 256 workgroups again)
+// and the sum taken inside the launch are faster (measured, 32 rows: 4096 x 11008 20.2 against
+// 23.8 us; 64 rows: 8192 x 8192 28.9 against 31.7 us; 4096 x 4096 gains nothing).
+StoreShape stream_store_shape(int N, int K, long variant_rows)
 {
-    const int nblk = (N + 15) / 16;
+    const int nblk = (N + 15) / 16, kfrags = K / 32;
+    StoreShape sh{1, 1};
     for (int nb = 8; nb > 1; nb >>= 1)
-        if (nblk / nb >= 192) return nb;
-    return 1;
+        if (nblk / nb >= 192) { sh.nb = nb; break; }
+    if (variant_rows > 16) {
+        for (int nb = 8; nb >= 2; nb >>= 1) {
+            const int tiles = (nblk + nb - 1) / nb;
+            int S = 256 / tiles;
+            if (S > 4) S = 4;
+            if (S < 2 || tiles * S < 192 || kfrags / (4 * S) < 20) continue;
+            sh.nb = nb;
+            sh.nseg = S;
+            break;
+        }
+    }
+    return sh;
 }
+
+static int mb_of(int rows) { const int mb = (rows + 15) / 16; return mb <= 1 ? 1 : mb == 2 ? 2 : 4; }
+
+// fp32 partial tiles of a split store-type projection (0 when it is not split)
+size_t stream_store_partial_bytes(int N, int K, long variant_rows, int rows)
+{
+    const StoreShape sh = stream_store_shape(N, K, variant_rows);
+    if (sh.nseg < 2) return 0;
+    const size_t tiles = ((N + 15) / 16 + sh.nb - 1) / sh.nb;
+    return (size_t)sh.nseg * tiles * mb_of(rows) * 16 * sh.nb * 16 * sizeof(float);
+}
+
 // Blocks a compute unit ends up with when `tiles` tiles of `nb` blocks are dealt to 256 of them.
 static int blocks_per_cu(int tiles, int nb) { return ((tiles + 255) / 256) * nb; }
 
@@ -438,17 +544,34 @@ static void stream_gu_shape(int N2, int *nb1, int *nb2)
     else *nb1 = 8;
 }
 
-hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *X, bool x_rows, bool norm, float eps,
-                                    const void *res, void *out, void *out_packed, int M, int N, int K, hipStream_t st)
+hipError_t launch_gemm_stream_store(const void *Wp, StoreShape sh, const void *X, bool x_rows, bool norm, float eps,
+                                    const void *res, void *out, void *out_packed, int M, int N, int K, float *partials,
+                                    int *counters, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31) || (N & 15)) return hipErrorInvalidValue;
-    if (nb != 1 && nb != 2 && nb != 4 && nb != 8) return hipErrorInvalidValue;   // a tile lies inside one weight group
+    const int nb = sh.nb;
+    if (nb != 1 && nb != 2 && nb != 4 && nb != 8) return hipErrorInvalidValue;
     GsArgs a{};
     a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = norm ? 1 : 0; a.eps = eps;
     a.M = M; a.N = N; a.res = (const bf16_t *)res; a.out = (bf16_t *)out; a.out_packed = (bf16_t *)out_packed;
     const int tiles = ((N / 16) + nb - 1) / nb;
     a.ntiles = tiles; a.kf_seg = a.kfrags;
+    if (sh.nseg > 1) {
+        // K over nseg workgroups per tile, summed inside the launch; only without the norm (no per-segment sums of squares here)
+        if (sh.nseg > 4 || norm || !partials || !counters || tiles > kStreamCounters || nb < 2) return hipErrorInvalidValue;
+        a.nseg = sh.nseg; a.kf_seg = (a.kfrags + sh.nseg - 1) / sh.nseg;
+        if (a.kf_seg * (sh.nseg - 1) >= a.kfrags) return hipErrorInvalidValue;   // no empty segment
+        a.part = partials; a.cnt = counters;
+        const int grid = tiles * sh.nseg;
+#define CCS_GS(NBV) (x_rows ? gs_launch_mb<NBV, GS_STORE, 1, 0, 1>(grid, a, st) : gs_launch_mb<NBV, GS_STORE, 0, 0, 1>(grid, a, st))
+        switch (nb) {
+            case 2: return CCS_GS(2);
+            case 4: return CCS_GS(4);
+            default: return CCS_GS(8);
+        }
+#undef CCS_GS
+    }
 #define CCS_GS(NBV) (x_rows ? gs_launch_mb<NBV, GS_STORE, 1>(tiles, a, st) : gs_launch_mb<NBV, GS_STORE, 0>(tiles, a, st))
     switch (nb) {
         case 1: return CCS_GS(1);
@@ -546,6 +669,9 @@ hipError_t init_gemm_stream_kernels()
     if (e == hipSuccess) e = gs_attr_mb<2, GS_STORE>();
     if (e == hipSuccess) e = gs_attr_mb<4, GS_STORE>();
     if (e == hipSuccess) e = gs_attr_mb<8, GS_STORE>();
+    if (e == hipSuccess) e = gs_attr_mb<2, GS_STORE, 0, 1>();
+    if (e == hipSuccess) e = gs_attr_mb<4, GS_STORE, 0, 1>();
+    if (e == hipSuccess) e = gs_attr_mb<8, GS_STORE, 0, 1>();
     if (e == hipSuccess) e = gs_attr_mb<2, GS_SWIGLU>();
     if (e == hipSuccess) e = gs_attr_mb<4, GS_SWIGLU>();
     if (e == hipSuccess) e = gs_attr_mb<6, GS_SWIGLU>();

@@ -107,12 +107,21 @@ hipError_t launch_gemm_tiled(const void *Wp, const void *Xp, bool x_rows, int ep
 // result depends on that row alone.
 enum { GS_STORE = 0, GS_SWIGLU = 1, GS_QKV_DECODE = 2, GS_PARTIALS = 3 };
 hipError_t init_gemm_stream_kernels();
-// Tile width (16-column blocks, one of 1, 2, 4, 8) of a store-type projection with N output columns.
-int stream_store_nb(int N);
+// Shape of a store-type projection [N, K] for a batch of `variant_rows` rows (the FULL batch's count):
+// tiles of nb 16-column blocks (1, 2, 4 or 8) and, when nseg > 1, K cut over nseg workgroups per
+// tile whose partial tiles the last of them to finish adds in segment order inside the launch.
+struct StoreShape { int nb, nseg; };
+StoreShape stream_store_shape(int N, int K, long variant_rows);
+// bytes of fp32 partial tiles a split launch of `rows` rows needs (0 when the shape is not split)
+size_t stream_store_partial_bytes(int N, int K, long variant_rows, int rows);
+constexpr int kStreamCounters = 256;   // arrival counters (int32) a split launch may use; all zero between launches
 // out[m, n] = sum_k x'[m, k] W[n, k] (+ res[m, n]) as row-major bf16 [M, N] and, when out_packed
-// is not null, also fragment-packed [M16, N] (the operand of the next projection).
-hipError_t launch_gemm_stream_store(const void *Wp, int nb, const void *X, bool x_rows, bool norm, float eps,
-                                    const void *res, void *out, void *out_packed, int M, int N, int K, hipStream_t st);
+// is not null, also fragment-packed [M16, N] (the operand of the next projection).  A split shape
+// needs `partials` (stream_store_partial_bytes) and `counters` (kStreamCounters zeroed int32, left
+// zeroed) and no norm.
+hipError_t launch_gemm_stream_store(const void *Wp, StoreShape sh, const void *X, bool x_rows, bool norm, float eps,
+                                    const void *res, void *out, void *out_packed, int M, int N, int K, float *partials,
+                                    int *counters, hipStream_t st);
 // u = silu(gate) * up of RMSNorm(x), fragment-packed [M16, N2 / 2]; weight [N2, K] with gate / up
 // interleaved in 16-row blocks; x raw.
 hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *X, bool x_rows, float eps, void *u_packed, int M, int N2,

@@ -88,6 +88,7 @@ struct WsPlan {
     // norm themselves); xa, xb: activations between layers of a run; xc, yc, offs: dense prefill
     // rows in / out and their per-sequence offsets
     size_t h, qkv, a, x1, gu, u, xp, x1p, kp, vtp, xa, xb, xc, yc, offs, ssqp, scratch, scratch_bytes, total;   // ssqp: per-segment sums of squares of a K-split projection
+    size_t cnt;   // arrival counters of split weight-streaming launches: always at offset 0, zeroed when the workspace is attached
 };
 
 // A store-type projection (O, down, a single projection) of a batch of `variant_rows` <= 64 rows runs
@@ -102,6 +103,8 @@ inline bool qkv_split(long long variant_rows) { return variant_rows > 32; }
 // A single projection of up to this many rows (of the FULL batch) reads the caller's row-major rows in
 // the LDS-tiled GEMM itself; larger batches are packed first.
 constexpr long long kDirectRowsMax = 512;
+// first bytes of every workspace: arrival counters of split weight-streaming launches
+constexpr size_t kCounterBytes = (size_t)ccs::kStreamCounters * sizeof(int32_t);
 constexpr long long kLinearStreamRowsMax = 32;
 
 int check_desc(const ccs_module_desc *D, Dims *out)
@@ -183,10 +186,12 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     const size_t r16 = align_up(rows, 16);
+    p.cnt = take(kCounterBytes);
     if (D->kind == CCS_LINEAR) {
         if (D->dtype == CCS_BF16) {
             p.xp = take(r16 * d.in_f * 2);
-            p.scratch_bytes = vrows <= kLinearStreamRowsMax ? 0 : ccs::tiled_partial_bytes((int)rows, d.out_f, d.in_f, vrows);
+            p.scratch_bytes = vrows <= kLinearStreamRowsMax ? ccs::stream_store_partial_bytes(d.out_f, d.in_f, vrows, (int)rows)
+                                                            : ccs::tiled_partial_bytes((int)rows, d.out_f, d.in_f, vrows);
             p.scratch = take(p.scratch_bytes);
         }
     } else if (D->dtype == CCS_BF16) {
@@ -215,6 +220,8 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.W3, d.H));
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.QD));
             s = max_sz(s, ccs::skinny_partial_bytes((int)rows, d.H, d.I));
+            s = max_sz(s, ccs::stream_store_partial_bytes(d.H, d.QD, vrows, (int)rows));
+            s = max_sz(s, ccs::stream_store_partial_bytes(d.H, d.I, vrows, (int)rows));
         } else {
             s = max_sz(s, ccs::tiled_partial_bytes((int)rows, d.W3, d.H, vrows));
             s = max_sz(s, ccs::tiled_partial_bytes((int)rows, d.H, d.QD, vrows));
@@ -428,7 +435,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
         WsPlan p = ws_plan(&D, d, M, 0, 0, skinny, false, 0, (long)variant_rows);
         if (p.total > ws_bytes) return fail(CCS_ENOMEM, "%s workspace has %zu bytes, batch needs %zu", ws_static ? "the static" : "the replica's", ws_bytes, p.total);
         if (skinny) {   // one launch, straight from the caller's rows
-            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.w, stream_store_nb(d.out_f), b->x, true, false, 0.f, nullptr, b->y, nullptr, M, d.out_f, d.in_f, st));
+            CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.w, stream_store_shape(d.out_f, d.in_f, (long)variant_rows), b->x, true, false, 0.f, nullptr, b->y, nullptr, M, d.out_f, d.in_f, (float *)(ws + p.scratch), (int *)(ws + p.cnt), st));
             return CCS_OK;
         }
         if (variant_rows <= kDirectRowsMax) {
@@ -499,11 +506,11 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
                     CCS_STAGE(CCS_ST_ATTN, launch_attn_decode_main(ws + p.qkv, scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, kc, vc, b->cache_cap, st));
                     if (!attn_decode_is_whole(d.nq, d.nkv)) CCS_STAGE(CCS_ST_ATTN_COMBINE, launch_attn_decode_combine(scratch, ws + p.a, b->n_seqs, d.nq, d.nkv, b->lens_dev, b->cache_cap, st));
                 } else {
-                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_store(A + m->ap.qkv, kWGroup, xq, xq_rows, true, D.rms_eps, nullptr, ws + p.qkv, nullptr, T, d.W3, d.H, st));
+                    CCS_STAGE(CCS_ST_GEMM_QKV, launch_gemm_stream_store(A + m->ap.qkv, StoreShape{kWGroup, 1}, xq, xq_rows, true, D.rms_eps, nullptr, ws + p.qkv, nullptr, T, d.W3, d.H, nullptr, nullptr, st));
                     CCS_STAGE(CCS_ST_ROPE, launch_rope_pack_prefill(ws + p.qkv, ws + p.kp, ws + p.vtp, b->n_seqs, seq_pad, d.nq, d.nkv, tab, offs, kc, vc, b->cache_cap, st));
                     CCS_STAGE(CCS_ST_ATTN, launch_attn_prefill_mfma(ws + p.qkv, ws + p.kp, ws + p.vtp, ws + p.a, b->n_seqs, seq_pad, d.nq, d.nkv, offs, st));
                 }
-                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_stream_store(A + m->ap.o, stream_store_nb(d.H), ws + p.a, false, false, 0.f, x_in, x1_out, ffn ? ws + p.x1p : nullptr, T, d.H, d.QD, st));
+                CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_stream_store(A + m->ap.o, stream_store_shape(d.H, d.QD, (long)variant_rows), ws + p.a, false, false, 0.f, x_in, x1_out, ffn ? ws + p.x1p : nullptr, T, d.H, d.QD, scratch, (int *)(ws + p.cnt), st));
             }
             if (ffn) {
                 if (attn) CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, ws + p.x1p, false, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
@@ -513,7 +520,7 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
                     CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_partials(A + m->ap.dn, ws + p.u, false, false, scratch, nullptr, T, d.H, d.I, st));
                     CCS_STAGE(CCS_ST_GEMM_DOWN_REDUCE, launch_partial_reduce(scratch, skinny_segments(d.H, d.I), EPI_STORE_RM, x1_in, x_out, next_xp, T, d.H, st));
                 } else {
-                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.dn, stream_store_nb(d.H), ws + p.u, false, false, 0.f, x1_in, x_out, next_xp, T, d.H, d.I, st));
+                    CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_store(A + m->ap.dn, stream_store_shape(d.H, d.I, (long)variant_rows), ws + p.u, false, false, 0.f, x1_in, x_out, next_xp, T, d.H, d.I, scratch, (int *)(ws + p.cnt), st));
                 }
                 xp_ready = !last;
             }
@@ -606,6 +613,8 @@ size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
     if (!skinny) {
         need = max_sz(need, ws_plan(desc, d, ccs::kSkinnyMaxRows, max_seqs, max_cache_cap, true, false, layer ? max_seq_pad : 0).total);
     }
+    if (desc->kind == CCS_LINEAR && rows > (size_t)kLinearStreamRowsMax)   // a small batch takes the weight-streaming launch, which may split K
+        need = max_sz(need, ws_plan(desc, d, (size_t)kLinearStreamRowsMax, max_seqs, 0, true, false, 0).total);
     if (layer && max_cache_cap > 0) {
         const bool dsk = max_seqs <= ccs::kSkinnyMaxRows;
         need = max_sz(need, ws_plan(desc, d, max_seqs, max_seqs, max_cache_cap, dsk, true, 0).total);
@@ -733,8 +742,9 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *w, void *a
         drop();
         return CCS_EHIP;
     }
-    e = hipEventRecord(R.ready, st);
-    if (e != hipSuccess) { drop(); return fail(CCS_EHIP, "hipEventRecord: %s", hipGetErrorString(e)); }
+    e = workspace_bytes >= kCounterBytes ? hipMemsetAsync(workspace0, 0, kCounterBytes, st) : hipSuccess;
+    if (e == hipSuccess) e = hipEventRecord(R.ready, st);
+    if (e != hipSuccess) { drop(); return fail(CCS_EHIP, "attaching the workspace: %s", hipGetErrorString(e)); }
     m->k = 1;
     *out = m;
     return CCS_OK;
@@ -787,6 +797,7 @@ int ccs_module_replicate(ccs_module *m, int32_t k, void *const *arenas, void *co
             e = ccs::launch_clone(N.arena, m->rep[0].arena, m->ap.total, N.stream);
             prof_end(pp, N.stream);
         }
+        if (e == hipSuccess && N.ws_bytes >= kCounterBytes) e = hipMemsetAsync(N.ws, 0, kCounterBytes, N.stream);
         if (e == hipSuccess) e = hipEventRecord(N.ready, N.stream);
         if (e != hipSuccess) {
             undo();

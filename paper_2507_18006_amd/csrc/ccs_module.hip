@@ -106,6 +106,15 @@ constexpr long long kDirectRowsMax = 512;
 // first bytes of every workspace: arrival counters of split weight-streaming launches
 constexpr size_t kCounterBytes = (size_t)ccs::kStreamCounters * sizeof(int32_t);
 constexpr long long kLinearStreamRowsMax = 32;
+// A single projection streams its weight in one launch up to 32 rows (of the FULL batch), and up to
+// 64 rows when the weight's shape lets that launch cut K over workgroups (wide tiles: measured on
+// 11008 -> 4096 at 64 rows 22.9 us in one launch, against 32.9 us over narrow tiles and 26 us for
+// the LDS-tiled GEMM with its reduction launch).
+inline bool linear_streams(int out_f, int in_f, long long variant_rows)
+{
+    if (variant_rows <= kLinearStreamRowsMax) return true;
+    return variant_rows <= ccs::kSkinnyMaxRows && ccs::stream_store_shape(out_f, in_f, (long)variant_rows).nseg > 1;
+}
 
 int check_desc(const ccs_module_desc *D, Dims *out)
 {
@@ -190,7 +199,7 @@ WsPlan ws_plan(const ccs_module_desc *D, const Dims &d, size_t rows, int n_seqs,
     if (D->kind == CCS_LINEAR) {
         if (D->dtype == CCS_BF16) {
             p.xp = take(r16 * d.in_f * 2);
-            p.scratch_bytes = vrows <= kLinearStreamRowsMax ? ccs::stream_store_partial_bytes(d.out_f, d.in_f, vrows, (int)rows)
+            p.scratch_bytes = linear_streams(d.out_f, d.in_f, vrows) ? ccs::stream_store_partial_bytes(d.out_f, d.in_f, vrows, (int)rows)
                                                             : ccs::tiled_partial_bytes((int)rows, d.out_f, d.in_f, vrows);
             p.scratch = take(p.scratch_bytes);
         }
@@ -424,10 +433,8 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
     if (D.kind == CCS_LINEAR) {
         const char *A = A0;
         const int M = b->n_seqs;
-        // a single projection streams its weight in one launch up to 32 rows; from 33 rows on the
-        // LDS-tiled GEMM with its K split is faster (measured on the 11008 -> 4096 projection: 26 us at
-        // 65 rows against 28 us at 32 rows in the streaming form)
-        const bool skinny = bf && variant_rows <= kLinearStreamRowsMax;
+        // small batches stream the weight in one launch (see linear_streams), larger ones take the LDS-tiled GEMM
+        const bool skinny = bf && linear_streams(d.out_f, d.in_f, variant_rows);
         if (!bf) {
             CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_f32((const float *)b->x, (const float *)(A + m->ap.w), nullptr, (float *)b->y, M, d.out_f, d.in_f, st));
             return CCS_OK;
@@ -614,7 +621,7 @@ size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
         need = max_sz(need, ws_plan(desc, d, ccs::kSkinnyMaxRows, max_seqs, max_cache_cap, true, false, layer ? max_seq_pad : 0).total);
     }
     if (desc->kind == CCS_LINEAR && rows > (size_t)kLinearStreamRowsMax)   // a small batch takes the weight-streaming launch, which may split K
-        need = max_sz(need, ws_plan(desc, d, (size_t)kLinearStreamRowsMax, max_seqs, 0, true, false, 0).total);
+        need = max_sz(need, ws_plan(desc, d, rows < (size_t)ccs::kSkinnyMaxRows ? rows : (size_t)ccs::kSkinnyMaxRows, max_seqs, 0, true, false, 0).total);
     if (layer && max_cache_cap > 0) {
         const bool dsk = max_seqs <= ccs::kSkinnyMaxRows;
         need = max_sz(need, ws_plan(desc, d, max_seqs, max_seqs, max_cache_cap, dsk, true, 0).total);

@@ -228,6 +228,37 @@ def test_bf16_linear_rows_across_variants():
         run_case(workloads.scaled(base, n_seqs=n), [1, 2, 4], seed=n)
 
 
+def test_bf16_projection_with_k_cut_over_workgroups_inside_one_launch():
+    """Weights wide and deep enough that the weight-streaming launch cuts K over 4, 3 and 2
+    workgroups per tile and the last of them to finish adds the partial tiles (17..64 rows; the
+    replica slices of 17 rows run the same variant with a single row block)."""
+    for (k_in, n_out, rows) in ((10240, 2048, (17, 32, 33, 64)), (7680, 5120, (20, 64)), (5120, 8192, (24, 49))):
+        base = workloads.scaled(C["C5"], in_features=k_in, out_features=n_out)
+        for n in rows:
+            run_case(workloads.scaled(base, n_seqs=n), [1, 2, 4], seed=300 + n)
+    # the same inside a decode step: the down projection of this layer splits K, with the residual behind it
+    dec = workloads.scaled(C["C2"], hidden=2048, n_q_heads=16, n_kv_heads=16, intermediate=10240, n_seqs=24,
+                           len_lo=0, len_hi=300)
+    run_case(dec, [1, 2, 3], seed=330)
+
+
+def test_bf16_split_k_launch_gives_the_same_bits_every_time():
+    """The sum over the K segments is taken in segment order by whichever workgroup finishes last:
+    the result must not depend on which one that is.  60 launches, one expected value."""
+    cfg = workloads.scaled(C["C5"], in_features=10240, out_features=2048, n_seqs=48)
+    m = U.make_module(cfg)
+    try:
+        db = U.DeviceBatch(m, cfg, workloads.make_inputs(cfg, 7))
+        m.forward_split(db.batch)
+        first = db.out().copy()
+        for it in range(60):
+            db.y.fill_(1.0)
+            m.forward_split(db.batch)
+            assert np.array_equal(db.out(), first), f"launch {it} differs"
+    finally:
+        m.destroy()
+
+
 def test_bf16_weight_block_groups_with_padding():
     """Weights are packed in groups of 8 row blocks: block counts that are not a multiple of 8
     (65 blocks; gate/up with 348) exercise the zero padding, odd k-fragment counts the ragged

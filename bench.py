@@ -6,7 +6,8 @@ Default workload (the configuration the headline metric is quoted on): a step = 
 a decode step: batch 32, 1024 cached positions per sequence (benchmark configuration 1), bf16, seeded
 synthetic tensors resident in HBM before timing starts.  `value` is tokens/s at k = 1; k = 2 and
 k = 4 (same total batch) and the replica-clone rate are reported beside it.  The `roofline`
-object prices the dominant kernel against its roofline (decode attention vs HBM; for the prefill
+object prices the dominant kernel against its roofline (decode: the launch that moves the most bytes -
+attention for the 7B shape, the gate/up projection for the 70B shape - vs HBM; for the prefill
 workload the gate/up projection vs the bf16 MFMA peak); `cpu_baseline` is the CPU oracle timed
 on this machine's host cores.
 
@@ -100,7 +101,8 @@ def bench_layer(args, name, sub=False):
     if decode:
         kv_bytes = int((lens + 1).sum()) * nkv * d * 2 * 2
         act_bytes = n_tok * (2 * H + 2 * nkv * d) * 2           # x in, y out, new K/V out
-        dominant = "attn"
+        gu_bytes = 2 * I * H * 2 + rows * (H + I) * 2           # gate/up launch: weights, x1 rows in, u rows out
+        dominant = "attn" if kv_bytes >= gu_bytes else "gemm_gu"   # the launch with the most bytes to move
     else:
         kv_bytes, act_bytes = 0, 2 * rows * H * 2
         dominant = "gemm_gu"
@@ -258,13 +260,19 @@ def bench_layer(args, name, sub=False):
         m.destroy()
 
     traffic, traffic_file = measured_traffic(name)
-    if decode:
+    if decode and dominant == "attn":
         roof = {"kernel": "attn_decode_whole_kernel (one workgroup per sequence and kv head, merge inside)" if nkv >= 16
                 else "attn_decode_mfma_kernel (one wavefront per 128-key chunk; + attn_combine_kernel, not included)", "bound": "hbm",
                 "achieved": round(kv_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(kv_bytes / dom_s / 1e9 / HBM_PEAK_GBPS, 4),
                 "traffic": traffic, "traffic_source": traffic_file,
                 "algorithmic_bytes_per_launch": kv_bytes}
+    elif decode:
+        roof = {"kernel": "gemm_stream_kernel (gate/up projection with RMSNorm in front and SwiGLU behind, one launch)", "bound": "hbm",
+                "achieved": round(gu_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(gu_bytes / dom_s / 1e9 / HBM_PEAK_GBPS, 4),
+                "traffic": traffic, "traffic_source": traffic_file,
+                "algorithmic_bytes_per_launch": gu_bytes}
     else:
         N, Kd = shapes[dominant]
         fl = 2.0 * rows * N * Kd

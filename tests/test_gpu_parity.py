@@ -257,6 +257,24 @@ def test_bf16_split_k_launch_gives_the_same_bits_every_time():
             assert np.array_equal(db.out(), first), f"launch {it} differs"
     finally:
         m.destroy()
+    # the 7B decode step at k = 1 and k = 2 (its down projection splits K): 300 steps back to back, compared on the device
+    cfg = C["C2"]
+    m = U.make_module(cfg)
+    try:
+        db = U.DeviceBatch(m, cfg, workloads.make_inputs(cfg, 0))
+        m.forward_split(db.batch)
+        torch.cuda.synchronize()
+        first = db.y.clone()
+        for k in (1, 2):
+            m.replicate(k)
+            bad = torch.zeros((), dtype=torch.int32, device=U.DEV)
+            for it in range(300):
+                m.forward_split(db.batch)
+                bad += (db.y != first).any().to(torch.int32)
+            torch.cuda.synchronize()
+            assert int(bad.item()) == 0, f"k = {k}: {int(bad.item())} of 300 steps differ from the first"
+    finally:
+        m.destroy()
 
 
 def test_bf16_weight_block_groups_with_padding():

@@ -20,14 +20,21 @@
 //     epilogue - a row's scale is a scalar, so it commutes with the projection;
 //   * epilogues: store (+ residual) row-major, optionally also fragment-packed for the next
 //     projection; SwiGLU into a fragment-packed u; and for the decode Q/K/V projection the rotary
-//     embedding, the q store and the KV-cache append (a tile holds dims [32 s, 32 s + 32) and
-//     [64 + 32 s, 64 + 32 s + 32) of one head, i.e. whole rotary pairs).
-//   * GS_PARTIALS: for 33..64 rows against a large weight the activations are re-read too often by
-//     narrow tiles (the time grows with the activation bytes), so those launches keep 128-column
-//     tiles and cut K into segments over the workgroups instead (a count that depends on the weight
-//     shape only); the kernel then leaves fp32 partial sums (and per-segment sums of squares) and a
-//     small second kernel adds them in segment order and applies the epilogue.
-// Tile width NB and everything else about the launch depend on the weight shape and on the row
+//     embedding, the q store and the KV-cache append (a tile is made of whole rotary pairs: dims
+//     [16 s, 16 s + 16) and their partners 64 up, plus - in the 3-block form - 16 dims of a v head).
+//   * tile shapes: a compute unit sustains only so many outstanding misses, so a launch streams
+//     at a rate proportional to the compute units it keeps busy - every launcher below picks tiles
+//     that leave all 256 of them about the same number of blocks (two passes over NB + NB2 blocks
+//     when one pass would need too many accumulators); and narrow tiles re-read the activations
+//     once per tile through the same L1, so where K is long enough (SPLIT) tiles stay wide, K is
+//     cut over 2..4 workgroups per tile and the workgroup that finishes last adds the partial
+//     tiles in segment order inside the launch (device-coherent stores and loads, an arrival
+//     counter per tile; nobody waits, so nothing can hang);
+//   * GS_PARTIALS: the same cut with fp32 partial sums (and per-segment sums of squares) left for a
+//     small second kernel that adds them in segment order and applies the epilogue - kept where
+//     that kernel has more to do than add (rotary + cache append for 33..64 rows) or measured
+//     faster (K > 8192 at 33..64 rows).
+// Tile shape, K cut and everything else about the launch depend on the weight shape and on the row
 // count of the full batch only, and every output row is computed from its own input row alone,
 // so a row's bits do not depend on the batch.
 #include "ccs_common.h"

@@ -242,6 +242,26 @@ def test_bf16_projection_with_k_cut_over_workgroups_inside_one_launch():
     run_case(dec, [1, 2, 3], seed=330)
 
 
+def test_bf16_gate_up_tile_shapes_of_the_weight_streaming_launch():
+    """The gate/up launch of a small batch gives every compute unit the same number of (gate, up)
+    pairs of blocks: one to four pairs in one pass, five and seven in two passes, six and more than
+    eight as tiles of three and four pairs.  One FFN block per case, 20 and 64 rows."""
+    for inter in (2752, 6144, 11008, 14336, 16640, 24576, 28672, 36864):   # ceil(pairs / 256) = 1, 2, 3, 4, 5, 6, 7, 9
+        ffn = workloads.scaled(C["C2"], kind="ffn_block", mode="linear", hidden=256, n_q_heads=2, n_kv_heads=2,
+                               intermediate=inter, n_seqs=20)
+        run_case(ffn, [1, 2], seed=400 + inter % 97)
+        run_case(workloads.scaled(ffn, n_seqs=64), [1, 3], seed=401 + inter % 97)
+
+
+def test_bf16_decode_qkv_tile_shapes_with_many_heads():
+    """The decode Q/K/V launch picks whole-head tiles for 144 grouped-query head slots and
+    pair + v-block tiles (two rounds of them) for 64 + 64 + 64 multi-head slots."""
+    for nq, nkv in ((96, 24), (64, 64)):
+        cfg = workloads.scaled(C["C2"], hidden=256, n_q_heads=nq, n_kv_heads=nkv, intermediate=512, n_seqs=12,
+                               len_lo=0, len_hi=200)
+        run_case(cfg, [1, 2], seed=500 + nq)
+
+
 def test_bf16_split_k_launch_gives_the_same_bits_every_time():
     """The sum over the K segments is taken in segment order by whichever workgroup finishes last:
     the result must not depend on which one that is.  60 launches, one expected value."""

@@ -705,7 +705,10 @@ __global__ __launch_bounds__(256, 2) void attn_decode_whole_kernel(
 }
 #undef DM_TR
 
-// Merge the chunk partials of one (sequence, head) in chunk order; thread c owns value c.
+// Merge the chunk partials of one (sequence, head) in chunk order; thread c owns value c.  The
+// (max, sum, value) loads of 16 chunks are all issued before anything is used, so a sequence of up to
+// 16 chunks (2048 keys) costs one memory round trip; longer ones carry a running maximum from block
+// to block of 16.
 __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restrict__ part,
                                                            bf16_t *__restrict__ out, int nq,
                                                            const int32_t *__restrict__ lens, int nchunks,
@@ -714,28 +717,28 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restri
     const int b = blockIdx.x / nq, h = blockIdx.x % nq, c = threadIdx.x;
     const int n = min((max(lens[b], 0) + chunk_keys) / chunk_keys, nchunks);
     const float *p = part + ((size_t)b * nq + h) * nchunks * kDecPart;
-    // eight chunks at a time, their loads all in flight; merged in chunk order
-    float M = -INFINITY;
-    for (int i0 = 0; i0 < n; i0 += 8) {
-        float m[8];
+    float M = -INFINITY, L = 0.f, a = 0.f;
+    for (int i0 = 0; i0 < n; i0 += 16) {
+        float m[16], l[16], v[16];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) m[e] = i0 + e < n ? p[(size_t)(i0 + e) * kDecPart] : -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) M = fmaxf(M, m[e]);
-    }
-    float L = 0.f, a = 0.f;
-    for (int i0 = 0; i0 < n; i0 += 8) {
-        float m[8], l[8], v[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 0; e < 16; ++e) {
             const bool ok = i0 + e < n;
             const float *q = p + (size_t)(ok ? i0 + e : 0) * kDecPart;
-            m[e] = ok ? q[0] : -INFINITY;   // weight 0
+            m[e] = q[0];
             l[e] = q[1];
             v[e] = q[4 + c];
+            if (!ok) m[e] = -INFINITY;   // weight 0
         }
+        float Mb = m[0];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 1; e < 16; ++e) Mb = fmaxf(Mb, m[e]);
+        const float Mn = fmaxf(M, Mb);                 // chunk 0 always has a key: Mn is finite
+        const float keep = fast_exp2(M - Mn);          // 0 for the first block (M = -inf), 1 when the maximum stays
+        L *= keep;
+        a *= keep;
+        M = Mn;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
             const float w = fast_exp2(m[e] - M);
             L = fmaf(l[e], w, L);
             a = fmaf(v[e], w, a);

@@ -30,6 +30,11 @@
 //     cut over 2..4 workgroups per tile and the workgroup that finishes last adds the partial
 //     tiles in segment order inside the launch (device-coherent stores and loads, an arrival
 //     counter per tile; nobody waits, so nothing can hang);
+//   * column-split form (COLS; gate/up of a 33..64-row batch with five to eight (gate, up) pairs per
+//     workgroup): the wavefronts share K and split the tile's columns, the activation fragments
+//     are fetched once per workgroup and handed round through LDS - NB / 4 x MB accumulator tiles
+//     per wavefront instead of NB x MB, so 14 blocks fit ONE pass where the K-split form needs
+//     two passes that fetch the activations twice (70B gate/up at 64 rows: 152 -> 143 us);
 //   * GS_PARTIALS: the same cut with fp32 partial sums (and per-segment sums of squares) left for a
 //     small second kernel that adds them in segment order and applies the epilogue - kept where
 //     that kernel has more to do than add (rotary + cache append for 33..64 rows) or measured
@@ -55,7 +60,7 @@ __device__ __forceinline__ f32x4_t gs_mfma(const uint4 &a, const uint4 &b, f32x4
 constexpr int gs_u(int MB, int NB) { return (NB + MB) <= 3 ? 6 : (NB + MB) <= 6 ? 4 : 2; }
 
 // floats of LDS the reduction and the row statistics take: W / 2 tile buffers, per-wavefront sums of squares, scales
-constexpr int gs_red_floats(int MB, int NB, int W) { return (W / 2) * MB * 16 * (NB * 16 + 4) + W * MB * 16 + MB * 16 + 4; }
+constexpr int gs_red_floats(int MB, int NB, int W, int COLS = 0) { return (COLS ? 1 : W / 2) * MB * 16 * (NB * 16 + 4) + W * MB * 16 + MB * 16 + 4; }
 
 struct GsArgs {
     const uint4 *Wp;      // grouped fragment-packed weight
@@ -75,7 +80,8 @@ struct GsArgs {
     float *ssq_part;      // optional: the rows' sums of squares per segment [S, M]
     // SPLIT: K cut over nseg workgroups per tile, summed by the workgroup of a tile that finishes last
     int nseg;
-    int *cnt;             // one arrival counter per tile; zero between launches
+    int *cnt;
+    int nbt;              // COLS: blocks of a tile that exist (<= NB); tile t starts at block t * nbt             // one arrival counter per tile; zero between launches
     // GS_QKV_DECODE
     int nq, nkv;
     const float2 *tab;
@@ -86,9 +92,11 @@ struct GsArgs {
 
 // One tile of a launch: the NB 16-column blocks blk0 .. blk0 + NB - 1 of the weight (GS_QKV_DECODE:
 // the blocks that `tile` names, see below) over K segment `seg`, from the first load to the last store.
-template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int SPLIT>
+template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int SPLIT, int COLS = 0>
 __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int blk0, const int tile, const int seg)
 {
+    static_assert(!COLS || (MB == 4 && kGsWaves == 4 && NB % 4 == 0 && !XROWS && EPI != GS_QKV_DECODE && EPI != GS_PARTIALS),
+                  "column-split form: 64 rows, four wavefronts, packed activations");
     constexpr int ROWF = NB * 16 + 4;      // floats per padded LDS row: conflict-free 16-byte accesses
     constexpr int BUF = MB * 16 * ROWF;    // floats per reduction buffer
     constexpr bool QKV3 = EPI == GS_QKV_DECODE && NB == 3;   // one rotary pair of blocks of a q or k head + one block of a v head
@@ -105,126 +113,210 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
     constexpr int PARTS = QKV3 ? 4 : NB >= 8 ? 1 : 8 / NB;
     const int hs = tile / PARTS, part = tile % PARTS;   // head slot and part of the head (GS_QKV_DECODE)
     const int last_blk = (a.N >> 4) - 1;               // blocks past the weight repeat the last one; never stored
-    const uint4 *wp[NB];
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        int nb;
-        if (QKV3) nb = j < 2 ? hs * 8 + j * 4 + part : (a.nq + a.nkv) * 8 + tile;
-        else if (EPI == GS_QKV_DECODE) nb = hs * 8 + (j / HH) * 4 + part * HH + (j % HH);
-        else nb = min(blk0 + j, last_blk);
-        wp[j] = a.Wp + (((size_t)(nb / G) * kfrags) * G + (nb % G)) * 64 + lane;
-    }
-    const size_t wstep = (size_t)G * 64;   // uint4 from one k-step of a block to the next
-
-    const uint4 *xp[MB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i) {
-        if (XROWS) {   // lane -> row i * 16 + lane / 4, 16-byte piece lane % 4 of the k-step's 64 bytes
-            const int row = min(i * 16 + (lane >> 2), a.M - 1);   // rows past the batch repeat the last one; never stored
-            xp[i] = a.X + (size_t)row * kfrags * 4 + (lane & 3);
-        } else {
-            const int blk = min(i, (a.M - 1) >> 4);   // row blocks past the batch repeat the last one; never stored
-            xp[i] = a.X + (size_t)blk * kfrags * 64 + lane;
-        }
-    }
-    constexpr int XSTEP = XROWS ? 4 : 64;   // uint4 per k-step
     const bool norm = a.norm != 0;
-    // XROWS: this wavefront's staging area, one 1 KiB fragment per (k-step of a set, row block), behind
-    // the reduction buffers.  Row r's piece c sits at slot 4 r + (c ^ (r / 4 % 4)): the writes (lane =
-    // 4 r + c) and the reads in fragment order (lane = r + 16 c) both touch every bank once per 16 lanes.
-    uint4 *stage = (uint4 *)(red + gs_red_floats(MB, NB, kGsWaves)) + wave * (U * MB * 64);
-    const int st_wr = ((lane >> 2) << 2) + ((lane & 3) ^ ((lane >> 4) & 3));
-    const int st_rd = ((lane & 15) << 2) + ((lane >> 4) ^ (((lane & 15) >> 2) & 3));
-
-    f32x4_t acc[NB][MB];
+    constexpr int HALF = kGsWaves / 2;
+    constexpr int NRB = COLS ? 1 : HALF;       // reduction buffers
+    float *wssq = red + NRB * BUF;             // [wavefronts][MB * 16 rows]
+    float *rsv = wssq + kGsWaves * MB * 16;    // [MB * 16]: rsqrt(mean square + eps) per row
+    const int nbt = COLS ? a.nbt : NB;         // blocks of this tile that exist
+    if constexpr (COLS) {
+        // Column-split form (64 rows): the wavefronts share K and split the tile's COLUMNS - wavefront w
+        // owns blocks w * NB / 4 .. - so a wavefront keeps NB / 4 x MB accumulator tiles instead of
+        // NB x MB and a tile can be 14 or 16 blocks wide in ONE pass; the activation fragments, which
+        // every wavefront needs, are fetched once per workgroup (wavefront w loads row block w) and
+        // handed round through LDS, one set of U k-steps per barrier, double-buffered.
+        constexpr int NBW = NB / 4;
+        const uint4 *wq[NBW];
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-        for (int i = 0; i < MB; ++i) acc[j][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    f32x4_t sq[MB];   // X X^T per row block; the diagonal is the rows' sum of squares
-#pragma unroll
-    for (int i = 0; i < MB; ++i) sq[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    // Two register sets of U k-steps each, rolling: while one set is multiplied the other is in
-    // flight.  The loop body has no branch around a load - past the end a set re-loads the last
-    // k-step (a cache hit) and is not multiplied - so that the compiler's wait counts stay exact.
-    // (Starting each tile's K walk at a different offset, so that the workgroups do not ask the L2
-    // for the same activation lines at the same moment, was measured: no gain.)
-    uint4 w0[U][NB], x0[U][MB], w1[U][NB], x1[U][MB];
-    const int n_sets = (kb_hi - kb_lo + U - 1) / U;
-#define GS_LOAD(W_, X_, SET)                                                                              \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
-        const int kk = min(kb_lo + (SET) * U + u, kb_hi - 1);                                             \
-        _Pragma("unroll") for (int j = 0; j < NB; ++j) W_[u][j] = ld_stream(wp[j] + (size_t)kk * wstep);  \
-        _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * XSTEP];              \
-    }
-#define GS_MUL(W_, X_, SET)                                                                               \
-    if (XROWS) {   /* row pieces -> fragment order through the wavefront's own LDS */                     \
-        _Pragma("unroll") for (int u = 0; u < U; ++u)                                                     \
-            _Pragma("unroll") for (int i = 0; i < MB; ++i) stage[(u * MB + i) * 64 + st_wr] = X_[u][i];   \
-        _Pragma("unroll") for (int u = 0; u < U; ++u)                                                     \
-            _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = stage[(u * MB + i) * 64 + st_rd];   \
-    }                                                                                                     \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
-        if (kb_lo + (SET) * U + u < kb_hi) {                                                              \
-            _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                 \
-                _Pragma("unroll") for (int i = 0; i < MB; ++i) acc[j][i] = gs_mfma(W_[u][j], X_[u][i], acc[j][i]); \
-            if (EPI == GS_SWIGLU || EPI == GS_QKV_DECODE || norm) {                                       \
-                _Pragma("unroll") for (int i = 0; i < MB; ++i) sq[i] = gs_mfma(X_[u][i], X_[u][i], sq[i]); \
-            }                                                                                             \
-        }                                                                                                 \
-    }
-    if (n_sets > 0) {
-        GS_LOAD(w0, x0, 0);
-        GS_LOAD(w1, x1, 1);
-        for (int s = 0; s < n_sets; s += 2) {
-            GS_MUL(w0, x0, s);
-            GS_LOAD(w0, x0, s + 2);
-            GS_MUL(w1, x1, s + 1);
-            GS_LOAD(w1, x1, s + 3);
+        for (int j = 0; j < NBW; ++j) {
+            const int nb = min(blk0 + min(wave * NBW + j, nbt - 1), last_blk);   // blocks past the tile repeat its last one; never stored
+            wq[j] = a.Wp + (((size_t)(nb / G) * kfrags) * G + (nb % G)) * 64 + lane;
         }
+        const size_t wstep = (size_t)G * 64;
+        const uint4 *xmine = a.X + (size_t)min(wave, (a.M - 1) >> 4) * kfrags * 64 + lane;   // row block `wave`
+        uint4 *xs = (uint4 *)(red + gs_red_floats(MB, NB, kGsWaves, 1));                      // [2 stages][U][MB][64]
+        f32x4_t acc[NBW][MB];
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) acc[j][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        f32x4_t sqw = f32x4_t{0.f, 0.f, 0.f, 0.f};   // X X^T of row block `wave`
+        uint4 w0[U][NBW], xr0[U], w1[U][NBW], xr1[U];
+        const int n_sets = (seg_hi - seg_lo + U - 1) / U;
+#define GC_LOAD(W_, XR_, SET)                                                                              \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                        \
+        const int kk = min(seg_lo + (SET) * U + u, seg_hi - 1);                                            \
+        _Pragma("unroll") for (int j = 0; j < NBW; ++j) W_[u][j] = ld_stream(wq[j] + (size_t)kk * wstep);  \
+        XR_[u] = xmine[(size_t)kk * 64];                                                                   \
     }
+#define GC_PUBLISH(XR_, STAGE)                                                                             \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) xs[(((STAGE) * U + u) * MB + wave) * 64 + lane] = XR_[u];
+        // set SET: X of all row blocks from stage STAGE, own weights W_, own row block XR_ for the sum of
+        // squares; then the next set's X (XN_, loaded a step ago) goes into the other stage, this set's
+        // registers are refilled two sets ahead, and the workgroup meets
+#define GC_STEP(W_, XR_, XN_, SET, STAGE)                                                                  \
+    {                                                                                                      \
+        uint4 xf[U][MB];                                                                                   \
+        _Pragma("unroll") for (int u = 0; u < U; ++u)                                                      \
+            _Pragma("unroll") for (int i = 0; i < MB; ++i) xf[u][i] = xs[(((STAGE) * U + u) * MB + i) * 64 + lane]; \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                    \
+            if (seg_lo + (SET) * U + u < seg_hi) {                                                         \
+                _Pragma("unroll") for (int j = 0; j < NBW; ++j)                                             \
+                    _Pragma("unroll") for (int i = 0; i < MB; ++i) acc[j][i] = gs_mfma(W_[u][j], xf[u][i], acc[j][i]); \
+                if (EPI == GS_SWIGLU || norm) sqw = gs_mfma(XR_[u], XR_[u], sqw);                          \
+            }                                                                                              \
+        }                                                                                                  \
+        GC_PUBLISH(XN_, 1 - (STAGE));                                                                      \
+        GC_LOAD(W_, XR_, (SET) + 2);                                                                       \
+        __syncthreads();                                                                                   \
+    }
+        GC_LOAD(w0, xr0, 0);
+        GC_PUBLISH(xr0, 0);
+        GC_LOAD(w1, xr1, 1);
+        __syncthreads();
+        for (int s = 0; s < n_sets; s += 2) {
+            GC_STEP(w0, xr0, xr1, s, 0);
+            GC_STEP(w1, xr1, xr0, s + 1, 1);
+        }
+#undef GC_LOAD
+#undef GC_PUBLISH
+#undef GC_STEP
+        // every wavefront puts its columns into the one tile buffer; its row block's sums of squares, zeros for the others
+        float *slot0 = red + (lane & 15) * ROWF + (lane >> 4) * 4;
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) {
+            const int cb = wave * NBW + j;
+            if (cb < nbt) {
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+                    *(float4 *)(slot0 + i * 16 * ROWF + cb * 16) = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
+            }
+        }
+        const int m16 = lane & 15;
+        if ((lane >> 4) == (m16 >> 2)) {
+            const float sv = (m16 & 3) == 0 ? sqw[0] : (m16 & 3) == 1 ? sqw[1] : (m16 & 3) == 2 ? sqw[2] : sqw[3];
+#pragma unroll
+            for (int i = 0; i < MB; ++i) wssq[wave * (MB * 16) + i * 16 + m16] = i == wave ? sv : 0.f;
+        }
+        __syncthreads();
+    } else {
+        const uint4 *wp[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            int nb;
+            if (QKV3) nb = j < 2 ? hs * 8 + j * 4 + part : (a.nq + a.nkv) * 8 + tile;
+            else if (EPI == GS_QKV_DECODE) nb = hs * 8 + (j / HH) * 4 + part * HH + (j % HH);
+            else nb = min(blk0 + j, last_blk);
+            wp[j] = a.Wp + (((size_t)(nb / G) * kfrags) * G + (nb % G)) * 64 + lane;
+        }
+        const size_t wstep = (size_t)G * 64;   // uint4 from one k-step of a block to the next
+
+        const uint4 *xp[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            if (XROWS) {   // lane -> row i * 16 + lane / 4, 16-byte piece lane % 4 of the k-step's 64 bytes
+                const int row = min(i * 16 + (lane >> 2), a.M - 1);   // rows past the batch repeat the last one; never stored
+                xp[i] = a.X + (size_t)row * kfrags * 4 + (lane & 3);
+            } else {
+                const int blk = min(i, (a.M - 1) >> 4);   // row blocks past the batch repeat the last one; never stored
+                xp[i] = a.X + (size_t)blk * kfrags * 64 + lane;
+            }
+        }
+        constexpr int XSTEP = XROWS ? 4 : 64;   // uint4 per k-step
+        // XROWS: this wavefront's staging area, one 1 KiB fragment per (k-step of a set, row block), behind
+        // the reduction buffers.  Row r's piece c sits at slot 4 r + (c ^ (r / 4 % 4)): the writes (lane =
+        // 4 r + c) and the reads in fragment order (lane = r + 16 c) both touch every bank once per 16 lanes.
+        uint4 *stage = (uint4 *)(red + gs_red_floats(MB, NB, kGsWaves)) + wave * (U * MB * 64);
+        const int st_wr = ((lane >> 2) << 2) + ((lane & 3) ^ ((lane >> 4) & 3));
+        const int st_rd = ((lane & 15) << 2) + ((lane >> 4) ^ (((lane & 15) >> 2) & 3));
+
+        f32x4_t acc[NB][MB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) acc[j][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        f32x4_t sq[MB];   // X X^T per row block; the diagonal is the rows' sum of squares
+#pragma unroll
+        for (int i = 0; i < MB; ++i) sq[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        // Two register sets of U k-steps each, rolling: while one set is multiplied the other is in
+        // flight.  The loop body has no branch around a load - past the end a set re-loads the last
+        // k-step (a cache hit) and is not multiplied - so that the compiler's wait counts stay exact.
+        // (Starting each tile's K walk at a different offset, so that the workgroups do not ask the L2
+        // for the same activation lines at the same moment, was measured: no gain.)
+        uint4 w0[U][NB], x0[U][MB], w1[U][NB], x1[U][MB];
+        const int n_sets = (kb_hi - kb_lo + U - 1) / U;
+#define GS_LOAD(W_, X_, SET)                                                                              \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
+            const int kk = min(kb_lo + (SET) * U + u, kb_hi - 1);                                             \
+            _Pragma("unroll") for (int j = 0; j < NB; ++j) W_[u][j] = ld_stream(wp[j] + (size_t)kk * wstep);  \
+            _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = xp[i][(size_t)kk * XSTEP];              \
+        }
+#define GS_MUL(W_, X_, SET)                                                                               \
+        if (XROWS) {   /* row pieces -> fragment order through the wavefront's own LDS */                     \
+            _Pragma("unroll") for (int u = 0; u < U; ++u)                                                     \
+                _Pragma("unroll") for (int i = 0; i < MB; ++i) stage[(u * MB + i) * 64 + st_wr] = X_[u][i];   \
+            _Pragma("unroll") for (int u = 0; u < U; ++u)                                                     \
+                _Pragma("unroll") for (int i = 0; i < MB; ++i) X_[u][i] = stage[(u * MB + i) * 64 + st_rd];   \
+        }                                                                                                     \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                       \
+            if (kb_lo + (SET) * U + u < kb_hi) {                                                              \
+                _Pragma("unroll") for (int j = 0; j < NB; ++j)                                                 \
+                    _Pragma("unroll") for (int i = 0; i < MB; ++i) acc[j][i] = gs_mfma(W_[u][j], X_[u][i], acc[j][i]); \
+                if (EPI == GS_SWIGLU || EPI == GS_QKV_DECODE || norm) {                                       \
+                    _Pragma("unroll") for (int i = 0; i < MB; ++i) sq[i] = gs_mfma(X_[u][i], X_[u][i], sq[i]); \
+                }                                                                                             \
+            }                                                                                                 \
+        }
+        if (n_sets > 0) {
+            GS_LOAD(w0, x0, 0);
+            GS_LOAD(w1, x1, 1);
+            for (int s = 0; s < n_sets; s += 2) {
+                GS_MUL(w0, x0, s);
+                GS_LOAD(w0, x0, s + 2);
+                GS_MUL(w1, x1, s + 1);
+                GS_LOAD(w1, x1, s + 3);
+            }
+        }
 #undef GS_LOAD
 #undef GS_MUL
 
-    if (XROWS) __syncthreads();   // (kept apart from the staging areas anyway; the wavefronts meet here before the epilogue)
-    // In-workgroup reduction through kGsWaves / 2 LDS buffers of row-major [row][NB * 16 columns]
-    // tiles: the upper half of the wavefronts write their accumulators, the lower half add them to
-    // their own (w + (w + kGsWaves / 2)) and write the sums; then every thread adds the buffers in
-    // index order for the outputs it stores.
-    constexpr int HALF = kGsWaves / 2;
-    float *wssq = red + HALF * BUF;         // [wavefronts][MB * 16 rows]
-    float *rsv = wssq + kGsWaves * MB * 16; // [MB * 16]: rsqrt(mean square + eps) per row
-    float *slot = red + (wave % HALF) * BUF + (lane & 15) * ROWF + (lane >> 4) * 4;   // + i * 16 * ROWF + j * 16
-    if (wave >= HALF) {
+        if (XROWS) __syncthreads();   // (kept apart from the staging areas anyway; the wavefronts meet here before the epilogue)
+        // In-workgroup reduction through kGsWaves / 2 LDS buffers of row-major [row][NB * 16 columns]
+        // tiles: the upper half of the wavefronts write their accumulators, the lower half add them to
+        // their own (w + (w + kGsWaves / 2)) and write the sums; then every thread adds the buffers in
+        // index order for the outputs it stores.
+        float *slot = red + (wave % HALF) * BUF + (lane & 15) * ROWF + (lane >> 4) * 4;   // + i * 16 * ROWF + j * 16
+        if (wave >= HALF) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
+            for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
-                *(float4 *)(slot + i * 16 * ROWF + j * 16) = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
-    }
-    {
-        // a row's sum of squares over this wavefront's part of K: element (m, m) of X X^T, which lane
-        // m + 16 * (m / 4) holds in register m % 4; the wavefronts are added in index order below
-        const int m16 = lane & 15;
-        if ((lane >> 4) == (m16 >> 2)) {
+                for (int i = 0; i < MB; ++i)
+                    *(float4 *)(slot + i * 16 * ROWF + j * 16) = make_float4(acc[j][i][0], acc[j][i][1], acc[j][i][2], acc[j][i][3]);
+        }
+        {
+            // a row's sum of squares over this wavefront's part of K: element (m, m) of X X^T, which lane
+            // m + 16 * (m / 4) holds in register m % 4; the wavefronts are added in index order below
+            const int m16 = lane & 15;
+            if ((lane >> 4) == (m16 >> 2)) {
 #pragma unroll
-            for (int i = 0; i < MB; ++i) {
-                const float s = (m16 & 3) == 0 ? sq[i][0] : (m16 & 3) == 1 ? sq[i][1] : (m16 & 3) == 2 ? sq[i][2] : sq[i][3];
-                wssq[wave * (MB * 16) + i * 16 + m16] = s;
+                for (int i = 0; i < MB; ++i) {
+                    const float s = (m16 & 3) == 0 ? sq[i][0] : (m16 & 3) == 1 ? sq[i][1] : (m16 & 3) == 2 ? sq[i][2] : sq[i][3];
+                    wssq[wave * (MB * 16) + i * 16 + m16] = s;
+                }
             }
         }
-    }
-    __syncthreads();
-    if (wave < HALF) {
+        __syncthreads();
+        if (wave < HALF) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
+            for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int i = 0; i < MB; ++i) {
-                float4 *p = (float4 *)(slot + i * 16 * ROWF + j * 16);
-                const float4 t = *p;
-                *p = make_float4(acc[j][i][0] + t.x, acc[j][i][1] + t.y, acc[j][i][2] + t.z, acc[j][i][3] + t.w);
-            }
+                for (int i = 0; i < MB; ++i) {
+                    float4 *p = (float4 *)(slot + i * 16 * ROWF + j * 16);
+                    const float4 t = *p;
+                    *p = make_float4(acc[j][i][0] + t.x, acc[j][i][1] + t.y, acc[j][i][2] + t.z, acc[j][i][3] + t.w);
+                }
+        }
     }
     if (threadIdx.x < MB * 16) {
         const int m = threadIdx.x;
@@ -237,7 +329,7 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
     }
     __syncthreads();
     constexpr int QUADS = MB * 16 * (NB * 4);   // float4 outputs of the tile
-    constexpr int NBUF = SPLIT ? 1 : HALF;      // buffers `fetch` adds
+    constexpr int NBUF = SPLIT ? 1 : NRB;       // buffers `fetch` adds
     if (SPLIT) {
         // K is cut over a.nseg workgroups per tile.  Every workgroup publishes its partial tile and
         // its part of the rows' sums of squares with device-coherent (write-through) stores, waits
@@ -253,7 +345,7 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
             const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
             float4 v = *(const float4 *)(red + m * ROWF + c);
 #pragma unroll
-            for (int w = 1; w < HALF; ++w) {
+            for (int w = 1; w < NRB; ++w) {
                 const float4 t = *(const float4 *)(red + w * BUF + m * ROWF + c);
                 v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
             }
@@ -333,7 +425,7 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
         for (int q = threadIdx.x; q < QUADS; q += kGsWaves * 64) {
             const int m = q / (NB * 4), c = (q % (NB * 4)) * 4;
             const int n = blk0 * 16 + c;
-            if (m >= a.M || n >= a.N) continue;
+            if (m >= a.M || n >= a.N || c >= nbt * 16) continue;
             float4 v = fetch(m, c);
             if (a.res) {
                 const uint2 r = *(const uint2 *)(a.res + (size_t)m * a.N + n);
@@ -347,7 +439,7 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
         for (int q = threadIdx.x; q < QUADS / 2; q += kGsWaves * 64) {
             const int m = q / (NB * 2), pr = (q % (NB * 2)) / 4, c4 = (q % 4) * 4;
             const int col = (blk0 / 2 + pr) * 16 + c4;   // column of u
-            if (m >= a.M || col >= a.N / 2) continue;
+            if (m >= a.M || col >= a.N / 2 || pr * 2 >= nbt) continue;
             const float4 g = fetch(m, pr * 32 + c4), u = fetch(m, pr * 32 + 16 + c4);
             const float o0 = g.x / (1.0f + __expf(-g.x)) * u.x, o1 = g.y / (1.0f + __expf(-g.y)) * u.y;
             const float o2 = g.z / (1.0f + __expf(-g.z)) * u.z, o3 = g.w / (1.0f + __expf(-g.w)) * u.w;
@@ -418,17 +510,21 @@ __device__ __forceinline__ void gs_pass(const GsArgs &a, float *red, const int b
 // The kernel: workgroup b works on column tile b % ntiles and K segment b / ntiles.  With NB2 > 0 a
 // tile is NB + NB2 blocks wide and is done in two passes (NB blocks, then NB2), which lets a launch
 // give every compute unit the same number of blocks when that number is too large for one pass's registers.
-template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int NB2, int SPLIT>
+template <int MB, int NB, int EPI, int kGsWaves, int U, int XROWS, int NB2, int SPLIT, int COLS>
 __global__ __launch_bounds__(kGsWaves * 64, (MB * NB <= 8 && kGsWaves == 4) ? 2 : 1) void gemm_stream_kernel(const GsArgs a)
 {
     extern __shared__ float red[];
     const int tile = blockIdx.x % a.ntiles, seg = blockIdx.x / a.ntiles;
-    gs_pass<MB, NB, EPI, kGsWaves, U, XROWS, SPLIT>(a, red, tile * (NB + NB2), tile, seg);
-    if (NB2 > 0) {
-        constexpr int NBB = NB2 > 0 ? NB2 : 1;
-        if ((tile * (NB + NB2) + NB) * 16 < a.N) {   // the same for the whole workgroup
-            __syncthreads();
-            gs_pass<MB, NBB, EPI, kGsWaves, gs_u(MB, NBB), XROWS, 0>(a, red, tile * (NB + NB2) + NB, tile, seg);
+    if constexpr (COLS) {
+        gs_pass<MB, NB, EPI, kGsWaves, U, XROWS, SPLIT, 1>(a, red, tile * a.nbt, tile, seg);
+    } else {
+        gs_pass<MB, NB, EPI, kGsWaves, U, XROWS, SPLIT>(a, red, tile * (NB + NB2), tile, seg);
+        if (NB2 > 0) {
+            constexpr int NBB = NB2 > 0 ? NB2 : 1;
+            if ((tile * (NB + NB2) + NB) * 16 < a.N) {   // the same for the whole workgroup
+                __syncthreads();
+                gs_pass<MB, NBB, EPI, kGsWaves, gs_u(MB, NBB), XROWS, 0>(a, red, tile * (NB + NB2) + NB, tile, seg);
+            }
         }
     }
 }
@@ -443,6 +539,9 @@ constexpr int gs_lds_bytes2(int MB, int NB, int NB2, int W, int XROWS)
     const int b = NB2 > 0 ? gs_lds_bytes(MB, NB2, W, gs_u(MB, NB2), XROWS) : 0;
     return a > b ? a : b;
 }
+// column-split form: one tile buffer, two stages of U k-steps of all MB row blocks
+constexpr int kGsColsU = 4;   // k-steps per set: 16 KiB of weights per wavefront and set with 16-block tiles
+constexpr int gs_lds_bytes_cols(int MB, int NB, int W) { return gs_red_floats(MB, NB, W, 1) * (int)sizeof(float) + 2 * kGsColsU * MB * 1024; }
 
 // wavefronts per workgroup of every instantiation (eight were measured: never faster)
 constexpr int kGsW = 4;
@@ -450,9 +549,24 @@ constexpr int kGsW = 4;
 template <int MB, int NB, int EPI, int XROWS, int NB2 = 0, int SPLIT = 0>
 hipError_t gs_launch(int grid, const GsArgs &a, hipStream_t st)
 {
-    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2, SPLIT>), dim3(grid), dim3(kGsW * 64),
+    hipLaunchKernelGGL((gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2, SPLIT, 0>), dim3(grid), dim3(kGsW * 64),
                        gs_lds_bytes2(MB, NB, NB2, kGsW, XROWS), st, a);
     return hipGetLastError();
+}
+
+// column-split form (64-row launches with wide tiles)
+template <int NB, int EPI, int SPLIT>
+hipError_t gs_launch_cols(int grid, const GsArgs &a, hipStream_t st)
+{
+    hipLaunchKernelGGL((gemm_stream_kernel<4, NB, EPI, kGsW, kGsColsU, 0, 0, SPLIT, 1>), dim3(grid), dim3(kGsW * 64),
+                       gs_lds_bytes_cols(4, NB, kGsW), st, a);
+    return hipGetLastError();
+}
+template <int NB, int EPI, int SPLIT>
+hipError_t gs_attr_cols()
+{
+    return hipFuncSetAttribute((const void *)gemm_stream_kernel<4, NB, EPI, kGsW, kGsColsU, 0, 0, SPLIT, 1>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, gs_lds_bytes_cols(4, NB, kGsW));
 }
 
 template <int NB, int EPI, int XROWS, int NB2 = 0, int SPLIT = 0>
@@ -467,7 +581,7 @@ hipError_t gs_launch_mb(int grid, const GsArgs &a, hipStream_t st)
 template <int MB, int NB, int EPI, int XROWS, int NB2, int SPLIT>
 hipError_t gs_attr()
 {
-    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2, SPLIT>,
+    return hipFuncSetAttribute((const void *)gemm_stream_kernel<MB, NB, EPI, kGsW, gs_u(MB, NB), XROWS, NB2, SPLIT, 0>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, gs_lds_bytes2(MB, NB, NB2, kGsW, XROWS));
 }
 template <int NB, int EPI, int NB2 = 0, int SPLIT = 0>
@@ -589,14 +703,30 @@ hipError_t launch_gemm_stream_store(const void *Wp, StoreShape sh, const void *X
 #undef CCS_GS
 }
 
+// gate/up takes the column-split form when the FULL batch has 33..64 rows, the activations are packed and a
+// workgroup gets five to eight (gate, up) pairs
+static bool stream_gu_cols(int N2, long variant_rows, bool x_rows)
+{
+    const int per_wg = (N2 / 32 + 255) / 256;
+    return variant_rows > 32 && !x_rows && per_wg >= 5 && per_wg <= 8;
+}
+
 hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *X, bool x_rows, float eps, void *u_packed, int M, int N2,
-                                     int K, hipStream_t st)
+                                     int K, long variant_rows, hipStream_t st)
 {
     if (M <= 0) return hipSuccess;
     if (M > kSkinnyMaxRows || (K & 31) || (N2 & 31)) return hipErrorInvalidValue;
     GsArgs a{};
     a.Wp = (const uint4 *)Wp; a.kfrags = K / 32; a.G = kWGroup; a.X = (const uint4 *)X; a.norm = 1; a.eps = eps;
     a.M = M; a.N = N2; a.out = (bf16_t *)u_packed;
+    const int pairs = N2 / 32, per_wg = (pairs + 255) / 256;
+    if (stream_gu_cols(N2, variant_rows, x_rows)) {
+        // 33..64 rows in the full batch: one pass over all of a workgroup's pairs in the column-split form (two passes
+        // would fetch the activations twice)
+        a.nbt = 2 * per_wg;
+        a.ntiles = (pairs + per_wg - 1) / per_wg; a.kf_seg = a.kfrags;
+        return gs_launch_cols<16, GS_SWIGLU, 0>(a.ntiles, a, st);
+    }
     int nb1, nb2;
     stream_gu_shape(N2, &nb1, &nb2);
     const int tiles = ((N2 / 16) + nb1 + nb2 - 1) / (nb1 + nb2);
@@ -689,6 +819,7 @@ hipError_t init_gemm_stream_kernels()
     if (e == hipSuccess) e = gs_attr_mb<8, GS_QKV_DECODE>();
     if (e == hipSuccess) e = gs_attr_mb<4, GS_QKV_DECODE>();
     if (e == hipSuccess) e = gs_attr_mb<3, GS_QKV_DECODE>();
+    if (e == hipSuccess) e = gs_attr_cols<16, GS_SWIGLU, 0>();
     return e;
 }
 

@@ -125,7 +125,7 @@ hipError_t launch_gemm_stream_store(const void *Wp, StoreShape sh, const void *X
 // u = silu(gate) * up of RMSNorm(x), fragment-packed [M16, N2 / 2]; weight [N2, K] with gate / up
 // interleaved in 16-row blocks; x raw.
 hipError_t launch_gemm_stream_swiglu(const void *Wp, const void *X, bool x_rows, float eps, void *u_packed, int M, int N2,
-                                     int K, hipStream_t st);
+                                     int K, long variant_rows, hipStream_t st);
 // Decode Q/K/V projection (head_dim 128, weight [Wq; Wk; Wv]: one head = one weight group) of
 // RMSNorm(x), x raw, and behind it the rotary embedding at position lens[m], the q store into the
 // row-major qkv buffer [M, (nq + 2 nkv) * 128] and the append of the rotated key and the value at

@@ -520,8 +520,8 @@ int forward_one(ccs_module *m, int r, const ccs_batch *b, long long variant_rows
                 CCS_STAGE(CCS_ST_GEMM_O, launch_gemm_stream_store(A + m->ap.o, stream_store_shape(d.H, d.QD, (long)variant_rows), ws + p.a, false, false, 0.f, x_in, x1_out, ffn ? ws + p.x1p : nullptr, T, d.H, d.QD, scratch, (int *)(ws + p.cnt), st));
             }
             if (ffn) {
-                if (attn) CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, ws + p.x1p, false, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
-                else CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, x_in, true, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, st));
+                if (attn) CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, ws + p.x1p, false, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, (long)variant_rows, st));
+                else CCS_STAGE(CCS_ST_GEMM_GU, launch_gemm_stream_swiglu(A + m->ap.gu, x_in, true, D.rms_eps, ws + p.u, T, 2 * d.I, d.H, (long)variant_rows, st));
                 void *next_xp = last ? nullptr : (void *)(ws + p.xp);   // inside a run: the next layer's packed input rows
                 if (store_split(d.I, variant_rows)) {
                     CCS_STAGE(CCS_ST_GEMM_DOWN, launch_gemm_stream_partials(A + m->ap.dn, ws + p.u, false, false, scratch, nullptr, T, d.H, d.I, st));

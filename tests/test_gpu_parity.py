@@ -253,6 +253,22 @@ def test_bf16_gate_up_tile_shapes_of_the_weight_streaming_launch():
         run_case(workloads.scaled(ffn, n_seqs=64), [1, 3], seed=401 + inter % 97)
 
 
+def test_bf16_column_split_form_of_the_streaming_launch_at_33_to_64_rows():
+    """33..64 rows: gate/up with five to eight (gate, up) pairs per workgroup runs in the form whose
+    wavefronts split the tile's columns and share the activations through LDS (one pass over up to 16
+    blocks); the replica slices of 20 and 32 rows run the same form.  And a wide O projection at the
+    same row counts (K cut over workgroups inside the launch)."""
+    for inter in (16640, 24576, 28672, 32768):          # 5, 6, 7, 8 pairs per workgroup
+        for n in (40, 64):
+            cfg = workloads.scaled(C["C2"], hidden=256, n_q_heads=2, n_kv_heads=2, intermediate=inter, n_seqs=n,
+                                   len_lo=0, len_hi=40)
+            run_case(cfg, [1, 2], seed=600 + inter % 89 + n)
+    for n in (40, 64):
+        cfg = workloads.scaled(C["C2"], kind="attn_block", hidden=6144, n_q_heads=20, n_kv_heads=20, intermediate=512,
+                               n_seqs=n, len_lo=0, len_hi=60)
+        run_case(cfg, [1, 2], seed=650 + n)
+
+
 def test_bf16_decode_qkv_tile_shapes_with_many_heads():
     """The decode Q/K/V launch picks whole-head tiles for 144 grouped-query head slots and
     pair + v-block tiles (two rounds of them) for 64 + 64 + 64 multi-head slots."""

@@ -147,6 +147,9 @@ size_t ccs_module_workspace_bytes(const ccs_module_desc *desc, int32_t max_seqs,
  * max(1, n_layers) structs holding device pointers) into
  * `arena0` (device, >= ccs_module_arena_bytes, 256-byte aligned) on `stream`, and remembers
  * `workspace0` (device, workspace_bytes long, 256-byte aligned) and `stream` as replica 0's.
+ * A workspace belongs to its replica from here on: the call clears its first KiB on `stream`
+ * (arrival counters that the replica's launches use and leave at zero); the caller must not
+ * write to it, nor hand it to another replica or module, while the replica exists.
  * The caller's weight buffers may be released after the stream has been synchronised.
  * Errors: CCS_EINVAL (null/misaligned pointers, bad desc), CCS_EUNSUPPORTED, CCS_EHIP. */
 int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *weights, void *arena0,
@@ -155,8 +158,9 @@ int ccs_module_create(const ccs_module_desc *desc, const ccs_weights *weights, v
 /* Set the number of instances to k (1 <= k <= CCS_MAX_REPLICAS).  For every replica j that
  * does not exist yet, arenas[j], workspaces[j] (device) and streams[j] are taken over and the
  * weights of replica 0 are cloned into arenas[j] by a streaming HBM->HBM copy enqueued on
- * streams[j] (after replica 0's pending pack/clone); replica j's forwards are ordered after
- * its clone.  Entries of existing replicas (j < current k, including 0) are ignored and may
+ * streams[j] (after replica 0's pending pack/clone), and the first KiB of workspaces[j] is
+ * cleared there as ccs_module_create does for replica 0's; replica j's forwards are ordered
+ * after both.  Entries of existing replicas (j < current k, including 0) are ignored and may
  * be null.  Shrinking (k below the current count) waits for the dropped replicas' work and
  * forgets them; their buffers go back to the caller.  Section 3.1 "Replication".
  * Errors: CCS_EINVAL, CCS_EHIP. */
